@@ -1,0 +1,252 @@
+"""Python face of the CPU oracle (oz2_oracle.c + constants.py).
+
+TEST INFRASTRUCTURE ONLY: importable from tests/, __graft_entry__.smoke() and
+bench.py's cpu_baseline leg; never from the product path.  Nothing here touches
+the GPU or the HIP library.
+
+Each function wraps one stage of Algorithm 1 of the paper and only marshals
+numpy arrays into the C routine that does the arithmetic; `gemm` chains the
+stages in the order of Algorithm 1 and returns every intermediate, so that a
+test can compare stage by stage.  FP32 inputs (SGEMM emulation) are widened to
+FP64 before the integer stages; the widening is exact, so the scale shifts,
+truncated integers and residues are those of the FP32 data.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+
+from . import constants as K
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oz2_oracle.c")
+_LIB = os.path.join(_HERE, "liboz2_oracle.so")
+_lib = None
+
+BUILD_CMD = ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-Wall", "-shared",
+             "-fPIC", _SRC, "-o", _LIB, "-lm"]
+
+
+def build(force: bool = False) -> str:
+    """Compile oz2_oracle.c (always when force, else only if not built yet)."""
+    global _lib
+    if force or not os.path.exists(_LIB):
+        subprocess.check_call(BUILD_CMD)
+        _lib = None
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _i64(x) -> C.c_int64:
+    return C.c_int64(int(x))
+
+
+def num_threads() -> int:
+    """Threads the C routines will use (OpenMP default)."""
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        return int(env.split(",")[0])
+    return len(os.sched_getaffinity(0))
+
+
+def _strides(X: np.ndarray, axis: int):
+    """axis=0: one vector per row of X; axis=1: one vector per column."""
+    assert X.ndim == 2 and X.dtype == np.float64 and X.flags.c_contiguous
+    rows, cols = X.shape
+    if axis == 0:
+        return rows, cols, cols, 1
+    return cols, rows, 1, cols
+
+
+def shifts(X: np.ndarray, axis: int, Pfast: float):
+    """Algorithm 1 line 1 (fast mode).  Returns (t, e, T) per vector."""
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    nv, ln, sv, sh = _strides(X, axis)
+    t = np.zeros(nv, np.int32)
+    e = np.zeros(nv, np.int32)
+    T = np.zeros(nv, np.float64)
+    _load().oz2o_shifts(_p(X), _i64(nv), _i64(ln), _i64(sv), _i64(sh),
+                        C.c_double(Pfast), _p(t), _p(e), _p(T))
+    return t, e, T
+
+
+def residues(X: np.ndarray, axis: int, t: np.ndarray, p: Sequence[int]) -> np.ndarray:
+    """Algorithm 1 lines 2-5.  Returns int8 [N][nv][len] (vector-major)."""
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    nv, ln, sv, sh = _strides(X, axis)
+    t = np.ascontiguousarray(t, dtype=np.int32)
+    pa = np.asarray(p, dtype=np.int32)
+    out = np.empty((len(pa), nv, ln), np.int8)
+    _load().oz2o_residues(_p(X), _i64(nv), _i64(ln), _i64(sv), _i64(sh),
+                          _p(t), _p(pa), C.c_int(len(pa)), _p(out))
+    return out
+
+
+def int8_gemm_rows(Ares: np.ndarray, Bres: np.ndarray, rows: np.ndarray) -> np.ndarray:
+    """Algorithm 1 line 6 for the listed rows.  Returns int32 [N][len(rows)][n]."""
+    N, m, k = Ares.shape
+    N2, n, k2 = Bres.shape
+    assert N == N2 and k == k2
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    assert rows.size == 0 or (rows.min() >= 0 and rows.max() < m)
+    out = np.empty((N, rows.size, n), np.int32)
+    _load().oz2o_int8_gemm_rows(_p(Ares), _p(Bres), C.c_int(N), _i64(m), _i64(n),
+                                _i64(k), _p(rows), _i64(rows.size), _p(out))
+    return out
+
+
+def int8_gemm_entries(Ares, Bres, ii, jj) -> np.ndarray:
+    """Algorithm 1 line 6 for scattered entries.  Returns int32 [N][count]."""
+    N, m, k = Ares.shape
+    _, n, _ = Bres.shape
+    ii = np.ascontiguousarray(ii, dtype=np.int64)
+    jj = np.ascontiguousarray(jj, dtype=np.int64)
+    assert ii.shape == jj.shape
+    out = np.empty((N, ii.size), np.int32)
+    _load().oz2o_int8_gemm_entries(_p(Ares), _p(Bres), C.c_int(N), _i64(m), _i64(n),
+                                   _i64(k), _p(ii), _p(jj), _i64(ii.size), _p(out))
+    return out
+
+
+def mod_reduce(prod: np.ndarray, p: Sequence[int]) -> np.ndarray:
+    """Algorithm 1 line 7.  prod is int32 [N][...]; returns uint8 of same shape."""
+    prod = np.ascontiguousarray(prod, dtype=np.int32)
+    N = prod.shape[0]
+    count = prod.size // N
+    pa = np.asarray(p, dtype=np.int32)
+    U = np.empty(prod.shape, np.uint8)
+    _load().oz2o_mod_reduce(_p(prod), C.c_int(N), _i64(count), _p(pa), _p(U))
+    return U
+
+
+def crt_fold(U: np.ndarray, c: K.Constants) -> np.ndarray:
+    """Algorithm 1 lines 8-11.  U is uint8 [N][...]; returns C'' (float64)."""
+    U = np.ascontiguousarray(U, dtype=np.uint8)
+    N = U.shape[0]
+    count = U.size // N
+    s1 = np.asarray(c.s1, np.float64)
+    s2 = np.asarray(c.s2, np.float64)
+    out = np.empty(U.shape[1:], np.float64)
+    _load().oz2o_crt_fold(_p(U), C.c_int(N), _i64(count), _p(s1), _p(s2),
+                          C.c_double(c.P1), C.c_double(c.P2), C.c_double(c.Pinv),
+                          _p(out))
+    return out
+
+
+def unscale_rows(Cpp, tA_rows, tB, alpha=1.0, beta=0.0, Cin=None) -> np.ndarray:
+    """Algorithm 1 line 12 + alpha/beta for [nrows][n] blocks."""
+    Cpp = np.ascontiguousarray(Cpp, np.float64)
+    nrows, n = Cpp.shape
+    tA_rows = np.ascontiguousarray(tA_rows, np.int32)
+    tB = np.ascontiguousarray(tB, np.int32)
+    out = np.empty_like(Cpp)
+    cin = None
+    if beta != 0.0:
+        cin = np.ascontiguousarray(Cin, np.float64)
+        assert cin.shape == Cpp.shape
+    _load().oz2o_unscale_rows(_p(Cpp), _p(tA_rows), _p(tB), _i64(nrows), _i64(n),
+                              C.c_double(alpha), C.c_double(beta),
+                              _p(cin) if cin is not None else None, _p(out))
+    return out
+
+
+def unscale_entries(Cpp, tsum, alpha=1.0, beta=0.0, Cin=None) -> np.ndarray:
+    Cpp = np.ascontiguousarray(Cpp, np.float64).ravel()
+    tsum = np.ascontiguousarray(tsum, np.int32).ravel()
+    out = np.empty_like(Cpp)
+    cin = None
+    if beta != 0.0:
+        cin = np.ascontiguousarray(Cin, np.float64).ravel()
+    _load().oz2o_unscale_entries(_p(Cpp), _p(tsum), _i64(Cpp.size),
+                                 C.c_double(alpha), C.c_double(beta),
+                                 _p(cin) if cin is not None else None, _p(out))
+    return out
+
+
+def round_to_f32(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, np.float64)
+    out = np.empty(x.shape, np.float32)
+    _load().oz2o_round_to_f32(_p(x), _i64(x.size), _p(out))
+    return out
+
+
+def dd_rows(A: np.ndarray, B: np.ndarray, rows: np.ndarray):
+    """Rows of A@B in double-double, and of |A|@|B|: (hi, lo, absprod)."""
+    A = np.ascontiguousarray(A, np.float64)
+    B = np.ascontiguousarray(B, np.float64)
+    m, k = A.shape
+    k2, n = B.shape
+    assert k == k2
+    rows = np.ascontiguousarray(rows, np.int64)
+    hi = np.empty((rows.size, n), np.float64)
+    lo = np.empty_like(hi)
+    ab = np.empty_like(hi)
+    _load().oz2o_dd_rows(_p(A), _i64(k), _p(B), _i64(n), _i64(n), _i64(k),
+                         _p(rows), _i64(rows.size), _p(hi), _p(lo), _p(ab))
+    return hi, lo, ab
+
+
+def prepare(A: np.ndarray, B: np.ndarray, num_moduli: int, is_double: bool = True) -> Dict:
+    """Algorithm 1 lines 1-5 on the whole of A and B."""
+    c = K.constants(num_moduli, is_double)
+    A64 = np.ascontiguousarray(A, dtype=np.float64)
+    B64 = np.ascontiguousarray(B, dtype=np.float64)
+    tA, eA, TA = shifts(A64, 0, c.Pfast)
+    tB, eB, TB = shifts(B64, 1, c.Pfast)
+    Ares = residues(A64, 0, tA, c.p)
+    Bres = residues(B64, 1, tB, c.p)
+    return dict(consts=c, tA=tA, tB=tB, eA=eA, eB=eB, TA=TA, TB=TB, Ares=Ares, Bres=Bres)
+
+
+def finish_rows(prep: Dict, rows: np.ndarray, alpha=1.0, beta=0.0,
+                Cin_rows: Optional[np.ndarray] = None) -> Dict:
+    """Algorithm 1 lines 6-12 for the listed rows of C."""
+    c = prep["consts"]
+    rows = np.ascontiguousarray(rows, np.int64)
+    prod = int8_gemm_rows(prep["Ares"], prep["Bres"], rows)
+    U = mod_reduce(prod, c.p)
+    Cpp = crt_fold(U, c)
+    cin = None if Cin_rows is None else np.asarray(Cin_rows, np.float64)
+    C64 = unscale_rows(Cpp, prep["tA"][rows], prep["tB"], float(alpha), float(beta), cin)
+    out = C64 if c.is_double else round_to_f32(C64)
+    return dict(prod=prod, U=U, Cpp=Cpp, C=out)
+
+
+def finish_entries(prep: Dict, ii, jj, alpha=1.0, beta=0.0, Cin=None) -> Dict:
+    """Algorithm 1 lines 6-12 for scattered entries (ii[c], jj[c]) of C."""
+    c = prep["consts"]
+    ii = np.asarray(ii, np.int64)
+    jj = np.asarray(jj, np.int64)
+    prod = int8_gemm_entries(prep["Ares"], prep["Bres"], ii, jj)
+    U = mod_reduce(prod, c.p)
+    Cpp = crt_fold(U, c)
+    tsum = prep["tA"][ii] + prep["tB"][jj]
+    cin = None if Cin is None else np.asarray(Cin, np.float64)
+    C64 = unscale_entries(Cpp, tsum, float(alpha), float(beta), cin)
+    out = C64 if c.is_double else round_to_f32(C64)
+    return dict(prod=prod, U=U, Cpp=Cpp, C=out)
+
+
+def gemm(A: np.ndarray, B: np.ndarray, num_moduli: int, alpha=1.0, beta=0.0,
+         Cin: Optional[np.ndarray] = None, is_double: bool = True) -> Dict:
+    """The whole of Algorithm 1; returns every stage."""
+    prep = prepare(A, B, num_moduli, is_double)
+    rows = np.arange(np.asarray(A).shape[0], dtype=np.int64)
+    fin = finish_rows(prep, rows, alpha, beta, Cin)
+    prep.update(fin)
+    return prep
