@@ -1,0 +1,147 @@
+/*
+ * oz2 -- DGEMM / SGEMM emulation on the INT8 matrix cores of AMD MI355X
+ * (gfx950) by Ozaki scheme II: the Chinese Remainder Theorem over N pairwise
+ * coprime moduli <= 256, N INT8 GEMMs with exact INT32 accumulation and an
+ * FP64 reconstruction (Sections 3 and 4 and Algorithm 1 of the paper "High-
+ * Performance and Power-Efficient Emulation of Matrix Multiplication using
+ * INT8 Matrix Engines", Uchino, Ozaki, Imamura, SC'25).
+ *
+ * C ABI.  Conventions shared by every entry point:
+ *   - matrices are ROW-MAJOR and not transposed; a column-major caller obtains
+ *     C = A*B by passing (B, A) and (n, m), since C^T = B^T A^T;
+ *   - pointers named A, B, C, dev_* are DEVICE pointers owned by the caller;
+ *     A and B are only read; host pointers are marked "host";
+ *   - calls are asynchronous on `stream`; the returned status reports argument
+ *     and launch errors only.  One call may be in flight per process at a time
+ *     (the workspace is shared);
+ *   - inputs must be finite.  Inf/NaN inputs give an unspecified (but memory
+ *     safe) result: the paper does not define them;
+ *   - no entry point throws; none synchronises the device except oz2_release,
+ *     oz2_set_workspace and oz2_last_stage_times_ms.
+ */
+#ifndef OZ2_H
+#define OZ2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ihipStream_t *hipStream_t;   /* same declaration as the HIP runtime's */
+
+typedef enum {
+    OZ2_OK = 0,
+    OZ2_INVALID_ARG = 1,   /* null pointer, negative size, leading dimension too small  */
+    OZ2_UNSUPPORTED = 2,   /* num_moduli outside 2..20, or k > 2^17                      */
+    OZ2_WORKSPACE = 3,     /* caller-provided workspace too small / allocation failed    */
+    OZ2_HIP_ERROR = 4      /* a HIP runtime call or a kernel launch failed               */
+} oz2_status;
+
+#define OZ2_MIN_MODULI 2
+#define OZ2_MAX_MODULI 20           /* Section 4.1: the table is kept to N <= 20        */
+#define OZ2_MAX_K (1 << 17)         /* Section 4.3: INT32 accumulation is exact up to it */
+
+/*
+ * C <- alpha * (A*B) + beta * C,  A: m x k (lda >= k), B: k x n (ldb >= n),
+ * C: m x n (ldc >= n), with A*B evaluated by Algorithm 1 in fast mode
+ * (Section 4.2) with `num_moduli` moduli: power-of-two row scaling of A and
+ * column scaling of B, truncation, residues modulo the first num_moduli members
+ * of the modulus set of Section 4.1 as INT8, num_moduli INT8 GEMMs accumulated
+ * in INT32, reduction modulo p_s, CRT accumulation and fold in FP64
+ * (Section 4.3) and inverse scaling.  More moduli give more accuracy: 14-17
+ * reach native FP64 level for well-scaled data, 7-9 reach FP32 level (Section 5.1).
+ *
+ * alpha, beta are host values.  beta == 0: C is not read (NaNs in it do not
+ * propagate).  m == 0 or n == 0: nothing is done.  k == 0: C <- beta * C.
+ * k > OZ2_MAX_K returns OZ2_UNSUPPORTED.
+ * oz2_sgemm takes FP32 data; its reconstruction still runs in FP64 and the
+ * result is rounded to FP32 once.
+ */
+oz2_status oz2_dgemm(int64_t m, int64_t n, int64_t k, double alpha,
+                     const double *A, int64_t lda, const double *B, int64_t ldb,
+                     double beta, double *C, int64_t ldc, int num_moduli,
+                     hipStream_t stream);
+
+oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha,
+                     const float *A, int64_t lda, const float *B, int64_t ldb,
+                     float beta, float *C, int64_t ldc, int num_moduli,
+                     hipStream_t stream);
+
+/*
+ * Workspace.  A call needs device scratch for the transposed copy of B, the
+ * shift vectors, the INT8 residue slices of A and B (Algorithm 1 lines 4-5)
+ * and the INT32 products (line 6): oz2_workspace_bytes gives the size for a
+ * problem (0 if the arguments are unsupported).  oz2_set_workspace hands the
+ * library a caller-owned device buffer (kept, not freed, must stay valid until
+ * replaced; 256-byte aligned); with (NULL, 0) the library goes back to
+ * allocating its own buffer with hipMalloc, growing it on demand and keeping
+ * it until oz2_release.  A call whose need exceeds a caller-owned buffer
+ * returns OZ2_WORKSPACE.
+ */
+size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double);
+oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes);
+void oz2_release(void);
+
+/*
+ * Constants of Section 4.1 for `num_moduli` moduli, written to HOST arrays of
+ * at least num_moduli entries (any of them may be NULL):
+ *   p           moduli p_i
+ *   pinv_prime  floor(2^32/p_i - 1), the multiplier of the mulhi reduction (Section 4.3)
+ *   s1, s2      the two-term split of (P/p_i) q_i  (is_double) or double(.) and 0 (single)
+ *   P1P2Pinv    { P1, P2, P_inv }
+ *   Pfast       P'_fast as a binary32 value
+ */
+oz2_status oz2_constants(int num_moduli, int is_double, int32_t *p, uint32_t *pinv_prime,
+                         double *s1, double *s2, double *P1P2Pinv, float *Pfast);
+
+/*
+ * The fast-mode shift of Section 4.2 as the kernels evaluate it.  For a row
+ * (column) with e = floor(log2 max|x|) and the exact integer
+ * T = sum_h ceil(|x_h| 2^(15-e))^2, the scaled row has exponent
+ * f = floor(P'_fast - max(1, 0.51 log2(T 2^-30))) and shift t = f - e.  The
+ * kernels find f by comparing T with a table: f = f_max - min{ j : T <= theta[j] }.
+ * This call writes f_max, the number of levels (<= 16) and theta[] to HOST memory.
+ */
+oz2_status oz2_shift_table(int num_moduli, int32_t *f_max, int32_t *levels, uint64_t *theta);
+
+/*
+ * Diagnostics: where the stages of the most recent oz2_dgemm / oz2_sgemm call
+ * live in the workspace.  dims (host, 4 entries) describes the layout:
+ *   OZ2_STAGE_SHIFT_A  int32 [m]                 dims = { m, 0, 0, 0 }
+ *   OZ2_STAGE_SHIFT_B  int32 [n]                 dims = { n, 0, 0, 0 }
+ *   OZ2_STAGE_RES_A    int8  [N][Mp][Kp]         dims = { N, Mp, Kp, m }   rows >= m, cols >= k are 0
+ *   OZ2_STAGE_RES_B    int8  [N][Np][Kp]         dims = { N, Np, Kp, n }   (B slices are stored transposed)
+ *   OZ2_STAGE_PROD     int32 [N][Mp][Np]         dims = { N, Mp, Np, 0 }
+ * Valid until the next call or workspace change; the caller synchronises.
+ */
+enum { OZ2_STAGE_SHIFT_A = 0, OZ2_STAGE_SHIFT_B = 1, OZ2_STAGE_RES_A = 2,
+       OZ2_STAGE_RES_B = 3, OZ2_STAGE_PROD = 4 };
+oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims);
+
+/*
+ * Diagnostics: the batched INT8 GEMM of Algorithm 1 line 6 on its own.
+ * dev_A: int8 [batch][Mp][Kp], dev_B: int8 [batch][Np][Kp] (both K-contiguous),
+ * dev_C: int32 [batch][Mp][Np];  C_b = A_b * B_b^T with wrapping INT32 sums.
+ * Mp and Np must be multiples of 256, Kp a multiple of 128 (OZ2_INVALID_ARG otherwise).
+ */
+oz2_status oz2_int8_gemm(const int8_t *dev_A, const int8_t *dev_B, int32_t *dev_C,
+                         int batch, int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream);
+
+/*
+ * Per-stage timing.  With profiling on, each call records HIP events around its
+ * stages on the call's stream; oz2_last_stage_times_ms waits for the last call
+ * and writes { scale+exponent, residues, INT8 GEMM, epilogue } in milliseconds
+ * to a HOST array.  Off by default (no events are recorded then).
+ */
+void oz2_set_profiling(int on);
+oz2_status oz2_last_stage_times_ms(float *out4);
+
+/* Static text for a status code. */
+const char *oz2_status_string(oz2_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OZ2_H */

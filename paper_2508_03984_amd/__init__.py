@@ -1,0 +1,13 @@
+"""oz2: DGEMM / SGEMM emulation on MI355X INT8 matrix cores (Ozaki scheme II).
+
+The work is done by liboz2.so (hand-written HIP for gfx950, C ABI in
+include/oz2.h).  This package is the thin binding: the functions of
+`paper_2508_03984_amd.binding` carry the same names as the C entry points and
+only marshal arguments; torch supplies device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    OZ2Error, lib_path, load, oz2_constants, oz2_dgemm, oz2_int8_gemm,
+    oz2_last_stage_times_ms, oz2_release, oz2_set_profiling, oz2_set_workspace,
+    oz2_sgemm, oz2_shift_table, oz2_stage_ptr, oz2_status_string, oz2_workspace_bytes,
+    stage_tensor, matmul,
+)

@@ -1,0 +1,222 @@
+"""ctypes binding of liboz2.so: same names as the C ABI (include/oz2.h),
+argument marshalling only.  Device buffers are torch tensors; the stream is
+torch's current stream unless given.  There is no fallback: if the library has
+not been built, every call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "liboz2.so")
+_lib = None
+
+OZ2_STAGE_SHIFT_A, OZ2_STAGE_SHIFT_B, OZ2_STAGE_RES_A, OZ2_STAGE_RES_B, OZ2_STAGE_PROD = range(5)
+
+EXPORTS = [
+    "oz2_dgemm", "oz2_sgemm", "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
+    "oz2_constants", "oz2_shift_table", "oz2_stage_ptr", "oz2_int8_gemm", "oz2_set_profiling",
+    "oz2_last_stage_times_ms", "oz2_status_string",
+]
+
+
+class OZ2Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {oz2_status_string(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load liboz2.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    try:
+        # torch ships its own HIP runtime under the same soname; importing it first makes the
+        # loader bind liboz2.so to that one, so that streams and pointers are shared.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2508_03984_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    i64, dbl, flt, vp, ci = C.c_int64, C.c_double, C.c_float, C.c_void_p, C.c_int
+    lib.oz2_dgemm.argtypes = [i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, ci, vp]
+    lib.oz2_sgemm.argtypes = [i64, i64, i64, flt, vp, i64, vp, i64, flt, vp, i64, ci, vp]
+    lib.oz2_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
+    lib.oz2_workspace_bytes.restype = C.c_size_t
+    lib.oz2_set_workspace.argtypes = [vp, C.c_size_t]
+    lib.oz2_release.argtypes = []
+    lib.oz2_release.restype = None
+    lib.oz2_constants.argtypes = [ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.oz2_shift_table.argtypes = [ci, vp, vp, vp]
+    lib.oz2_stage_ptr.argtypes = [ci, C.POINTER(vp), C.POINTER(i64)]
+    lib.oz2_int8_gemm.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp]
+    lib.oz2_set_profiling.argtypes = [ci]
+    lib.oz2_set_profiling.restype = None
+    lib.oz2_last_stage_times_ms.argtypes = [C.POINTER(flt)]
+    lib.oz2_status_string.argtypes = [ci]
+    lib.oz2_status_string.restype = C.c_char_p
+    for name in ("oz2_dgemm", "oz2_sgemm", "oz2_set_workspace", "oz2_constants", "oz2_shift_table",
+                 "oz2_stage_ptr", "oz2_int8_gemm", "oz2_last_stage_times_ms"):
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    return C.c_void_p(int(stream))
+
+
+def _dev(t, dtype=None) -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"tensor of dtype {dtype} expected, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise OZ2Error(status, where)
+
+
+def oz2_status_string(status: int) -> str:
+    return load().oz2_status_string(int(status)).decode()
+
+
+def oz2_dgemm(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=None) -> None:
+    import torch
+    _check(load().oz2_dgemm(m, n, k, float(alpha), _dev(A, torch.float64), lda,
+                            _dev(B, torch.float64), ldb, float(beta), _dev(C_, torch.float64), ldc,
+                            int(num_moduli), _stream(stream)), "oz2_dgemm")
+
+
+def oz2_sgemm(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=None) -> None:
+    import torch
+    _check(load().oz2_sgemm(m, n, k, float(alpha), _dev(A, torch.float32), lda,
+                            _dev(B, torch.float32), ldb, float(beta), _dev(C_, torch.float32), ldc,
+                            int(num_moduli), _stream(stream)), "oz2_sgemm")
+
+
+def oz2_workspace_bytes(m, n, k, num_moduli, is_double=True) -> int:
+    return int(load().oz2_workspace_bytes(m, n, k, int(num_moduli), int(bool(is_double))))
+
+
+def oz2_set_workspace(buf) -> None:
+    """buf: a device uint8 tensor the caller keeps alive, or None for library-owned."""
+    if buf is None:
+        _check(load().oz2_set_workspace(C.c_void_p(0), 0), "oz2_set_workspace")
+    else:
+        _check(load().oz2_set_workspace(_dev(buf), buf.numel() * buf.element_size()),
+               "oz2_set_workspace")
+
+
+def oz2_release() -> None:
+    load().oz2_release()
+
+
+def oz2_constants(num_moduli: int, is_double: bool = True) -> dict:
+    import numpy as np
+    n = int(num_moduli)
+    p = np.zeros(20, np.int32); pv = np.zeros(20, np.uint32)
+    s1 = np.zeros(20, np.float64); s2 = np.zeros(20, np.float64)
+    P = np.zeros(3, np.float64); pf = np.zeros(1, np.float32)
+    _check(load().oz2_constants(n, int(bool(is_double)), p.ctypes.data, pv.ctypes.data,
+                                s1.ctypes.data, s2.ctypes.data, P.ctypes.data, pf.ctypes.data),
+           "oz2_constants")
+    return dict(p=p[:n], pinv_prime=pv[:n], s1=s1[:n], s2=s2[:n], P1=float(P[0]), P2=float(P[1]),
+                Pinv=float(P[2]), Pfast=float(pf[0]))
+
+
+def oz2_shift_table(num_moduli: int) -> dict:
+    import numpy as np
+    f = np.zeros(1, np.int32); lv = np.zeros(1, np.int32); th = np.zeros(16, np.uint64)
+    _check(load().oz2_shift_table(int(num_moduli), f.ctypes.data, lv.ctypes.data, th.ctypes.data),
+           "oz2_shift_table")
+    return dict(f_max=int(f[0]), levels=int(lv[0]), theta=th[:int(lv[0])].copy())
+
+
+def oz2_stage_ptr(stage: int) -> Tuple[int, Tuple[int, int, int, int]]:
+    ptr = C.c_void_p(0)
+    dims = (C.c_int64 * 4)()
+    _check(load().oz2_stage_ptr(int(stage), C.byref(ptr), dims), "oz2_stage_ptr")
+    return int(ptr.value or 0), tuple(int(d) for d in dims)
+
+
+def oz2_int8_gemm(A, B, C_, batch, Mp, Np, Kp, stream=None) -> None:
+    import torch
+    _check(load().oz2_int8_gemm(_dev(A, torch.int8), _dev(B, torch.int8), _dev(C_, torch.int32),
+                                int(batch), Mp, Np, Kp, _stream(stream)), "oz2_int8_gemm")
+
+
+def oz2_set_profiling(on: bool) -> None:
+    load().oz2_set_profiling(int(bool(on)))
+
+
+def oz2_last_stage_times_ms():
+    out = (C.c_float * 4)()
+    _check(load().oz2_last_stage_times_ms(out), "oz2_last_stage_times_ms")
+    return [float(x) for x in out]
+
+
+# ------------------------------------------------------------------ conveniences (no arithmetic)
+def stage_tensor(stage: int, copy: bool = True):
+    """A stage buffer of the last call as a torch tensor (synchronises first).  With
+    copy=False the tensor aliases the library's workspace and is valid until the next call."""
+    import torch
+    ptr, dims = oz2_stage_ptr(stage)
+    torch.cuda.synchronize()
+    if stage in (OZ2_STAGE_SHIFT_A, OZ2_STAGE_SHIFT_B):
+        shape, dtype = (dims[0],), torch.int32
+    elif stage in (OZ2_STAGE_RES_A, OZ2_STAGE_RES_B):
+        shape, dtype = dims[:3], torch.int8
+    else:
+        shape, dtype = dims[:3], torch.int32
+    typestr = {torch.int32: "<i4", torch.int8: "|i1"}[dtype]
+    view = torch.as_tensor(_DeviceView(ptr, tuple(shape), typestr), device="cuda")
+    return view.clone() if copy else view
+
+
+class _DeviceView:
+    """Zero-copy description of library-owned device memory for torch.as_tensor."""
+
+    def __init__(self, ptr: int, shape, typestr: str):
+        self.__cuda_array_interface__ = dict(shape=shape, typestr=typestr, data=(ptr, False),
+                                             version=2, strides=None)
+
+
+def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=None, stream=None):
+    """C = alpha * A @ B + beta * out for row-major device tensors, via oz2_dgemm / oz2_sgemm."""
+    import torch
+    if A.dim() != 2 or B.dim() != 2 or A.shape[1] != B.shape[0] or A.dtype != B.dtype:
+        raise ValueError("A (m x k) and B (k x n) of one dtype expected")
+    if A.stride(1) != 1 and A.shape[1] > 1 or B.stride(1) != 1 and B.shape[1] > 1:
+        raise ValueError("row-major operands expected")
+    m, k = A.shape
+    n = B.shape[1]
+    if out is None:
+        if beta != 0.0:
+            raise ValueError("beta != 0 needs `out`")
+        out = torch.empty((m, n), dtype=A.dtype, device=A.device)
+    lda = A.stride(0) if m > 1 else max(k, 1)
+    ldb = B.stride(0) if k > 1 else max(n, 1)
+    ldc = out.stride(0) if m > 1 else max(n, 1)
+    fn = oz2_dgemm if A.dtype == torch.float64 else oz2_sgemm
+    fn(m, n, k, alpha, A, lda, B, ldb, beta, out, ldc, num_moduli, stream)
+    return out

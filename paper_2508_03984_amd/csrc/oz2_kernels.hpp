@@ -1,0 +1,74 @@
+// Launchers of the gfx950 kernels behind oz2_dgemm / oz2_sgemm.  Every launcher
+// enqueues on `stream`, checks nothing but its own launch, and returns the HIP
+// error of that launch.  Buffer shapes are stated per launcher; all pointers
+// are device pointers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "oz2_constants.hpp"
+
+namespace oz2 {
+
+// Tile granularity the INT8 GEMM assumes for its padded operands.
+constexpr int64_t kPadMN = 256;   // rows of the A slices, rows of the B^T slices
+constexpr int64_t kPadK = 128;    // contraction length
+
+// Per-modulus constants handed to kernels by value (Section 4.1).
+struct ModArgs {
+    int32_t n;
+    int32_t rounds;                      // 1 or 2 reduction rounds in the residue kernel
+    int32_t p[kMaxModuli];
+    uint32_t pinv_prime[kMaxModuli];
+    double pinv[kMaxModuli];
+    double s1[kMaxModuli], s2[kMaxModuli];
+    double P1, P2, Pinv;
+};
+
+// Shift table of Section 4.2 (see oz2_constants.hpp).
+struct ShiftArgs {
+    int32_t f_max, levels;
+    uint64_t theta[kMaxLevels];
+};
+
+ModArgs make_mod_args(const Table &t);
+ShiftArgs make_shift_args(const Table &t);
+
+// out[c][r] = in[r][c]; in is rows x cols with leading dimension ld, out is cols x rows dense.
+template <typename T>
+hipError_t launch_transpose(const T *in, int64_t ld, int64_t rows, int64_t cols, T *out,
+                            hipStream_t stream);
+
+// Algorithm 1 line 1 (fast mode): one shift per row of X (rows x len, leading dimension ld).
+template <typename T>
+hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, const ShiftArgs &sa,
+                         int32_t *t, hipStream_t stream);
+
+// Algorithm 1 lines 2-5: out[s][r][h] = rmod(trunc(X[r][h] * 2^t[r]), p_s) as int8 for
+// s < n, r < rows_pad, h < len_pad; entries with r >= rows or h >= len are written as 0.
+template <typename T>
+hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *t,
+                           const ModArgs &ma, int8_t *out, int64_t rows_pad, int64_t len_pad,
+                           hipStream_t stream);
+
+// Algorithm 1 line 6: C[b] = A[b] * B[b]^T for b < batch, int8 in, wrapping int32 out.
+// A: [batch][Mp][Kp], B: [batch][Np][Kp], C: [batch][Mp][Np]; Mp, Np multiples of kPadMN,
+// Kp a multiple of kPadK.
+hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64_t Mp,
+                            int64_t Np, int64_t Kp, hipStream_t stream);
+
+// Algorithm 1 lines 7-12 and the alpha/beta update, fused:
+// C[i][j] = alpha * ldexp(C''(i,j), -(tA[i]+tB[j])) + beta * C[i][j]   (OutT = double or float)
+// prod: [n_mod][Mp][Np] int32.
+template <typename OutT>
+hipError_t launch_epilogue(const int32_t *prod, int64_t Mp, int64_t Np, int64_t m, int64_t n,
+                           const int32_t *tA, const int32_t *tB, const ModArgs &ma, double alpha,
+                           double beta, OutT *C, int64_t ldc, hipStream_t stream);
+
+// C <- beta * C (the k == 0 case).
+template <typename OutT>
+hipError_t launch_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n, double beta,
+                          hipStream_t stream);
+
+}  // namespace oz2

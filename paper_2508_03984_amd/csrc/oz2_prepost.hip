@@ -1,0 +1,324 @@
+// Bandwidth-bound kernels of the emulation for gfx950: transposition of B,
+// fast-mode shifts (Algorithm 1 line 1), residue slices (lines 2-5) and the fused
+// mod-reduce + CRT + unscale epilogue (lines 7-12).  64-wide wavefronts throughout.
+#include "oz2_kernels.hpp"
+
+namespace oz2 {
+
+ModArgs make_mod_args(const Table &t) {
+    ModArgs a{};
+    a.n = t.n;
+    // One reduction round is exact while |x'| < 2^46 (see residue_of); |x'| < 2^(f_max+1).
+    a.rounds = (t.f_max + 1 <= 46) ? 1 : 2;
+    for (int i = 0; i < t.n; ++i) {
+        a.p[i] = t.p[i];
+        a.pinv_prime[i] = t.pinv_prime[i];
+        a.pinv[i] = t.pinv[i];
+        a.s1[i] = t.s1[i];
+        a.s2[i] = t.s2[i];
+    }
+    a.P1 = t.P1; a.P2 = t.P2; a.Pinv = t.Pinv;
+    return a;
+}
+
+ShiftArgs make_shift_args(const Table &t) {
+    ShiftArgs s{};
+    s.f_max = t.f_max;
+    s.levels = t.levels;
+    for (int j = 0; j < kMaxLevels; ++j) s.theta[j] = j < t.levels ? t.theta[j] : ~0ull;
+    return s;
+}
+
+namespace {
+
+constexpr int kWave = 64;
+
+// ----------------------------------------------------------------------------------------
+// Transpose (B is row-major k x n; everything downstream wants its columns contiguous).
+// ----------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose(const T *__restrict__ in, int64_t ld,
+                                                   int64_t rows, int64_t cols,
+                                                   T *__restrict__ out) {
+    __shared__ T tile[64][65];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;          // 64 x 4
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+    for (int i = ty; i < 64; i += 4) {
+        int64_t r = r0 + i, c = c0 + tx;
+        tile[i][tx] = (r < rows && c < cols) ? in[r * ld + c] : T(0);
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        int64_t c = c0 + i, r = r0 + tx;                              // out row = input column
+        if (c < cols && r < rows) out[c * rows + r] = tile[tx][i];
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// Shifts.  One workgroup per row: pass 1 finds max|x| (as an integer compare of the FP64
+// bit patterns), pass 2 re-reads the row (from L2) and sums q^2 with
+// q = ceil(|x| 2^(15-e)) <= 2^16 in 64-bit integers, which is exact and independent of
+// the order of summation.  f comes from the threshold table, t = f - e.
+// ----------------------------------------------------------------------------------------
+__device__ inline uint64_t wave_max(uint64_t v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        uint64_t o = __shfl_xor(v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+__device__ inline uint64_t wave_sum(uint64_t v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ inline int floor_log2_of_bits(uint64_t bits) {            // bits of a finite |x| > 0
+    int ex = (int)(bits >> 52);
+    if (ex) return ex - 1023;
+    return (63 - __clzll((long long)bits)) - 1074;                    // subnormal
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_shifts(const T *__restrict__ X, int64_t ld, int64_t len,
+                                                ShiftArgs sa, int32_t *__restrict__ t) {
+    __shared__ uint64_t part[4];
+    __shared__ uint64_t bcast;
+    const T *x = X + (int64_t)blockIdx.x * ld;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    uint64_t mx = 0;
+    for (int64_t h = threadIdx.x; h < len; h += 256) {
+        uint64_t b = (uint64_t)__double_as_longlong(fabs((double)x[h]));
+        mx = b > mx ? b : mx;
+    }
+    mx = wave_max(mx);
+    if (lane == 0) part[wave] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t m = part[0];
+        for (int w = 1; w < 4; ++w) m = part[w] > m ? part[w] : m;
+        bcast = m;
+    }
+    __syncthreads();
+    mx = bcast;
+    if (mx == 0) {                                                    // all-zero row
+        if (threadIdx.x == 0) t[blockIdx.x] = 0;
+        return;
+    }
+    const int e = floor_log2_of_bits(mx);
+
+    uint64_t sum = 0;
+    for (int64_t h = threadIdx.x; h < len; h += 256) {
+        double q = ceil(ldexp(fabs((double)x[h]), 15 - e));
+        uint64_t qi = (uint64_t)q;
+        sum += qi * qi;
+    }
+    sum = wave_sum(sum);
+    __syncthreads();                                                  // part[] is reused
+    if (lane == 0) part[wave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t T_ = part[0] + part[1] + part[2] + part[3];
+        int j = 0;
+        while (j < sa.levels - 1 && T_ > sa.theta[j]) ++j;
+        t[blockIdx.x] = (sa.f_max - j) - e;
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// Residues.  x' = trunc(x 2^t) is an integer-valued FP64 number below 2^77.  Its
+// symmetric residue modulo p comes from rounds of  y <- fma(-rint(y * (1/p)), p, y),
+// the reduction of Section 4.2 kept in FP64 throughout (FP64 and FP32 FMA run at the
+// same rate on this chip, so there is nothing to gain from dropping to FP32):
+//   round 1 is exact (the difference is an integer below 2^26 in magnitude) and leaves
+//   |y| <= p/2 + 2^-52 |x'|;  for |x'| < 2^46 the quotient estimate is within 2^-13 of
+//   x'/p, closer than any integer/p can be to a half-integer for odd p, so rint returns
+//   round(x'/p) and y is already the residue in [-(p-1)/2, (p-1)/2];
+//   otherwise a second round, now on |y| < 2^26, does the same.
+// p = 256: 1/p is exact, y lands in [-128, 128] and the int8 cast wraps 128 to -128,
+// which is the same class (Section 4.1).
+// ----------------------------------------------------------------------------------------
+template <int ROUNDS>
+__device__ inline int residue_of(double x, double p, double pinv) {
+    double y = fma(-rint(x * pinv), p, x);
+    if (ROUNDS == 2) y = fma(-rint(y * pinv), p, y);
+    return (int)y;
+}
+
+constexpr int kResPerThread = 8;     // consecutive elements per thread -> 8-byte stores
+
+template <typename T, int ROUNDS>
+__global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64_t ld,
+                                                  int64_t rows, int64_t len,
+                                                  const int32_t *__restrict__ t, ModArgs ma,
+                                                  int8_t *__restrict__ out, int64_t rows_pad,
+                                                  int64_t len_pad) {
+    const int64_t chunks = len_pad / kResPerThread;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= rows_pad * chunks) return;
+    const int64_t r = idx / chunks, h0 = (idx % chunks) * kResPerThread;
+
+    double v[kResPerThread];
+    if (r < rows) {
+        const int sh = t[r];
+        const T *x = X + r * ld + h0;
+#pragma unroll
+        for (int i = 0; i < kResPerThread; ++i)
+            v[i] = (h0 + i < len) ? trunc(ldexp((double)x[i], sh)) : 0.0;
+    } else {
+#pragma unroll
+        for (int i = 0; i < kResPerThread; ++i) v[i] = 0.0;
+    }
+
+    const int64_t plane = rows_pad * len_pad;
+    int8_t *o = out + r * len_pad + h0;
+    for (int s = 0; s < ma.n; ++s) {
+        const double p = (double)ma.p[s], pinv = ma.pinv[s];
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < kResPerThread; ++i) {
+            uint32_t b = (uint32_t)residue_of<ROUNDS>(v[i], p, pinv) & 0xffu;
+            w[i >> 2] |= b << (8 * (i & 3));
+        }
+        *reinterpret_cast<uint2 *>(o + (int64_t)s * plane) = make_uint2(w[0], w[1]);
+    }
+}
+
+// ----------------------------------------------------------------------------------------
+// Epilogue: for each (i, j) read the N int32 products once, U_s = mod(C'_s, p_s) by the
+// mulhi reduction of Section 4.3, C1 += s_s1 U_s, C2 += s_s2 U_s (s = 1..N, one FMA each),
+// Q = rint(P_inv C1), C'' = fma(-P2, Q, fma(-P1, Q, C1) + C2), c = C'' 2^-(tA_i + tB_j).
+// One thread per 4 consecutive columns (16-byte loads of the int32 planes).
+// ----------------------------------------------------------------------------------------
+__device__ inline int mod_small(int x, int p, int pinv_prime) {
+    int y = x - __mulhi(x, pinv_prime) * p;
+    y -= (y >= p) ? p : 0;
+    y += (y < 0) ? p : 0;
+    return y;
+}
+
+template <typename OutT>
+__device__ inline OutT finish(double c, double alpha, double beta, const OutT *Cin) {
+    double r;
+    if (beta == 0.0) r = (alpha == 1.0) ? c : alpha * c;
+    else r = fma(alpha, c, beta * (double)*Cin);
+    return (OutT)r;
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(256) void k_epilogue(const int32_t *__restrict__ prod, int64_t Mp,
+                                                  int64_t Np, int64_t m, int64_t n,
+                                                  const int32_t *__restrict__ tA,
+                                                  const int32_t *__restrict__ tB, ModArgs ma,
+                                                  double alpha, double beta, OutT *C,
+                                                  int64_t ldc) {
+    const int64_t quads = (n + 3) / 4;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= m * quads) return;
+    const int64_t i = idx / quads, j0 = (idx % quads) * 4;
+
+    const int64_t plane = Mp * Np;
+    const int32_t *src = prod + i * Np + j0;                          // Np % 4 == 0, j0 + 3 < Np
+    double C1[4] = {0, 0, 0, 0}, C2[4] = {0, 0, 0, 0};
+    for (int s = 0; s < ma.n; ++s) {
+        const int4 x = *reinterpret_cast<const int4 *>(src + (int64_t)s * plane);
+        const int p = ma.p[s], pv = (int)ma.pinv_prime[s];
+        const double s1 = ma.s1[s], s2 = ma.s2[s];
+        const int xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            double u = (double)mod_small(xs[c], p, pv);
+            C1[c] = fma(s1, u, C1[c]);
+            C2[c] = fma(s2, u, C2[c]);
+        }
+    }
+    const int ta = tA[i];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (j0 + c < n) {
+            double Q = rint(ma.Pinv * C1[c]);
+            double T_ = fma(-ma.P1, Q, C1[c]);
+            double Cpp = fma(-ma.P2, Q, T_ + C2[c]);
+            double val = ldexp(Cpp, -(ta + tB[j0 + c]));
+            OutT *dst = C + i * ldc + j0 + c;
+            *dst = finish<OutT>(val, alpha, beta, dst);
+        }
+    }
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(256) void k_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n,
+                                                 double beta) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= m * n) return;
+    OutT *dst = C + (idx / n) * ldc + idx % n;
+    *dst = (beta == 0.0) ? OutT(0) : (OutT)(beta * (double)*dst);
+}
+
+inline unsigned blocks_for(int64_t threads) { return (unsigned)((threads + 255) / 256); }
+
+}  // namespace
+
+template <typename T>
+hipError_t launch_transpose(const T *in, int64_t ld, int64_t rows, int64_t cols, T *out,
+                            hipStream_t stream) {
+    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
+    hipLaunchKernelGGL((k_transpose<T>), grid, dim3(256), 0, stream, in, ld, rows, cols, out);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, const ShiftArgs &sa,
+                         int32_t *t, hipStream_t stream) {
+    hipLaunchKernelGGL((k_shifts<T>), dim3((unsigned)rows), dim3(256), 0, stream, X, ld, len, sa, t);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *t,
+                           const ModArgs &ma, int8_t *out, int64_t rows_pad, int64_t len_pad,
+                           hipStream_t stream) {
+    const int64_t threads = rows_pad * (len_pad / kResPerThread);
+    if (ma.rounds == 1)
+        hipLaunchKernelGGL((k_residues<T, 1>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
+                           ld, rows, len, t, ma, out, rows_pad, len_pad);
+    else
+        hipLaunchKernelGGL((k_residues<T, 2>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
+                           ld, rows, len, t, ma, out, rows_pad, len_pad);
+    return hipGetLastError();
+}
+
+template <typename OutT>
+hipError_t launch_epilogue(const int32_t *prod, int64_t Mp, int64_t Np, int64_t m, int64_t n,
+                           const int32_t *tA, const int32_t *tB, const ModArgs &ma, double alpha,
+                           double beta, OutT *C, int64_t ldc, hipStream_t stream) {
+    const int64_t threads = m * ((n + 3) / 4);
+    hipLaunchKernelGGL((k_epilogue<OutT>), dim3(blocks_for(threads)), dim3(256), 0, stream, prod,
+                       Mp, Np, m, n, tA, tB, ma, alpha, beta, C, ldc);
+    return hipGetLastError();
+}
+
+template <typename OutT>
+hipError_t launch_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n, double beta,
+                          hipStream_t stream) {
+    hipLaunchKernelGGL((k_scale_c<OutT>), dim3(blocks_for(m * n)), dim3(256), 0, stream, C, ldc, m,
+                       n, beta);
+    return hipGetLastError();
+}
+
+#define OZ2_INSTANTIATE(T)                                                                        \
+    template hipError_t launch_transpose<T>(const T *, int64_t, int64_t, int64_t, T *,           \
+                                            hipStream_t);                                         \
+    template hipError_t launch_shifts<T>(const T *, int64_t, int64_t, int64_t, const ShiftArgs &, \
+                                         int32_t *, hipStream_t);                                 \
+    template hipError_t launch_residues<T>(const T *, int64_t, int64_t, int64_t, const int32_t *, \
+                                           const ModArgs &, int8_t *, int64_t, int64_t,           \
+                                           hipStream_t);                                          \
+    template hipError_t launch_epilogue<T>(const int32_t *, int64_t, int64_t, int64_t, int64_t,  \
+                                           const int32_t *, const int32_t *, const ModArgs &,     \
+                                           double, double, T *, int64_t, hipStream_t);            \
+    template hipError_t launch_scale_c<T>(T *, int64_t, int64_t, int64_t, double, hipStream_t);
+OZ2_INSTANTIATE(double)
+OZ2_INSTANTIATE(float)
+
+}  // namespace oz2

@@ -1,0 +1,256 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Integer stages (shifts, residues, INT32 products) must be
+bit-exact; the final C must agree to 1e-14 relative (FP64 path) or 2^-23 (FP32
+path) -- both sides start from identical integers and run the same IEEE
+operations, so the expected difference is zero."""
+import os
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+TOL64 = 1e-14
+TOL32 = 2.0 ** -23
+
+
+@pytest.fixture(scope="module")
+def oz():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2508_03984_amd as oz
+    oz.load()                      # raises if liboz2.so has not been built: no fallback
+    yield oz
+    oz.oz2_release()
+
+
+def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None):
+    """Run oz2_dgemm / oz2_sgemm and fetch every stage, trimmed to the logical shapes."""
+    import torch
+    m, k = A.shape
+    n = B.shape[1]
+    dt = torch.float64 if A.dtype == np.float64 else torch.float32
+    lda = lda or k
+    ldb = ldb or n
+    dA = torch.zeros((m, lda), dtype=dt, device="cuda"); dA[:, :k] = torch.from_numpy(A).cuda()
+    dB = torch.zeros((k, ldb), dtype=dt, device="cuda"); dB[:, :n] = torch.from_numpy(B).cuda()
+    dC = (torch.from_numpy(np.ascontiguousarray(Cin)).cuda() if Cin is not None
+          else torch.full((m, n), float("nan"), dtype=dt, device="cuda"))
+    fn = oz.oz2_dgemm if dt == torch.float64 else oz.oz2_sgemm
+    fn(m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+    torch.cuda.synchronize()
+    from paper_2508_03984_amd import binding as b
+    out = dict(C=dC.cpu().numpy())
+    out["tA"] = oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy()
+    out["tB"] = oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy()
+    ra = oz.stage_tensor(b.OZ2_STAGE_RES_A); rb = oz.stage_tensor(b.OZ2_STAGE_RES_B)
+    pr = oz.stage_tensor(b.OZ2_STAGE_PROD)
+    out["pad_clean"] = bool((ra[:, m:, :] == 0).all() and (ra[:, :, k:] == 0).all()
+                            and (rb[:, n:, :] == 0).all() and (rb[:, :, k:] == 0).all())
+    out["Ares"] = ra[:, :m, :k].cpu().numpy()
+    out["Bres"] = rb[:, :n, :k].cpu().numpy()
+    out["prod"] = pr[:, :m, :n].cpu().numpy()
+    return out
+
+
+def assert_parity(got, ref, is_double):
+    assert np.array_equal(got["tA"], ref["tA"]), "row shifts differ"
+    assert np.array_equal(got["tB"], ref["tB"]), "column shifts differ"
+    assert got["pad_clean"], "padding of the residue slices is not zero"
+    assert np.array_equal(got["Ares"], ref["Ares"]), "residues of A differ"
+    assert np.array_equal(got["Bres"], ref["Bres"]), "residues of B differ"
+    assert np.array_equal(got["prod"], ref["prod"]), "INT32 products differ"
+    c, r = got["C"].astype(np.float64), ref["C"].astype(np.float64)
+    denom = np.where(r == 0, 1.0, np.abs(r))
+    rel = np.max(np.abs(c - r) / denom) if c.size else 0.0
+    assert rel <= (TOL64 if is_double else TOL32), f"C differs: max rel {rel}"
+    assert np.array_equal(c == 0, r == 0)
+
+
+CASES = [
+    # m, n, k, N, phi, dtype
+    (256, 256, 256, 14, 0.5, np.float64),      # the small configuration of the benchmark set
+    (1, 1, 1, 2, 0.5, np.float64),
+    (3, 5, 7, 20, 0.5, np.float64),
+    (300, 200, 333, 16, 0.5, np.float64),      # ragged in every dimension
+    (520, 390, 1000, 12, 2.0, np.float64),     # several tiles, one reduction round
+    (257, 513, 129, 13, 1.0, np.float64),      # first N with two reduction rounds
+    (130, 260, 640, 20, 4.0, np.float64),      # widest integers
+    (256, 256, 256, 8, 0.5, np.float32),
+    (300, 200, 333, 5, 1.0, np.float32),
+    (97, 515, 1030, 9, 0.5, np.float32),
+    (64, 64, 512, 2, 0.5, np.float32),
+]
+
+
+@pytest.mark.parametrize("m,n,k,N,phi,dtype", CASES)
+def test_stage_parity(oz, oracle, m, n, k, N, phi, dtype):
+    A, B = S.gemm_inputs(m, n, k, phi, seed=10 + N, dtype=dtype)
+    is_double = dtype == np.float64
+    ref = oracle.gemm(A, B, N, is_double=is_double)
+    got = gpu_gemm(oz, A, B, N)
+    assert_parity(got, ref, is_double)
+
+
+def test_alpha_beta_and_leading_dimensions(oz, oracle):
+    A, B = S.gemm_inputs(70, 90, 150, 0.5, seed=3)
+    Cin = S.matrix(70, 90, 0.5, seed=5)
+    for alpha, beta in ((1.0, 0.0), (-2.5, 0.0), (1.0, 1.0), (0.75, -0.5), (0.0, 2.0)):
+        ref = oracle.gemm(A, B, 15, alpha, beta, Cin)
+        got = gpu_gemm(oz, A, B, 15, alpha, beta, Cin.copy(), lda=160, ldb=97)
+        assert_parity(got, ref, True)
+    A32, B32, C32 = A.astype(np.float32), B.astype(np.float32), Cin.astype(np.float32)
+    ref = oracle.gemm(A32, B32, 8, 1.5, 0.25, C32, is_double=False)
+    got = gpu_gemm(oz, A32, B32, 8, 1.5, 0.25, C32.copy(), lda=151, ldb=128)
+    assert_parity(got, ref, False)
+
+
+def test_beta_zero_does_not_read_c(oz, oracle):
+    A, B = S.gemm_inputs(33, 17, 40, 0.5, seed=1)
+    got = gpu_gemm(oz, A, B, 14, 2.0, 0.0, np.full((33, 17), np.nan))
+    assert_parity(got, oracle.gemm(A, B, 14, 2.0, 0.0), True)
+
+
+def test_degenerate_inputs(oz, oracle):
+    A, B = S.gemm_inputs(40, 50, 60, 1.0, seed=9)
+    A[3, :] = 0.0                       # zero row
+    B[:, 7] = 0.0                       # zero column
+    A[5, :] *= 2.0 ** -1040             # subnormal row
+    B[:, 9] *= 2.0 ** 900               # huge column
+    A[6, :] = 0.0; A[6, 11] = -1.0      # single entry
+    A[7, :] = 1.0                       # constant rows and columns: worst case of the bound
+    B[:, 11] = -1.0
+    assert_parity(gpu_gemm(oz, A, B, 16), oracle.gemm(A, B, 16), True)
+    Z = np.zeros((20, 30)); Zb = np.zeros((30, 10))
+    assert_parity(gpu_gemm(oz, Z, Zb, 14), oracle.gemm(Z, Zb, 14), True)
+
+
+def test_empty_and_k_zero(oz):
+    import torch
+    C = torch.full((4, 5), 3.0, dtype=torch.float64, device="cuda")
+    A = torch.zeros((4, 1), dtype=torch.float64, device="cuda")
+    oz.oz2_dgemm(0, 5, 3, 1.0, A, 3, A, 5, 0.0, C, 5, 14)
+    oz.oz2_dgemm(4, 0, 3, 1.0, A, 3, A, 1, 0.0, C, 1, 14)
+    torch.cuda.synchronize()
+    assert bool((C == 3.0).all())
+    oz.oz2_dgemm(4, 5, 0, 1.0, A, 1, A, 5, 0.5, C, 5, 14)      # k = 0: C <- beta C
+    torch.cuda.synchronize()
+    assert bool((C == 1.5).all())
+    oz.oz2_dgemm(4, 5, 0, 1.0, A, 1, A, 5, 0.0, C, 5, 14)
+    torch.cuda.synchronize()
+    assert bool((C == 0.0).all())
+
+
+def test_int8_gemm_random_and_extreme(oz, oracle):
+    import torch
+    rng = np.random.default_rng(0)
+    batch, Mp, Np, Kp = 3, 256, 512, 384
+    A = rng.integers(-128, 128, (batch, Mp, Kp), dtype=np.int8)
+    B = rng.integers(-128, 128, (batch, Np, Kp), dtype=np.int8)
+    A[0, :7, :] = -128; B[0, :9, :] = -128; A[1, 3, :] = 127; B[1, 5, :] = 127
+    dC = torch.empty((batch, Mp, Np), dtype=torch.int32, device="cuda")
+    oz.oz2_int8_gemm(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), dC, batch, Mp, Np, Kp)
+    ref = oracle.int8_gemm_rows(A, B, np.arange(Mp))
+    assert np.array_equal(dC.cpu().numpy(), ref)
+
+
+def test_int32_wrap_at_k_2_pow_17(oz):
+    """Section 4.3: k = 2^17 with all residues -128 sums to 2^31, which wraps to -2^31."""
+    import torch
+    Mp = Np = 256; Kp = 2 ** 17
+    A = torch.full((1, Mp, Kp), -128, dtype=torch.int8, device="cuda")
+    A[0, 1, :] = 127
+    A[0, 2, -1] = 0
+    C = torch.empty((1, Mp, Np), dtype=torch.int32, device="cuda")
+    oz.oz2_int8_gemm(A, A, C, 1, Mp, Np, Kp)
+    c = C.cpu().numpy()[0]
+    assert c[0, 0] == -2 ** 31 and c[5, 9] == -2 ** 31
+    assert c[1, 1] == 127 * 127 * Kp and c[0, 1] == -128 * 127 * Kp
+    assert c[2, 2] == 2 ** 31 - 128 * 128 and c[0, 2] == 2 ** 31 - 128 * 128
+
+
+def test_determinism(oz):
+    import torch
+    A, B = S.gemm_inputs(300, 280, 500, 0.5, seed=4)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    c1 = oz.matmul(dA, dB, 15).clone()
+    c2 = oz.matmul(dA, dB, 15)
+    assert torch.equal(c1, c2)
+
+
+def test_caller_owned_workspace(oz, oracle):
+    import torch
+    A, B = S.gemm_inputs(100, 120, 140, 0.5, seed=6)
+    need = oz.oz2_workspace_bytes(100, 120, 140, 14, True)
+    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    oz.oz2_set_workspace(small)
+    with pytest.raises(oz.OZ2Error) as e:
+        oz.matmul(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), 14)
+    assert e.value.status == 3
+    buf = torch.empty(need, dtype=torch.uint8, device="cuda")
+    oz.oz2_set_workspace(buf)
+    try:
+        assert_parity(gpu_gemm(oz, A, B, 14), oracle.gemm(A, B, 14), True)
+    finally:
+        oz.oz2_set_workspace(None)
+
+
+# ------------------------------------------------------------------ benchmark-size configurations
+def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries=1500):
+    """Full comparison of shifts and residues, sampled comparison of products and C."""
+    import torch
+    from paper_2508_03984_amd import binding as b
+    is_double = dtype == np.float64
+    A, B = S.gemm_inputs(m, n, k, phi, seed, dtype)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = oz.matmul(dA, dB, N)
+    torch.cuda.synchronize()
+    prep = oracle.prepare(A, B, N, is_double)
+    assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
+    assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), prep["tB"])
+    ra = oz.stage_tensor(b.OZ2_STAGE_RES_A, copy=False)
+    for s in range(N):                                   # compare on the device, slice by slice
+        assert torch.equal(ra[s, :m, :k], torch.from_numpy(prep["Ares"][s]).cuda()), f"A slice {s}"
+    del ra
+    rb = oz.stage_tensor(b.OZ2_STAGE_RES_B, copy=False)
+    for s in range(N):
+        assert torch.equal(rb[s, :n, :k], torch.from_numpy(prep["Bres"][s]).cuda()), f"B slice {s}"
+    del rb
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, n_rows)]))
+    fin = oracle.finish_rows(prep, rows)
+    prod = oz.stage_tensor(b.OZ2_STAGE_PROD, copy=False)
+    got_rows = prod[:, torch.from_numpy(rows).cuda(), :n].cpu().numpy()
+    assert np.array_equal(got_rows, fin["prod"]), "INT32 products differ on sampled rows"
+    ii = rng.integers(0, m, n_entries); jj = rng.integers(0, n, n_entries)
+    ent = oracle.finish_entries(prep, ii, jj)
+    ti, tj = torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()
+    assert np.array_equal(prod[:, ti, tj].cpu().numpy(), ent["prod"])
+    del prod
+    tol = TOL64 if is_double else TOL32
+    for got, ref in ((dC[torch.from_numpy(rows).cuda()].cpu().numpy(), fin["C"]),
+                     (dC[ti, tj].cpu().numpy(), ent["C"])):
+        g, r = got.astype(np.float64), ref.astype(np.float64)
+        assert np.max(np.abs(g - r) / np.where(r == 0, 1.0, np.abs(r))) <= tol
+    return dC
+
+
+def test_config_4096_sampled(oz, oracle):
+    for N in (12, 16, 20):
+        sampled_parity(oz, oracle, 4096, 4096, 4096, N, 0.5, np.float64, seed=0)
+
+
+def test_config_16384_dgemm_sampled(oz, oracle):
+    sampled_parity(oz, oracle, 16384, 16384, 16384, 16, 0.5, np.float64, seed=0,
+                   n_rows=2, n_entries=1000)
+
+
+def test_config_sgemm_8192_sampled(oz, oracle):
+    sampled_parity(oz, oracle, 8192, 8192, 8192, 8, 0.5, np.float32, seed=0, n_rows=3)
+
+
+def test_config_nonsquare_k_65536_sampled(oz, oracle):
+    sampled_parity(oz, oracle, 8192, 8192, 65536, 18, 1.0, np.float64, seed=0,
+                   n_rows=2, n_entries=500)
