@@ -31,6 +31,34 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def gemm_only(oz, torch, size, N, args) -> int:
+    """Times oz2_int8_gemm alone on uniformly random int8 slices of the padded shape."""
+    pad = lambda x, to: (x + to - 1) // to * to
+    Mp = Np = pad(size, 256)
+    Kp = pad(size, 128)
+    g = torch.Generator(device="cuda").manual_seed(0)
+    A = torch.randint(-128, 128, (N, Kp // 64, Mp, 64), dtype=torch.int8, device="cuda", generator=g)
+    B = torch.randint(-128, 128, (N, Kp // 64, Np, 64), dtype=torch.int8, device="cuda", generator=g)
+    C = torch.empty((N, Mp, Np), dtype=torch.int32, device="cuda")
+    for _ in range(args.warmup):
+        oz.oz2_int8_gemm(A, B, C, N, Mp, Np, Kp)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        oz.oz2_int8_gemm(A, B, C, N, Mp, Np, Kp)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    ops = 2.0 * Mp * Np * Kp * N
+    tops = ops / (ms * 1e-3) / 1e12
+    log(f"int8 gemm {N} x {Mp}x{Np}x{Kp}: {ms:.3f} ms, {tops:.0f} TOP/s ({100 * tops / INT8_PEAK_TOPS:.1f}% of peak)")
+    print(json.dumps({"stage": "int8_gemm", "ms_per_launch": ms, "achieved_TOPs": tops,
+                      "frac_of_int8_peak": tops / INT8_PEAK_TOPS, "batch": N, "Mp": Mp, "Np": Np,
+                      "Kp": Kp, "steps": args.steps}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +69,9 @@ def main() -> int:
     ap.add_argument("--phi", type=float, default=0.5)
     ap.add_argument("--sgemm", action="store_true", help="FP32 emulation (oz2_sgemm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stage", choices=["all", "int8_gemm"], default="all",
+                    help="int8_gemm: time only the batched INT8 GEMM on random residues "
+                         "(for profiler runs); prints a reduced JSON line")
     ap.add_argument("--cpu-block", type=int, default=1024,
                     help="the oracle is timed on C[0:b, 0:b] with the full k")
     args = ap.parse_args()
@@ -63,6 +94,8 @@ def main() -> int:
 
     m = n = k = args.size
     N = args.moduli
+    if args.stage == "int8_gemm":
+        return gemm_only(oz, torch, m, N, args)
     np_dt, t_dt = (np.float32, torch.float32) if args.sgemm else (np.float64, torch.float64)
     log(f"generating inputs {m}x{k}, {k}x{n} phi={args.phi} ...")
     t0 = time.time()

@@ -111,9 +111,11 @@ oz2_status oz2_shift_table(int num_moduli, int32_t *f_max, int32_t *levels, uint
  * live in the workspace.  dims (host, 4 entries) describes the layout:
  *   OZ2_STAGE_SHIFT_A  int32 [m]                 dims = { m, 0, 0, 0 }
  *   OZ2_STAGE_SHIFT_B  int32 [n]                 dims = { n, 0, 0, 0 }
- *   OZ2_STAGE_RES_A    int8  [N][Mp][Kp]         dims = { N, Mp, Kp, m }   rows >= m, cols >= k are 0
- *   OZ2_STAGE_RES_B    int8  [N][Np][Kp]         dims = { N, Np, Kp, n }   (B slices are stored transposed)
+ *   OZ2_STAGE_RES_A    int8  [N][Kp/64][Mp][64]  dims = { N, Mp, Kp, m }   rows >= m, k-index >= k are 0
+ *   OZ2_STAGE_RES_B    int8  [N][Kp/64][Np][64]  dims = { N, Np, Kp, n }   (B slices are stored transposed)
  *   OZ2_STAGE_PROD     int32 [N][Mp][Np]         dims = { N, Mp, Np, 0 }
+ * The residue slices are K-blocked: residue (row r, k-index h) of slice s is at
+ * ((s * Kp/64 + h/64) * rows + r) * 64 + h%64, so that a (rows x 64) tile is contiguous.
  * Valid until the next call or workspace change; the caller synchronises.
  */
 enum { OZ2_STAGE_SHIFT_A = 0, OZ2_STAGE_SHIFT_B = 1, OZ2_STAGE_RES_A = 2,
@@ -122,8 +124,9 @@ oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims);
 
 /*
  * Diagnostics: the batched INT8 GEMM of Algorithm 1 line 6 on its own.
- * dev_A: int8 [batch][Mp][Kp], dev_B: int8 [batch][Np][Kp] (both K-contiguous),
- * dev_C: int32 [batch][Mp][Np];  C_b = A_b * B_b^T with wrapping INT32 sums.
+ * dev_A: int8 [batch][Kp/64][Mp][64], dev_B: int8 [batch][Kp/64][Np][64] (the K-blocked
+ * layout of the residue slices, see oz2_stage_ptr), dev_C: int32 [batch][Mp][Np];
+ * C_b = A_b * B_b^T with wrapping INT32 sums.
  * Mp and Np must be multiples of 256, Kp a multiple of 128 (OZ2_INVALID_ARG otherwise).
  */
 oz2_status oz2_int8_gemm(const int8_t *dev_A, const int8_t *dev_B, int32_t *dev_C,

@@ -185,7 +185,7 @@ def stage_tensor(stage: int, copy: bool = True):
     if stage in (OZ2_STAGE_SHIFT_A, OZ2_STAGE_SHIFT_B):
         shape, dtype = (dims[0],), torch.int32
     elif stage in (OZ2_STAGE_RES_A, OZ2_STAGE_RES_B):
-        shape, dtype = dims[:3], torch.int8
+        shape, dtype = (dims[0], dims[2] // 64, dims[1], 64), torch.int8     # K-blocked
     else:
         shape, dtype = dims[:3], torch.int32
     typestr = {torch.int32: "<i4", torch.int8: "|i1"}[dtype]
@@ -199,6 +199,18 @@ class _DeviceView:
     def __init__(self, ptr: int, shape, typestr: str):
         self.__cuda_array_interface__ = dict(shape=shape, typestr=typestr, data=(ptr, False),
                                              version=2, strides=None)
+
+
+def unblock_slices(t):
+    """[N][K/64][R][64] (the library's K-blocked slice layout) -> [N][R][K]."""
+    n, kb, r, w = t.shape
+    return t.permute(0, 2, 1, 3).reshape(n, r, kb * w)
+
+
+def block_slices(t):
+    """[N][R][K] -> [N][K/64][R][64], K a multiple of 64."""
+    n, r, k = t.shape
+    return t.reshape(n, r, k // 64, 64).permute(0, 2, 1, 3).contiguous()
 
 
 def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=None, stream=None):

@@ -1,14 +1,28 @@
 // Batched INT8 GEMM with exact (wrapping) INT32 accumulation on the gfx950 matrix cores:
 // Algorithm 1 line 6, C'_s = A'_s B'_s for all moduli s in one launch.
 //
-// Operands are the padded, K-contiguous residue slices: A [batch][Mp][Kp] and
-// B [batch][Np][Kp] (B transposed), so both tiles are staged through LDS the same way
+// Operands are the padded residue slices in the K-blocked layout the residue kernel
+// writes: A [batch][Kp/64][Mp][64] and B [batch][Kp/64][Np][64] (B transposed), i.e. 64
+// consecutive k of one row are contiguous and consecutive rows of one 64-wide K block
+// follow each other.  A (rows x 64) tile of either operand is then one contiguous run of
+// memory, fetched as whole 128-byte lines, both tiles are staged through LDS the same way
 // and every MFMA operand is a 16-byte K-run read with one ds_read_b128.
 //
 // Tiling: workgroup = 4 wavefronts (2 x 2), block tile (64 TM) x (64 TN) x BK, each
-// wavefront owns (32 TM) x (32 TN) = TM x TN v_mfma_i32_32x32x32_i8 accumulators.
-// LDS holds two stages; 16-byte chunks of a row are XOR-swizzled with the row index so
-// that the 32 rows a fragment read touches fall in distinct bank groups.
+// wavefront owns (32 TM) x (32 TN) = TM x TN v_mfma_i32_32x32x32_i8 accumulators
+// (256 AGPRs at TM = TN = 4, one wavefront per SIMD).
+//
+// Data movement: global_load_lds_dwordx4 copies HBM/L2 straight into a ring of STAGES LDS
+// stages, STAGES-1 tiles ahead of the math, so no VGPRs or ds_write instructions are spent
+// on staging.  A wavefront's 64 lanes fill 64 consecutive 16-byte LDS chunks per
+// instruction; the XOR swizzle that keeps the fragment reads free of bank conflicts is
+// applied on the global side (which 16 bytes of a row a lane fetches).  MFMA operands are
+// double-buffered in registers and fetched one 32-deep K step ahead, across stage
+// boundaries, so LDS latency is covered by 16 MFMAs.
+//
+// Synchronisation per K tile: one s_waitcnt vmcnt(n) that leaves the youngest tiles in
+// flight, then one s_barrier.  The compiler does not track LDS writes made by
+// global_load_lds, so these two are what orders them against the ds_reads.
 #include "oz2_kernels.hpp"
 
 namespace oz2 {
@@ -16,44 +30,106 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef const __attribute__((address_space(1))) void *global_ptr_t;
 
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima).
+constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
+
+// LDS on this chip is 64 banks x 4 B: a 256-byte line is 16 slots of 16 B, and a
+// ds_read_b128 is served 16 lanes per clock.  A tile row is CPR slots, so rows r and
+// r + 16/CPR start in the same slot; XOR-ing the chunk index with (row / (16/CPR)) spreads
+// the 32 rows that a fragment read touches over all 16 slots in every group of lanes the
+// hardware serves together (measured: 230 B/clk/CU against 125 with a 128-byte-line swizzle).
 template <int CPR>
-__device__ inline int swizzle(int row, int chunk) {
-    // CPR chunks of 16 B per row; rows that share LDS bank groups get distinct XOR masks.
-    return chunk ^ ((row / (8 / CPR)) & (CPR - 1));
+__device__ inline int swizzle_mask(int row) {
+    return (row / (16 / CPR)) & (CPR - 1);
 }
 
-template <int TM, int TN, int BK>
+struct TileMap {
+    int tiles_m, tiles_n;      // tiles per slice
+    int swizzled;              // 1: tiles_m and tiles_n are multiples of 16
+};
+
+// Workgroup id -> (slice, tile row, tile column).  Workgroups are handed to the 8 XCDs
+// round-robin by id, and 256 run at a time (one per CU).  In the swizzled map the 256
+// co-resident workgroups cover one 16 x 16-tile region of one slice, and the 32 that share
+// an XCD (and its L2) cover an 8 x 4 sub-block of it, so an A tile row is fetched into that
+// L2 once for 4 workgroups and a B tile row once for 8.
+__device__ inline void map_tile(const TileMap &tm, int id, int &s, int &tr, int &tc) {
+    if (tm.swizzled) {
+        const int xcd = id & 7, local = id >> 3;
+        const int pos = local & 31, region = local >> 5;
+        const int regions_n = tm.tiles_n / 16, regions = (tm.tiles_m / 16) * regions_n;
+        s = region / regions;
+        const int r = region % regions;
+        tr = (r / regions_n) * 16 + (xcd >> 2) * 8 + (pos >> 2);
+        tc = (r % regions_n) * 16 + (xcd & 3) * 4 + (pos & 3);
+    } else {
+        const int per = tm.tiles_m * tm.tiles_n;
+        s = id / per;
+        tr = (id % per) / tm.tiles_n;
+        tc = id % tm.tiles_n;
+    }
+}
+
+template <int TM, int TN, int BK, int STAGES>
 __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
                                                    const int8_t *__restrict__ B,
                                                    int32_t *__restrict__ C, int64_t Mp,
-                                                   int64_t Np, int64_t Kp) {
+                                                   int64_t Np, int64_t Kp, TileMap tmap) {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
     constexpr int ROWS = BM + BN;                      // A rows then B rows in one LDS stage
     constexpr int CHUNKS = ROWS * CPR;
-    constexpr int LPT = CHUNKS / 256;                  // global 16-byte loads per thread and stage
-    static_assert(CHUNKS % 256 == 0, "tile must split evenly over the workgroup");
-    static_assert(CPR == 4 || CPR == 8, "BK must be 64 or 128");
+    constexpr int LPT = CHUNKS / 256;                  // LDS-direct loads per lane and tile
+    constexpr int KK = BK / 32;                        // MFMA K steps per tile
+    constexpr int STAGE_BYTES = CHUNKS * 16;
+    constexpr int ROWS_PER_LOAD = 64 / CPR;            // rows one wavefront-wide load covers
+    static_assert(CHUNKS % 256 == 0 && (BM * CPR) % (64 * LPT) == 0,
+                  "each wavefront must load from one operand only");
+    static_assert(BK == kBlockK, "the K tile is the K block of the operand layout");
+    static_assert(CPR == 4, "the load-side swizzle below assumes one mask per lane");
+    static_assert(STAGES >= 3 && (STAGES - 3) * LPT < 64, "vmcnt is a 6-bit counter");
+    static_assert(KK >= 2, "operand double-buffering assumes an even number of K steps");
 
-    extern __shared__ v4i lds[];                       // [2][ROWS][CPR]
+    extern __shared__ v4i lds[];                       // [STAGES][ROWS][CPR]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t bm = (int64_t)blockIdx.y * BM, bn = (int64_t)blockIdx.x * BN;
-    const int64_t s = blockIdx.z;
-    const int8_t *Ab = A + (s * Mp + bm) * Kp;
-    const int8_t *Bb = B + (s * Np + bn) * Kp;
+    int s, tile_r, tile_c;
+    map_tile(tmap, (int)blockIdx.x, s, tile_r, tile_c);
+    const int64_t bm = (int64_t)tile_r * BM, bn = (int64_t)tile_c * BN;
+    const int64_t KB = Kp / BK;                        // K blocks per slice
+    const int8_t *Ab = A + ((int64_t)s * KB * Mp + bm) * BK;      // K block 0 of this tile
+    const int8_t *Bb = B + ((int64_t)s * KB * Np + bn) * BK;
 
-    // Global source of each of this thread's chunks (row-major over [ROWS][CPR]).
-    const int8_t *src[LPT];
-    int dst[LPT];
+    // Load i of this wavefront fills LDS chunks [64 q, 64 q + 64) of a stage, q = wave*LPT + i,
+    // i.e. rows q*ROWS_PER_LOAD ...; lane -> (row, physical chunk) -> logical chunk to fetch.
+    // In the blocked layout those 64 chunks are 1 KiB of contiguous memory.
+    const int row0 = wave * LPT * ROWS_PER_LOAD + lane / CPR;
+    const int ch = (lane % CPR) ^ swizzle_mask<CPR>(row0);
+    const bool from_a = row0 < BM;
+    const int8_t *src0 = (from_a ? Ab + (int64_t)row0 * BK : Bb + (int64_t)(row0 - BM) * BK) + ch * 16;
+    const int64_t tile_step = (from_a ? Mp : Np) * BK;  // next K block of the same rows
+    constexpr int src_step = ROWS_PER_LOAD * BK;
+    char *const lds_bytes = reinterpret_cast<char *>(lds);
+    char *const my_dst = lds_bytes + wave * LPT * 1024;
+
+    auto issue_tile = [&](int t) {
+        const int8_t *src = src0 + (int64_t)t * tile_step;
+        char *dst = my_dst + (t % STAGES) * STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-        int ci = tid + 256 * i, row = ci / CPR, ch = ci % CPR;
-        src[i] = (row < BM ? Ab + (int64_t)row * Kp : Bb + (int64_t)(row - BM) * Kp) + ch * 16;
-        dst[i] = row * CPR + swizzle<CPR>(row, ch);
-    }
+        for (int i = 0; i < LPT; ++i)
+            __builtin_amdgcn_global_load_lds((global_ptr_t)(src + i * src_step),
+                                             (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
+    };
+
+    const int KT = (int)(Kp / BK);                     // >= 2: Kp is a multiple of 128
+#pragma unroll
+    for (int t = 0; t < STAGES - 1; ++t)
+        if (t < KT) issue_tile(t);
 
     v16i acc[TM][TN];
 #pragma unroll
@@ -63,53 +139,64 @@ __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    v4i stage[LPT];
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) stage[i] = *reinterpret_cast<const v4i *>(src[i]);
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) lds[dst[i]] = stage[i];
-    __syncthreads();
-
-    const int KT = (int)(Kp / BK);
+    // Fragment addressing: lane l reads row (l % 32) of a 32-row fragment, 16-byte chunk
+    // 2*kk + l/32 of the K tile.  The swizzle mask depends on l % 32 only.
     const int lrow = lane & 31, lhalf = lane >> 5;
+    const int mask = swizzle_mask<CPR>(lrow);
+    const int a_off = (wm * 32 * TM + lrow) * CPR;             // in chunks
+    const int b_off = (BM + wn * 32 * TN + lrow) * CPR;
+
+    v4i fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int buf, int t, int kk) {
+        const v4i *st = lds + (t % STAGES) * CHUNKS;
+        const int c = (kk * 2 + lhalf) ^ mask;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[buf][i] = st[a_off + i * 32 * CPR + c];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = st[b_off + j * 32 * CPR + c];
+    };
+
+    // Tiles 0 and 1 must have landed before the first fragment reads.
+    if (KT >= STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, 0);
+
     for (int kt = 0; kt < KT; ++kt) {
-        const v4i *cur = lds + (kt & 1) * CHUNKS;
-        v4i *nxt = lds + ((kt + 1) & 1) * CHUNKS;
-        const bool more = kt + 1 < KT;
-        if (more) {
+        const bool issued = kt + STAGES - 1 < KT;
+        if (issued) issue_tile(kt + STAGES - 1);       // into the stage read during kt - 1
 #pragma unroll
-            for (int i = 0; i < LPT; ++i)
-                stage[i] = *reinterpret_cast<const v4i *>(src[i] + (int64_t)(kt + 1) * BK);
-        }
+        for (int kk = 0; kk < KK; ++kk) {
+            const int cur = kk & 1, nxt = cur ^ 1;
+            // The first MFMA row runs before the next operands are requested: its operands
+            // were requested a whole K step ago, so waiting for them (the LDS counter is
+            // waited down to zero at that point) does not wait for the new requests.
 #pragma unroll
-        for (int kk = 0; kk < BK / 32; ++kk) {
-            v4i a[TM], b[TN];
+            for (int j = 0; j < TN; ++j)
+                acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][0], fb[cur][j],
+                                                                  acc[0][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk + 1 < KK) load_frags(nxt, kt, kk + 1);
+            else if (kt + 1 < KT) load_frags(nxt, kt + 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int row = wm * 32 * TM + i * 32 + lrow;
-                a[i] = cur[row * CPR + swizzle<CPR>(row, kk * 2 + lhalf)];
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int row = BM + wn * 32 * TN + j * 32 + lrow;
-                b[j] = cur[row * CPR + swizzle<CPR>(row, kk * 2 + lhalf)];
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 1; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j],
+                                                                      acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < LPT; ++i) nxt[dst[i]] = stage[i];
-        }
-        __syncthreads();
+        // Tile kt + 2 must be complete (and visible to every wavefront) before iteration
+        // kt + 1 prefetches fragments from it; the barrier also frees stage kt % STAGES.
+        if (issued) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __builtin_amdgcn_s_barrier();
     }
 
     // Accumulator layout of the 32x32 MFMA: lane l, register r holds
     // row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-    int32_t *Cb = C + (s * Mp + bm) * Np + bn;
+    int32_t *Cb = C + ((int64_t)s * Mp + bm) * Np + bn;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -122,22 +209,27 @@ __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
             }
 }
 
-template <int TM, int TN, int BK>
+template <int TM, int TN, int BK, int STAGES>
 hipError_t launch(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64_t Mp, int64_t Np,
                   int64_t Kp, hipStream_t stream) {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr size_t lds_bytes = 2ull * (BM + BN) * BK;
+    constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_int8_gemm<TM, TN, BK>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)lds_bytes);
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(&k_int8_gemm<TM, TN, BK, STAGES>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((unsigned)(Np / BN), (unsigned)(Mp / BM), (unsigned)batch);
-    hipLaunchKernelGGL((k_int8_gemm<TM, TN, BK>), grid, dim3(256), lds_bytes, stream, A, B, C, Mp,
-                       Np, Kp);
+    TileMap tm;
+    tm.tiles_m = (int)(Mp / BM);
+    tm.tiles_n = (int)(Np / BN);
+    tm.swizzled = (tm.tiles_m % 16 == 0 && tm.tiles_n % 16 == 0) ? 1 : 0;
+    const int64_t total = (int64_t)tm.tiles_m * tm.tiles_n * batch;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_int8_gemm<TM, TN, BK, STAGES>), dim3((unsigned)total), dim3(256), lds_bytes,
+                       stream, A, B, C, Mp, Np, Kp, tm);
     return hipGetLastError();
 }
 
@@ -147,8 +239,8 @@ hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, int32_t *C, int ba
                             int64_t Np, int64_t Kp, hipStream_t stream) {
     // Small problems get the 128 x 128 tile so that more workgroups exist.
     if (Mp * Np * batch < (int64_t)256 * 256 * 512)
-        return launch<2, 2, 64>(A, B, C, batch, Mp, Np, Kp, stream);
-    return launch<4, 4, 64>(A, B, C, batch, Mp, Np, Kp, stream);
+        return launch<2, 2, 64, 4>(A, B, C, batch, Mp, Np, Kp, stream);
+    return launch<4, 4, 64, 5>(A, B, C, batch, Mp, Np, Kp, stream);
 }
 
 }  // namespace oz2

@@ -14,6 +14,7 @@ namespace oz2 {
 // Tile granularity the INT8 GEMM assumes for its padded operands.
 constexpr int64_t kPadMN = 256;   // rows of the A slices, rows of the B^T slices
 constexpr int64_t kPadK = 128;    // contraction length
+constexpr int kBlockK = 64;       // K block of the residue-slice layout [Kp/64][rows][64]
 
 // Per-modulus constants handed to kernels by value (Section 4.1).
 struct ModArgs {
@@ -45,16 +46,17 @@ template <typename T>
 hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, const ShiftArgs &sa,
                          int32_t *t, hipStream_t stream);
 
-// Algorithm 1 lines 2-5: out[s][r][h] = rmod(trunc(X[r][h] * 2^t[r]), p_s) as int8 for
-// s < n, r < rows_pad, h < len_pad; entries with r >= rows or h >= len are written as 0.
+// Algorithm 1 lines 2-5: rmod(trunc(X[r][h] * 2^t[r]), p_s) as int8 for s < n,
+// r < rows_pad, h < len_pad, stored K-blocked: out[s][h / 64][r][h % 64]; entries with
+// r >= rows or h >= len are written as 0.
 template <typename T>
 hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *t,
                            const ModArgs &ma, int8_t *out, int64_t rows_pad, int64_t len_pad,
                            hipStream_t stream);
 
 // Algorithm 1 line 6: C[b] = A[b] * B[b]^T for b < batch, int8 in, wrapping int32 out.
-// A: [batch][Mp][Kp], B: [batch][Np][Kp], C: [batch][Mp][Np]; Mp, Np multiples of kPadMN,
-// Kp a multiple of kPadK.
+// A: [batch][Kp/64][Mp][64], B: [batch][Kp/64][Np][64] (K-blocked, see launch_residues),
+// C: [batch][Mp][Np]; Mp, Np multiples of kPadMN, Kp a multiple of kPadK.
 hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64_t Mp,
                             int64_t Np, int64_t Kp, hipStream_t stream);
 

@@ -153,10 +153,15 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
                                                   const int32_t *__restrict__ t, ModArgs ma,
                                                   int8_t *__restrict__ out, int64_t rows_pad,
                                                   int64_t len_pad) {
-    const int64_t chunks = len_pad / kResPerThread;
+    // Thread -> (K block, row, 8-element piece of the 64-wide block), piece fastest: a
+    // wavefront writes 8 rows x 64 B = 512 contiguous bytes of the blocked output and reads
+    // 512 contiguous bytes of each of 8 input rows.
+    constexpr int kPieces = kBlockK / kResPerThread;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= rows_pad * chunks) return;
-    const int64_t r = idx / chunks, h0 = (idx % chunks) * kResPerThread;
+    if (idx >= rows_pad * (len_pad / kResPerThread)) return;
+    const int64_t kb = idx / (rows_pad * kPieces);
+    const int64_t r = (idx / kPieces) % rows_pad;
+    const int64_t h0 = kb * kBlockK + (idx % kPieces) * kResPerThread;
 
     double v[kResPerThread];
     if (r < rows) {
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
     }
 
     const int64_t plane = rows_pad * len_pad;
-    int8_t *o = out + r * len_pad + h0;
+    int8_t *o = out + (kb * rows_pad + r) * kBlockK + (h0 - kb * kBlockK);
     for (int s = 0; s < ma.n; ++s) {
         const double p = (double)ma.p[s], pinv = ma.pinv[s];
         uint32_t w[2] = {0u, 0u};

@@ -45,7 +45,8 @@ def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None):
     out = dict(C=dC.cpu().numpy())
     out["tA"] = oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy()
     out["tB"] = oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy()
-    ra = oz.stage_tensor(b.OZ2_STAGE_RES_A); rb = oz.stage_tensor(b.OZ2_STAGE_RES_B)
+    ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A))
+    rb = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_B))
     pr = oz.stage_tensor(b.OZ2_STAGE_PROD)
     out["pad_clean"] = bool((ra[:, m:, :] == 0).all() and (ra[:, :, k:] == 0).all()
                             and (rb[:, n:, :] == 0).all() and (rb[:, :, k:] == 0).all())
@@ -151,7 +152,8 @@ def test_int8_gemm_random_and_extreme(oz, oracle):
     B = rng.integers(-128, 128, (batch, Np, Kp), dtype=np.int8)
     A[0, :7, :] = -128; B[0, :9, :] = -128; A[1, 3, :] = 127; B[1, 5, :] = 127
     dC = torch.empty((batch, Mp, Np), dtype=torch.int32, device="cuda")
-    oz.oz2_int8_gemm(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), dC, batch, Mp, Np, Kp)
+    oz.oz2_int8_gemm(oz.block_slices(torch.from_numpy(A).cuda()),
+                     oz.block_slices(torch.from_numpy(B).cuda()), dC, batch, Mp, Np, Kp)
     ref = oracle.int8_gemm_rows(A, B, np.arange(Mp))
     assert np.array_equal(dC.cpu().numpy(), ref)
 
@@ -164,6 +166,7 @@ def test_int32_wrap_at_k_2_pow_17(oz):
     A[0, 1, :] = 127
     A[0, 2, -1] = 0
     C = torch.empty((1, Mp, Np), dtype=torch.int32, device="cuda")
+    A = oz.block_slices(A)
     oz.oz2_int8_gemm(A, A, C, 1, Mp, Np, Kp)
     c = C.cpu().numpy()[0]
     assert c[0, 0] == -2 ** 31 and c[5, 9] == -2 ** 31
@@ -210,11 +213,11 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
     prep = oracle.prepare(A, B, N, is_double)
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), prep["tB"])
-    ra = oz.stage_tensor(b.OZ2_STAGE_RES_A, copy=False)
+    ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A, copy=False))    # a permuted view
     for s in range(N):                                   # compare on the device, slice by slice
         assert torch.equal(ra[s, :m, :k], torch.from_numpy(prep["Ares"][s]).cuda()), f"A slice {s}"
     del ra
-    rb = oz.stage_tensor(b.OZ2_STAGE_RES_B, copy=False)
+    rb = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_B, copy=False))
     for s in range(N):
         assert torch.equal(rb[s, :n, :k], torch.from_numpy(prep["Bres"][s]).cuda()), f"B slice {s}"
     del rb
