@@ -25,7 +25,8 @@ FLAGS = [
 
 def build_library(verbose: bool = False) -> str:
     """Compile every source for gfx950 and link liboz2.so; always rebuilds."""
-    cmd = [HIPCC] + FLAGS + ["-x", "hip"] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    extra = os.environ.get("OZ2_EXTRA_HIPCC_FLAGS", "").split()      # for experiments
+    cmd = [HIPCC] + FLAGS + extra + ["-x", "hip"] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -8,9 +8,10 @@
 // memory, fetched as whole 128-byte lines, both tiles are staged through LDS the same way
 // and every MFMA operand is a 16-byte K-run read with one ds_read_b128.
 //
-// Tiling: workgroup = 4 wavefronts (2 x 2), block tile (64 TM) x (64 TN) x BK, each
-// wavefront owns (32 TM) x (32 TN) = TM x TN v_mfma_i32_32x32x32_i8 accumulators
-// (256 AGPRs at TM = TN = 4, one wavefront per SIMD).
+// Tiling: workgroup = WM x WN wavefronts, block tile (32 TM WM) x (32 TN WN) x 64, each
+// wavefront owns (32 TM) x (32 TN) = TM x TN v_mfma_i32_32x32x32_i8 accumulators.  The
+// large configuration is 2 x 4 wavefronts of 128 x 64 (a 256 x 256 block, 128 accumulator
+// registers per lane, two wavefronts per SIMD).
 //
 // Data movement: global_load_lds_dwordx4 copies HBM/L2 straight into a ring of STAGES LDS
 // stages, STAGES-1 tiles ahead of the math, so no VGPRs or ds_write instructions are spent
@@ -74,20 +75,21 @@ __device__ inline void map_tile(const TileMap &tm, int id, int &s, int &tr, int 
     }
 }
 
-template <int TM, int TN, int BK, int STAGES>
-__global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
+template <int WM, int WN, int TM, int TN, int BK, int STAGES>
+__global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__restrict__ A,
                                                    const int8_t *__restrict__ B,
                                                    int32_t *__restrict__ C, int64_t Mp,
                                                    int64_t Np, int64_t Kp, TileMap tmap) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int THREADS = 64 * WM * WN;              // WM x WN wavefronts
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
     constexpr int ROWS = BM + BN;                      // A rows then B rows in one LDS stage
     constexpr int CHUNKS = ROWS * CPR;
-    constexpr int LPT = CHUNKS / 256;                  // LDS-direct loads per lane and tile
+    constexpr int LPT = CHUNKS / THREADS;              // LDS-direct loads per lane and tile
     constexpr int KK = BK / 32;                        // MFMA K steps per tile
     constexpr int STAGE_BYTES = CHUNKS * 16;
     constexpr int ROWS_PER_LOAD = 64 / CPR;            // rows one wavefront-wide load covers
-    static_assert(CHUNKS % 256 == 0 && (BM * CPR) % (64 * LPT) == 0,
+    static_assert(CHUNKS % THREADS == 0 && (BM * CPR) % (64 * LPT) == 0,
                   "each wavefront must load from one operand only");
     static_assert(BK == kBlockK, "the K tile is the K block of the operand layout");
     static_assert(CPR == 4, "the load-side swizzle below assumes one mask per lane");
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
     extern __shared__ v4i lds[];                       // [STAGES][ROWS][CPR]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     int s, tile_r, tile_c;
     map_tile(tmap, (int)blockIdx.x, s, tile_r, tile_c);
     const int64_t bm = (int64_t)tile_r * BM, bn = (int64_t)tile_c * BN;
@@ -117,14 +119,16 @@ __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
     char *const lds_bytes = reinterpret_cast<char *>(lds);
     char *const my_dst = lds_bytes + wave * LPT * 1024;
 
-    auto issue_tile = [&](int t) {
+    // Loads [i0, i1) of tile t for this wavefront.
+    auto issue_loads = [&](int t, int i0, int i1) {
         const int8_t *src = src0 + (int64_t)t * tile_step;
         char *dst = my_dst + (t % STAGES) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < LPT; ++i)
+        for (int i = i0; i < i1; ++i)
             __builtin_amdgcn_global_load_lds((global_ptr_t)(src + i * src_step),
                                              (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
     };
+    auto issue_tile = [&](int t) { issue_loads(t, 0, LPT); };
 
     const int KT = (int)(Kp / BK);                     // >= 2: Kp is a multiple of 128
 #pragma unroll
@@ -162,9 +166,13 @@ __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
     __builtin_amdgcn_s_barrier();
     load_frags(0, 0, 0);
 
+    // The LPT loads of a tile are spread over the MFMA rows of a K tile (after every row
+    // but the first of each K step), so that a load that has to wait for room in the memory
+    // pipeline holds up one MFMA row, not the whole tile.
+    constexpr int SLOTS = KK * (TM - 1);
+    constexpr int PER_SLOT = (LPT + SLOTS - 1) / SLOTS;
     for (int kt = 0; kt < KT; ++kt) {
-        const bool issued = kt + STAGES - 1 < KT;
-        if (issued) issue_tile(kt + STAGES - 1);       // into the stage read during kt - 1
+        const bool issued = kt + STAGES - 1 < KT;      // loads go into the stage read during kt - 1
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
             const int cur = kk & 1, nxt = cur ^ 1;
@@ -180,12 +188,17 @@ __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
             else if (kt + 1 < KT) load_frags(nxt, kt + 1, 0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 1; i < TM; ++i)
+            for (int i = 1; i < TM; ++i) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j],
                                                                       acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
+                const int slot = kk * (TM - 1) + (i - 1);
+                const int i0 = slot * PER_SLOT, i1 = (i0 + PER_SLOT < LPT) ? i0 + PER_SLOT : LPT;
+                if (issued && i0 < LPT) issue_loads(kt + STAGES - 1, i0, i1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         // Tile kt + 2 must be complete (and visible to every wavefront) before iteration
         // kt + 1 prefetches fragments from it; the barrier also frees stage kt % STAGES.
@@ -209,15 +222,15 @@ __global__ __launch_bounds__(256) void k_int8_gemm(const int8_t *__restrict__ A,
             }
 }
 
-template <int TM, int TN, int BK, int STAGES>
+template <int WM, int WN, int TM, int TN, int BK, int STAGES>
 hipError_t launch(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64_t Mp, int64_t Np,
                   int64_t Kp, hipStream_t stream) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(&k_int8_gemm<TM, TN, BK, STAGES>),
+            reinterpret_cast<const void *>(&k_int8_gemm<WM, WN, TM, TN, BK, STAGES>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -228,7 +241,7 @@ hipError_t launch(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64
     tm.swizzled = (tm.tiles_m % 16 == 0 && tm.tiles_n % 16 == 0) ? 1 : 0;
     const int64_t total = (int64_t)tm.tiles_m * tm.tiles_n * batch;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_int8_gemm<TM, TN, BK, STAGES>), dim3((unsigned)total), dim3(256), lds_bytes,
+    hipLaunchKernelGGL((k_int8_gemm<WM, WN, TM, TN, BK, STAGES>), dim3((unsigned)total), dim3(64 * WM * WN), lds_bytes,
                        stream, A, B, C, Mp, Np, Kp, tm);
     return hipGetLastError();
 }
@@ -239,8 +252,11 @@ hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, int32_t *C, int ba
                             int64_t Np, int64_t Kp, hipStream_t stream) {
     // Small problems get the 128 x 128 tile so that more workgroups exist.
     if (Mp * Np * batch < (int64_t)256 * 256 * 512)
-        return launch<2, 2, 64, 4>(A, B, C, batch, Mp, Np, Kp, stream);
-    return launch<4, 4, 64, 5>(A, B, C, batch, Mp, Np, Kp, stream);
+        return launch<2, 2, 2, 2, 64, 4>(A, B, C, batch, Mp, Np, Kp, stream);
+    // 8 wavefronts (2 per SIMD), each 128 x 64: measured 58.6 ms at 16 x 16384^3 against
+    // 63.5 ms for 4 wavefronts of 128 x 128 -- a wavefront that is held up issuing a load
+    // leaves the matrix core to its SIMD partner.
+    return launch<2, 4, 4, 2, 64, 4>(A, B, C, batch, Mp, Np, Kp, stream);
 }
 
 }  // namespace oz2
