@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0          # MI355X dense INT8 MFMA, published
 HBM_PEAK_GBS = 8000.0
 
+# L2<->memory bytes per launch of k_int8_gemm from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script, scaled by what the counters read for `--stage copy` (x2.000 / x1.000); the
+# summary is profiles/oz2_dgemm_16384_N16_counters.txt.  Keyed by (dtype, m=n=k, N).
+MEASURED_GEMM_TRAFFIC_BYTES = {("f64", 16384, 16): 103.39e9 + 17.18e9}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -59,6 +64,29 @@ def gemm_only(oz, torch, size, N, args) -> int:
     return 0
 
 
+def copy_only(torch, args) -> int:
+    """A device-to-device copy of 4 GiB: reads 4 GiB and writes 4 GiB of HBM."""
+    nbytes = 4 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(args.warmup):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    gbs = 2.0 * nbytes / (ms * 1e-3) / 1e9
+    log(f"copy of {nbytes} B: {ms:.3f} ms, {gbs:.0f} GB/s read+write")
+    print(json.dumps({"stage": "copy", "bytes_read": nbytes, "bytes_written": nbytes,
+                      "ms_per_copy": ms, "GBps_read_plus_write": gbs, "steps": args.steps}),
+          flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,9 +97,10 @@ def main() -> int:
     ap.add_argument("--phi", type=float, default=0.5)
     ap.add_argument("--sgemm", action="store_true", help="FP32 emulation (oz2_sgemm)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--stage", choices=["all", "int8_gemm"], default="all",
-                    help="int8_gemm: time only the batched INT8 GEMM on random residues "
-                         "(for profiler runs); prints a reduced JSON line")
+    ap.add_argument("--stage", choices=["all", "int8_gemm", "copy"], default="all",
+                    help="int8_gemm: time only the batched INT8 GEMM on random residues; "
+                         "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
+                         "counters); both print a reduced JSON line")
     ap.add_argument("--cpu-block", type=int, default=1024,
                     help="the oracle is timed on C[0:b, 0:b] with the full k")
     args = ap.parse_args()
@@ -96,6 +125,8 @@ def main() -> int:
     N = args.moduli
     if args.stage == "int8_gemm":
         return gemm_only(oz, torch, m, N, args)
+    if args.stage == "copy":
+        return copy_only(torch, args)
     np_dt, t_dt = (np.float32, torch.float32) if args.sgemm else (np.float64, torch.float64)
     log(f"generating inputs {m}x{k}, {k}x{n} phi={args.phi} ...")
     t0 = time.time()
@@ -200,7 +231,8 @@ def main() -> int:
                    "num_moduli": N, "m": m, "n": n, "k": k, "phi": args.phi},
         "roofline": {"bound": "mfma", "kernel": "k_int8_gemm (batched over moduli)",
                      "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tops / INT8_PEAK_TOPS, "traffic": None,
+                     "frac": gemm_tops / INT8_PEAK_TOPS,
+                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(("f32" if args.sgemm else "f64", m, N)),
                      "ops_per_launch": gemm_ops, "avg_launch_ms": float(stage_ms[2]),
                      "note": "INT8 multiply-adds counted as 2 ops each, against the dense INT8 peak"},
         "stages": {"ms": {"shifts": float(stage_ms[0]), "residues": float(stage_ms[1]),
