@@ -166,7 +166,7 @@ def main() -> int:
     gemm_tops = gemm_ops / (stage_ms[2] * 1e-3) / 1e12
     E = 4 if args.sgemm else 8
     stage_bytes = [
-        E * (m * k + 3 * k * n) + 4 * (m + n),                  # shifts: A once, B read+written+read
+        E * (m * k + 2 * k * n) + 4 * (m + n),                  # shifts: A once, B twice (max, then sum)
         E * (m * k + k * n) + N * (Mp * Kp + Np * Kp),          # residues
         N * (Mp * Kp + Np * Kp) + 4 * N * Mp * Np,              # GEMM compulsory traffic
         4 * N * m * n + E * m * n,                              # epilogue

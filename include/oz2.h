@@ -70,8 +70,8 @@ oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha,
                      hipStream_t stream);
 
 /*
- * Workspace.  A call needs device scratch for the transposed copy of B, the
- * shift vectors, the INT8 residue slices of A and B (Algorithm 1 lines 4-5)
+ * Workspace.  A call needs device scratch for the shift vectors (and the
+ * per-column partial results behind them), the INT8 residue slices of A and B (Algorithm 1 lines 4-5)
  * and the INT32 products (line 6): oz2_workspace_bytes gives the size for a
  * problem (0 if the arguments are unsupported).  oz2_set_workspace hands the
  * library a caller-owned device buffer (kept, not freed, must stay valid until

@@ -23,12 +23,12 @@ struct Layout {
     size_t off_bt, off_ta, off_tb, off_ra, off_rb, off_prod, total;
 };
 
-Layout make_layout(int64_t m, int64_t n, int64_t k, int N, size_t elem) {
+Layout make_layout(int64_t m, int64_t n, int64_t k, int N) {
     Layout L{};
     L.m = m; L.n = n; L.k = k; L.N = N;
     L.Mp = round_up(m, kPadMN); L.Np = round_up(n, kPadMN); L.Kp = round_up(k, kPadK);
     size_t o = 0;
-    L.off_bt = o;   o += align256((size_t)n * k * elem);
+    L.off_bt = o;   o += align256(column_scratch_bytes(n));   // per-column max and sum of squares
     L.off_ta = o;   o += align256((size_t)m * 4);
     L.off_tb = o;   o += align256((size_t)n * 4);
     L.off_ra = o;   o += align256((size_t)N * L.Mp * L.Kp);
@@ -97,11 +97,11 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
     const Table &tab = table(N, is_double);
     const ModArgs ma = make_mod_args(tab);
     const ShiftArgs sa = make_shift_args(tab);
-    const Layout L = make_layout(m, n, k, N, sizeof(T));
+    const Layout L = make_layout(m, n, k, N);
     if (oz2_status st = ensure_workspace(L.total)) return st;
     g.last = L; g.have_last = true; g.ev_recorded = false;
 
-    T *Bt = reinterpret_cast<T *>(g.ws + L.off_bt);
+    void *col_scratch = g.ws + L.off_bt;
     int32_t *tA = reinterpret_cast<int32_t *>(g.ws + L.off_ta);
     int32_t *tB = reinterpret_cast<int32_t *>(g.ws + L.off_tb);
     int8_t *rA = reinterpret_cast<int8_t *>(g.ws + L.off_ra);
@@ -109,12 +109,11 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
     int32_t *prod = reinterpret_cast<int32_t *>(g.ws + L.off_prod);
 
     if (oz2_status st = mark(0, stream)) return st;
-    OZ2_TRY(launch_transpose<T>(B, ldb, k, n, Bt, stream));
     OZ2_TRY(launch_shifts<T>(A, lda, m, k, sa, tA, stream));
-    OZ2_TRY(launch_shifts<T>(Bt, k, n, k, sa, tB, stream));
+    OZ2_TRY(launch_shifts_cols<T>(B, ldb, k, n, sa, col_scratch, tB, stream));
     if (oz2_status st = mark(1, stream)) return st;
     OZ2_TRY(launch_residues<T>(A, lda, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
-    OZ2_TRY(launch_residues<T>(Bt, k, n, k, tB, ma, rB, L.Np, L.Kp, stream));
+    OZ2_TRY(launch_residues_cols<T>(B, ldb, k, n, tB, ma, rB, L.Np, L.Kp, stream));
     if (oz2_status st = mark(2, stream)) return st;
     OZ2_TRY(launch_int8_gemm(rA, rB, prod, N, L.Mp, L.Np, L.Kp, stream));
     if (oz2_status st = mark(3, stream)) return st;
@@ -143,7 +142,8 @@ oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha, const float *
 
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double) {
     if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
-    return make_layout(m, n, k, num_moduli, is_double ? 8 : 4).total;
+    (void)is_double;                                          // the workspace holds no input-typed data
+    return make_layout(m, n, k, num_moduli).total;
 }
 
 oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes) {

@@ -36,11 +36,6 @@ struct ShiftArgs {
 ModArgs make_mod_args(const Table &t);
 ShiftArgs make_shift_args(const Table &t);
 
-// out[c][r] = in[r][c]; in is rows x cols with leading dimension ld, out is cols x rows dense.
-template <typename T>
-hipError_t launch_transpose(const T *in, int64_t ld, int64_t rows, int64_t cols, T *out,
-                            hipStream_t stream);
-
 // Algorithm 1 line 1 (fast mode): one shift per row of X (rows x len, leading dimension ld).
 template <typename T>
 hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, const ShiftArgs &sa,
@@ -53,6 +48,19 @@ template <typename T>
 hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *t,
                            const ModArgs &ma, int8_t *out, int64_t rows_pad, int64_t len_pad,
                            hipStream_t stream);
+
+// The same two stages for the COLUMNS of X (rows x cols, leading dimension ld), reading X in
+// place: one shift per column, and residue slices of X transposed, K-blocked:
+// out[s][h / 64][c][h % 64] for c < cols_pad, h < rows_pad (zero beyond cols / rows).
+// scratch: column_scratch_bytes(cols) bytes of device memory, overwritten.
+size_t column_scratch_bytes(int64_t cols);
+template <typename T>
+hipError_t launch_shifts_cols(const T *X, int64_t ld, int64_t rows, int64_t cols,
+                              const ShiftArgs &sa, void *scratch, int32_t *t, hipStream_t stream);
+template <typename T>
+hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t cols, const int32_t *t,
+                                const ModArgs &ma, int8_t *out, int64_t cols_pad, int64_t rows_pad,
+                                hipStream_t stream);
 
 // Algorithm 1 line 6: C[b] = A[b] * B[b]^T for b < batch, int8 in, wrapping int32 out.
 // A: [batch][Kp/64][Mp][64], B: [batch][Kp/64][Np][64] (K-blocked, see launch_residues),

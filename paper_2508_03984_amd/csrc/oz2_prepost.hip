@@ -1,4 +1,4 @@
-// Bandwidth-bound kernels of the emulation for gfx950: transposition of B,
+// Bandwidth-bound kernels of the emulation for gfx950 (row side: A, and the output):
 // fast-mode shifts (Algorithm 1 line 1), residue slices (lines 2-5) and the fused
 // mod-reduce + CRT + unscale epilogue (lines 7-12).  64-wide wavefronts throughout.
 #include "oz2_kernels.hpp"
@@ -32,27 +32,6 @@ ShiftArgs make_shift_args(const Table &t) {
 namespace {
 
 constexpr int kWave = 64;
-
-// ----------------------------------------------------------------------------------------
-// Transpose (B is row-major k x n; everything downstream wants its columns contiguous).
-// ----------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void k_transpose(const T *__restrict__ in, int64_t ld,
-                                                   int64_t rows, int64_t cols,
-                                                   T *__restrict__ out) {
-    __shared__ T tile[64][65];
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;          // 64 x 4
-    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
-    for (int i = ty; i < 64; i += 4) {
-        int64_t r = r0 + i, c = c0 + tx;
-        tile[i][tx] = (r < rows && c < cols) ? in[r * ld + c] : T(0);
-    }
-    __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        int64_t c = c0 + i, r = r0 + tx;                              // out row = input column
-        if (c < cols && r < rows) out[c * rows + r] = tile[tx][i];
-    }
-}
 
 // ----------------------------------------------------------------------------------------
 // Shifts.  One workgroup per row: pass 1 finds max|x| (as an integer compare of the FP64
@@ -265,14 +244,6 @@ inline unsigned blocks_for(int64_t threads) { return (unsigned)((threads + 255) 
 }  // namespace
 
 template <typename T>
-hipError_t launch_transpose(const T *in, int64_t ld, int64_t rows, int64_t cols, T *out,
-                            hipStream_t stream) {
-    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64));
-    hipLaunchKernelGGL((k_transpose<T>), grid, dim3(256), 0, stream, in, ld, rows, cols, out);
-    return hipGetLastError();
-}
-
-template <typename T>
 hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, const ShiftArgs &sa,
                          int32_t *t, hipStream_t stream) {
     hipLaunchKernelGGL((k_shifts<T>), dim3((unsigned)rows), dim3(256), 0, stream, X, ld, len, sa, t);
@@ -312,8 +283,6 @@ hipError_t launch_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n, double bet
 }
 
 #define OZ2_INSTANTIATE(T)                                                                        \
-    template hipError_t launch_transpose<T>(const T *, int64_t, int64_t, int64_t, T *,           \
-                                            hipStream_t);                                         \
     template hipError_t launch_shifts<T>(const T *, int64_t, int64_t, int64_t, const ShiftArgs &, \
                                          int32_t *, hipStream_t);                                 \
     template hipError_t launch_residues<T>(const T *, int64_t, int64_t, int64_t, const int32_t *, \
