@@ -87,6 +87,71 @@ def copy_only(torch, args) -> int:
     return 0
 
 
+SWEEPS = {
+    # the parity-test configurations of the benchmark set, timed: (m, n, k, phi, fp64?, moduli)
+    "dgemm_4096": [(4096, 4096, 4096, 0.5, True, list(range(12, 21)))],
+    "dgemm_16384": [(16384, 16384, 16384, phi, True, [16, 17, 18, 19, 20]) for phi in (0.5, 1.0, 2.0)],
+    "sgemm": [(8192, 8192, 8192, 0.5, False, [5, 6, 7, 8, 9]),
+              (16384, 16384, 16384, 0.5, False, [5, 6, 7, 8, 9])],
+    "nonsquare": [(8192, 8192, 65536, 1.0, True, [18])],
+}
+
+
+def sweep(oz, torch, name, args) -> int:
+    """Times oz2_dgemm / oz2_sgemm over the moduli counts of a configuration and measures the
+    error of each result (and of the native GEMM) against a double-double product on three
+    sampled rows.  One JSON line per (shape, phi, N) goes to gpurun_out/sweep_<name>.jsonl."""
+    import numpy as np
+    import synth_inputs as S
+    from oracle import oz2_oracle as O              # reference leg only
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    path = os.path.join(ROOT, "gpurun_out", f"sweep_{name}.jsonl")
+    with open(path, "w") as f:
+        for (m, n, k, phi, is_double, moduli) in SWEEPS[name]:
+            np_dt, t_dt = (np.float64, torch.float64) if is_double else (np.float32, torch.float32)
+            A, B = S.gemm_inputs(m, n, k, phi, seed=0, dtype=np_dt)
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+            dC = torch.empty((m, n), dtype=t_dt, device="cuda")
+            rows = np.array([0, m // 3, m - 1])
+            trows = torch.from_numpy(rows).cuda()
+            hi, lo, ab = O.dd_rows(A.astype(np.float64), B.astype(np.float64), rows)
+            err = lambda c: float(np.max(np.abs((c.astype(np.float64) - hi) - lo) / ab))
+            torch.mm(dA, dB, out=dC)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(3):
+                torch.mm(dA, dB, out=dC)
+            torch.cuda.synchronize()
+            native_tflops = 2.0 * m * n * k / ((time.perf_counter() - t1) / 3) / 1e12
+            native_err = err(dC[trows].cpu().numpy())
+            fn = oz.oz2_dgemm if is_double else oz.oz2_sgemm
+            for N in moduli:
+                for _ in range(args.warmup):
+                    fn(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N)
+                torch.cuda.synchronize()
+                oz.oz2_set_profiling(True)
+                stage_ms = np.zeros(4)
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    fn(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N)
+                    stage_ms += np.array(oz.oz2_last_stage_times_ms())
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) / args.steps
+                oz.oz2_set_profiling(False)
+                rec = {"m": m, "n": n, "k": k, "phi": phi, "dtype": "f64" if is_double else "f32",
+                       "num_moduli": N, "ms": 1e3 * dt, "emulated_tflops": 2.0 * m * n * k / dt / 1e12,
+                       "stage_ms": (stage_ms / args.steps).round(3).tolist(),
+                       "err_emulated": err(dC[trows].cpu().numpy()), "native_tflops": native_tflops,
+                       "err_native": native_err}
+                log(json.dumps(rec))
+                f.write(json.dumps(rec) + "\n")
+                f.flush()
+            del dA, dB, dC
+    print(json.dumps({"sweep": name, "file": path}), flush=True)
+    oz.oz2_release()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -101,6 +166,9 @@ def main() -> int:
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
                          "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
                          "counters); both print a reduced JSON line")
+    ap.add_argument("--sweep", choices=sorted(SWEEPS), default=None,
+                    help="time a whole configuration of the benchmark set over its moduli counts; "
+                         "lines go to gpurun_out/sweep_<name>.jsonl")
     ap.add_argument("--cpu-block", type=int, default=1024,
                     help="the oracle is timed on C[0:b, 0:b] with the full k")
     args = ap.parse_args()
@@ -123,6 +191,8 @@ def main() -> int:
 
     m = n = k = args.size
     N = args.moduli
+    if args.sweep:
+        return sweep(oz, torch, args.sweep, args)
     if args.stage == "int8_gemm":
         return gemm_only(oz, torch, m, N, args)
     if args.stage == "copy":
