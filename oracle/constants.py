@@ -21,6 +21,8 @@ Every quantity follows Section 4.1 ("Determination of Constants") of the paper:
 * P'_fast         single(0.5*log2(P-1) - 1.5); the printed formula lacks the
                   factor 0.5, without which Eq. 3 cannot hold (the bound
                   2*mu*|a|*nu*|b| <= 2*2^(2P') must stay below P)
+* P'_accu         single(0.5*log2(P-1) - 0.5), with the same factor 0.5: it makes the
+                  accurate-mode bound exactly 2*2^(2P') = P-1 < P
 * pinv'_i         floor(2^32/p_i - 1), the multiplier of the mulhi reduction
                   (Section 4.3)
 
@@ -80,6 +82,7 @@ class Constants:
     P2: float
     Pinv: float
     Pfast: float          # binary32 value widened to double
+    Paccu: float          # single(0.5*log2(P-1) - 0.5), same reading as P'_fast
     pinv_prime: List[int]
 
 
@@ -94,6 +97,7 @@ def constants(n: int, is_double: bool = True) -> Constants:
     P1 = float(P)                       # int -> float is correctly rounded
     Pinv = float(Fraction(1, P))        # Fraction -> float is correctly rounded
     Pfast = _to_f32(0.5 * math.log2(P - 1) - 1.5)
+    Paccu = _to_f32(0.5 * math.log2(P - 1) - 0.5)
     pinv_prime = [(1 << 32) // pi - 1 for pi in p]
 
     if is_double:
@@ -114,4 +118,4 @@ def constants(n: int, is_double: bool = True) -> Constants:
         s1 = [float(wi) for wi in w]
         s2 = [0.0] * n
     return Constants(n, is_double, p, P, q, w, beta, s1, s2, P1, P2, Pinv,
-                     Pfast, pinv_prime)
+                     Pfast, Paccu, pinv_prime)

@@ -10,6 +10,8 @@
  *
  * Stages (numbering of Algorithm 1, Section 4):
  *   line 1      oz2o_shifts            fast-mode scale vectors (Section 4.2)
+ *               oz2o_accu_prescale /   accurate-mode scale vectors (Section 4.2)
+ *               oz2o_accu_shifts
  *   lines 2-5   oz2o_residues          trunc(scaled) and rmod(., p_s) as int8
  *   line 6      oz2o_int8_gemm_rows /  int8 x int8 products, wrapping int32 sums
  *               oz2o_int8_gemm_entries
@@ -87,6 +89,54 @@ void oz2o_shifts(const double *X, int64_t nv, int64_t len, int64_t stride_v,
         t[v] = (int32_t)f - e;
         if (e_out) e_out[v] = e;
         if (T_out) T_out[v] = T;
+    }
+}
+
+
+/* ------------------------------------------------------------------------- */
+/* Accurate mode (Section 4.2, second half).                                  */
+/*   mu'_i = 2^(5 - floor(log2 max_h |a_ih|)),  abar_ih = ceil(mu'_i |a_ih|)   */
+/* (an integer in [0, 64], so it fits INT8), likewise nu'_j and bbar for the   */
+/* columns of B.  oz2o_accu_prescale writes e = floor(log2 max) per vector    */
+/* (0 for an all-zero vector) and the 7-bit matrix, vector-major [nv][len].   */
+/* ------------------------------------------------------------------------- */
+void oz2o_accu_prescale(const double *X, int64_t nv, int64_t len, int64_t stride_v,
+                        int64_t stride_h, int32_t *e_out, int8_t *bar)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < nv; ++v) {
+        const double *x = X + v * stride_v;
+        double amax = 0.0;
+        for (int64_t h = 0; h < len; ++h) {
+            double a = fabs(x[h * stride_h]);
+            if (a > amax) amax = a;
+        }
+        int e = 0;
+        if (amax != 0.0) {
+            int ex;
+            (void)frexp(amax, &ex);
+            e = ex - 1;
+        }
+        e_out[v] = e;
+        for (int64_t h = 0; h < len; ++h)
+            bar[v * len + h] = (int8_t)ceil(ldexp(fabs(x[h * stride_h]), 5 - e));
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Accurate-mode shifts from the row (column) maxima of Cbar = Abar * Bbar:    */
+/*   mu_i = mu'_i * 2^floor(P'_accu - 0.51 log2 max_h cbar_ih)                 */
+/* i.e. t_i = (5 - e_i) + floor(P'_accu - 0.51 log2 cmax_i).  A vector whose   */
+/* own entries are all zero gets shift 0; a maximum of 0 that comes from the  */
+/* OTHER matrix being zero is taken as 1 (any shift is valid then).           */
+/* ------------------------------------------------------------------------- */
+void oz2o_accu_shifts(const int32_t *e, const int64_t *cmax, const uint8_t *is_zero,
+                      int64_t nv, double Paccu, int32_t *t)
+{
+    for (int64_t v = 0; v < nv; ++v) {
+        if (is_zero[v]) { t[v] = 0; continue; }
+        double c = cmax[v] > 0 ? (double)cmax[v] : 1.0;
+        t[v] = (5 - e[v]) + (int32_t)floor(Paccu - 0.51 * log2(c));
     }
 }
 

@@ -201,16 +201,52 @@ def dd_rows(A: np.ndarray, B: np.ndarray, rows: np.ndarray):
     return hi, lo, ab
 
 
-def prepare(A: np.ndarray, B: np.ndarray, num_moduli: int, is_double: bool = True) -> Dict:
-    """Algorithm 1 lines 1-5 on the whole of A and B."""
+def accu_prescale(X: np.ndarray, axis: int):
+    """Accurate mode: (e, 7-bit matrix ceil(|x| 2^(5-e)) as int8 [nv][len])."""
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    nv, ln, sv, sh = _strides(X, axis)
+    e = np.zeros(nv, np.int32)
+    bar = np.empty((nv, ln), np.int8)
+    _load().oz2o_accu_prescale(_p(X), _i64(nv), _i64(ln), _i64(sv), _i64(sh), _p(e), _p(bar))
+    return e, bar
+
+
+def accu_shifts(A64: np.ndarray, B64: np.ndarray, Paccu: float) -> Dict:
+    """Accurate-mode scale vectors of Section 4.2: Cbar = Abar Bbar, then the shifts from its
+    row and column maxima.  The product is a library matmul in FP64, which is exact here
+    (entries are integers below 2^29)."""
+    eA, Abar = accu_prescale(A64, 0)
+    eB, Bbar = accu_prescale(B64, 1)
+    Cbar = np.matmul(Abar.astype(np.float64), Bbar.astype(np.float64).T)
+    rmax = Cbar.max(axis=1).astype(np.int64) if Cbar.size else np.zeros(A64.shape[0], np.int64)
+    cmax = Cbar.max(axis=0).astype(np.int64) if Cbar.size else np.zeros(B64.shape[1], np.int64)
+    zA = np.ascontiguousarray(~A64.any(axis=1), dtype=np.uint8)
+    zB = np.ascontiguousarray(~B64.any(axis=0), dtype=np.uint8)
+    tA = np.zeros(A64.shape[0], np.int32)
+    tB = np.zeros(B64.shape[1], np.int32)
+    lib = _load()
+    lib.oz2o_accu_shifts(_p(eA), _p(rmax), _p(zA), _i64(tA.size), C.c_double(Paccu), _p(tA))
+    lib.oz2o_accu_shifts(_p(eB), _p(cmax), _p(zB), _i64(tB.size), C.c_double(Paccu), _p(tB))
+    return dict(tA=tA, tB=tB, eA=eA, eB=eB, Abar=Abar, Bbar=Bbar, rmax=rmax, cmax=cmax)
+
+
+def prepare(A: np.ndarray, B: np.ndarray, num_moduli: int, is_double: bool = True,
+            accurate: bool = False) -> Dict:
+    """Algorithm 1 lines 1-5 on the whole of A and B (fast or accurate scale vectors)."""
     c = K.constants(num_moduli, is_double)
     A64 = np.ascontiguousarray(A, dtype=np.float64)
     B64 = np.ascontiguousarray(B, dtype=np.float64)
-    tA, eA, TA = shifts(A64, 0, c.Pfast)
-    tB, eB, TB = shifts(B64, 1, c.Pfast)
-    Ares = residues(A64, 0, tA, c.p)
-    Bres = residues(B64, 1, tB, c.p)
-    return dict(consts=c, tA=tA, tB=tB, eA=eA, eB=eB, TA=TA, TB=TB, Ares=Ares, Bres=Bres)
+    if accurate:
+        out = accu_shifts(A64, B64, c.Paccu)
+        tA, tB = out["tA"], out["tB"]
+    else:
+        tA, eA, TA = shifts(A64, 0, c.Pfast)
+        tB, eB, TB = shifts(B64, 1, c.Pfast)
+        out = dict(tA=tA, tB=tB, eA=eA, eB=eB, TA=TA, TB=TB)
+    out["consts"] = c
+    out["Ares"] = residues(A64, 0, tA, c.p)
+    out["Bres"] = residues(B64, 1, tB, c.p)
+    return out
 
 
 def finish_rows(prep: Dict, rows: np.ndarray, alpha=1.0, beta=0.0,
@@ -243,9 +279,9 @@ def finish_entries(prep: Dict, ii, jj, alpha=1.0, beta=0.0, Cin=None) -> Dict:
 
 
 def gemm(A: np.ndarray, B: np.ndarray, num_moduli: int, alpha=1.0, beta=0.0,
-         Cin: Optional[np.ndarray] = None, is_double: bool = True) -> Dict:
+         Cin: Optional[np.ndarray] = None, is_double: bool = True, accurate: bool = False) -> Dict:
     """The whole of Algorithm 1; returns every stage."""
-    prep = prepare(A, B, num_moduli, is_double)
+    prep = prepare(A, B, num_moduli, is_double, accurate)
     rows = np.arange(np.asarray(A).shape[0], dtype=np.int64)
     fin = finish_rows(prep, rows, alpha, beta, Cin)
     prep.update(fin)
