@@ -94,6 +94,8 @@ SWEEPS = {
     "sgemm": [(8192, 8192, 8192, 0.5, False, [5, 6, 7, 8, 9]),
               (16384, 16384, 16384, 0.5, False, [5, 6, 7, 8, 9])],
     "nonsquare": [(8192, 8192, 65536, 1.0, True, [18])],
+    # fast against accurate mode on inputs with a wide exponent range
+    "modes": [(8192, 8192, 8192, phi, True, [14, 15, 16, 17, 18]) for phi in (0.5, 2.0, 4.0)],
 }
 
 
@@ -124,8 +126,12 @@ def sweep(oz, torch, name, args) -> int:
             torch.cuda.synchronize()
             native_tflops = 2.0 * m * n * k / ((time.perf_counter() - t1) / 3) / 1e12
             native_err = err(dC[trows].cpu().numpy())
-            fn = oz.oz2_dgemm if is_double else oz.oz2_sgemm
-            for N in moduli:
+            modes = [False, True] if name == "modes" else [args.accurate]
+            for N, accurate in [(N, a) for N in moduli for a in modes]:
+                if accurate:
+                    fn = oz.oz2_dgemm_accurate if is_double else oz.oz2_sgemm_accurate
+                else:
+                    fn = oz.oz2_dgemm if is_double else oz.oz2_sgemm
                 for _ in range(args.warmup):
                     fn(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N)
                 torch.cuda.synchronize()
@@ -139,7 +145,7 @@ def sweep(oz, torch, name, args) -> int:
                 dt = (time.perf_counter() - t0) / args.steps
                 oz.oz2_set_profiling(False)
                 rec = {"m": m, "n": n, "k": k, "phi": phi, "dtype": "f64" if is_double else "f32",
-                       "num_moduli": N, "ms": 1e3 * dt, "emulated_tflops": 2.0 * m * n * k / dt / 1e12,
+                       "mode": "accurate" if accurate else "fast", "num_moduli": N, "ms": 1e3 * dt, "emulated_tflops": 2.0 * m * n * k / dt / 1e12,
                        "stage_ms": (stage_ms / args.steps).round(3).tolist(),
                        "err_emulated": err(dC[trows].cpu().numpy()), "native_tflops": native_tflops,
                        "err_native": native_err}
@@ -161,6 +167,8 @@ def main() -> int:
     ap.add_argument("--moduli", type=int, default=16)
     ap.add_argument("--phi", type=float, default=0.5)
     ap.add_argument("--sgemm", action="store_true", help="FP32 emulation (oz2_sgemm)")
+    ap.add_argument("--accurate", action="store_true",
+                    help="accurate mode of Section 4.2 (oz2_dgemm_accurate / oz2_sgemm_accurate)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage", choices=["all", "int8_gemm", "copy"], default="all",
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
@@ -204,7 +212,10 @@ def main() -> int:
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     dC = torch.empty((m, n), dtype=t_dt, device="cuda")
     log(f"  done in {time.time() - t0:.1f}s")
-    fn = oz.oz2_sgemm if args.sgemm else oz.oz2_dgemm
+    if args.accurate:
+        fn = oz.oz2_sgemm_accurate if args.sgemm else oz.oz2_dgemm_accurate
+    else:
+        fn = oz.oz2_sgemm if args.sgemm else oz.oz2_dgemm
     stream = torch.cuda.current_stream()
 
     def step():
@@ -273,7 +284,7 @@ def main() -> int:
         b = min(args.cpu_block, m)
         As, Bs = np.ascontiguousarray(A[:b, :]), np.ascontiguousarray(B[:, :b])
         t2 = time.perf_counter()
-        ref = O.gemm(As, Bs, N, is_double=not args.sgemm)
+        ref = O.gemm(As, Bs, N, is_double=not args.sgemm, accurate=args.accurate)
         dt = time.perf_counter() - t2
         cpu = {"value": 2.0 * b * b * k / dt / 1e12, "unit": "TFLOP/s", "cores": O.num_threads(),
                "kind": "oracle",
@@ -283,8 +294,9 @@ def main() -> int:
         r = ref["C"].astype(np.float64)
         # shifts of B's columns and A's rows do not depend on the other rows/columns, so the
         # sub-block of the full GPU result must equal the oracle's result on the sub-problem
-        cpu["gpu_vs_oracle_max_rel_diff"] = float(
-            np.max(np.abs(sub - r) / np.where(r == 0, 1.0, np.abs(r))))
+        if not args.accurate:                   # accurate-mode shifts depend on all of A and B
+            cpu["gpu_vs_oracle_max_rel_diff"] = float(
+                np.max(np.abs(sub - r) / np.where(r == 0, 1.0, np.abs(r))))
         log(f"cpu oracle {cpu}")
 
     out = {
@@ -297,7 +309,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{'SGEMM' if args.sgemm else 'DGEMM'} emulation m=n=k={m}, "
                                f"{'fp32' if args.sgemm else 'fp64'} row-major, phi={args.phi}, "
-                               f"seed 0/1, fast mode, N={N} moduli, alpha=1 beta=0",
+                               f"seed 0/1, {'accurate' if args.accurate else 'fast'} mode, N={N} moduli, "
+                               f"alpha=1 beta=0",
                    "num_moduli": N, "m": m, "n": n, "k": k, "phi": args.phi},
         "roofline": {"bound": "mfma", "kernel": "k_int8_gemm (batched over moduli)",
                      "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",

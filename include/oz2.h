@@ -70,6 +70,26 @@ oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha,
                      hipStream_t stream);
 
 /*
+ * The same product with the scale vectors of ACCURATE mode (Section 4.2, second half):
+ * A and B are first reduced to 7-bit matrices Abar = ceil(mu' |A|), Bbar = ceil(|B| nu')
+ * (mu', nu' powers of two that bring each row / column maximum into [32, 64)), their
+ * product Cbar is formed on the INT8 matrix cores, and its row and column maxima bound
+ * sum_h |a_ih||b_hj| directly instead of through the Cauchy-Schwarz inequality.  This costs
+ * one more INT8 GEMM and gives larger scale factors, i.e. a smaller truncation error for
+ * the same number of moduli (it matters for inputs with a wide exponent range).
+ * Arguments, conventions and errors are those of oz2_dgemm / oz2_sgemm.
+ */
+oz2_status oz2_dgemm_accurate(int64_t m, int64_t n, int64_t k, double alpha,
+                              const double *A, int64_t lda, const double *B, int64_t ldb,
+                              double beta, double *C, int64_t ldc, int num_moduli,
+                              hipStream_t stream);
+
+oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha,
+                              const float *A, int64_t lda, const float *B, int64_t ldb,
+                              float beta, float *C, int64_t ldc, int num_moduli,
+                              hipStream_t stream);
+
+/*
  * Workspace.  A call needs device scratch for the shift vectors (and the
  * per-column partial results behind them), the INT8 residue slices of A and B (Algorithm 1 lines 4-5)
  * and the INT32 products (line 6): oz2_workspace_bytes gives the size for a
@@ -102,9 +122,18 @@ oz2_status oz2_constants(int num_moduli, int is_double, int32_t *p, uint32_t *pi
  * T = sum_h ceil(|x_h| 2^(15-e))^2, the scaled row has exponent
  * f = floor(P'_fast - max(1, 0.51 log2(T 2^-30))) and shift t = f - e.  The
  * kernels find f by comparing T with a table: f = f_max - min{ j : T <= theta[j] }.
- * This call writes f_max, the number of levels (<= 16) and theta[] to HOST memory.
+ * This call writes f_max, the number of levels (<= 20) and theta[] to HOST memory.
  */
 oz2_status oz2_shift_table(int num_moduli, int32_t *f_max, int32_t *levels, uint64_t *theta);
+
+/*
+ * The accurate-mode counterpart: P'_accu (binary32) and the table for
+ * f = floor(P'_accu - 0.51 log2 c) over the integer c = maximum of a row or column of Cbar
+ * (1 <= c <= 2^29): f = f_max - min{ j : c <= theta[j] }; the shift is t = (5 - e) + f.
+ * Writes to HOST memory; theta needs room for 20 entries.
+ */
+oz2_status oz2_shift_table_accurate(int num_moduli, float *Paccu, int32_t *f_max, int32_t *levels,
+                                    uint64_t *theta);
 
 /*
  * Diagnostics: where the stages of the most recent oz2_dgemm / oz2_sgemm call

@@ -211,6 +211,16 @@ def accu_prescale(X: np.ndarray, axis: int):
     return e, bar
 
 
+def accu_shift_from_max(e, cmax, Paccu: float, is_zero=None) -> np.ndarray:
+    """t = (5 - e) + floor(P'_accu - 0.51 log2 max(c, 1)) per vector (0 for zero vectors)."""
+    e = np.ascontiguousarray(e, np.int32)
+    cmax = np.ascontiguousarray(cmax, np.int64)
+    z = np.zeros(e.size, np.uint8) if is_zero is None else np.ascontiguousarray(is_zero, np.uint8)
+    t = np.zeros(e.size, np.int32)
+    _load().oz2o_accu_shifts(_p(e), _p(cmax), _p(z), _i64(e.size), C.c_double(Paccu), _p(t))
+    return t
+
+
 def accu_shifts(A64: np.ndarray, B64: np.ndarray, Paccu: float) -> Dict:
     """Accurate-mode scale vectors of Section 4.2: Cbar = Abar Bbar, then the shifts from its
     row and column maxima.  The product is a library matmul in FP64, which is exact here
@@ -222,11 +232,8 @@ def accu_shifts(A64: np.ndarray, B64: np.ndarray, Paccu: float) -> Dict:
     cmax = Cbar.max(axis=0).astype(np.int64) if Cbar.size else np.zeros(B64.shape[1], np.int64)
     zA = np.ascontiguousarray(~A64.any(axis=1), dtype=np.uint8)
     zB = np.ascontiguousarray(~B64.any(axis=0), dtype=np.uint8)
-    tA = np.zeros(A64.shape[0], np.int32)
-    tB = np.zeros(B64.shape[1], np.int32)
-    lib = _load()
-    lib.oz2o_accu_shifts(_p(eA), _p(rmax), _p(zA), _i64(tA.size), C.c_double(Paccu), _p(tA))
-    lib.oz2o_accu_shifts(_p(eB), _p(cmax), _p(zB), _i64(tB.size), C.c_double(Paccu), _p(tB))
+    tA = accu_shift_from_max(eA, rmax, Paccu, zA)
+    tB = accu_shift_from_max(eB, cmax, Paccu, zB)
     return dict(tA=tA, tB=tB, eA=eA, eB=eB, Abar=Abar, Bbar=Bbar, rmax=rmax, cmax=cmax)
 
 

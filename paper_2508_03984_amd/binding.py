@@ -16,7 +16,8 @@ _lib = None
 OZ2_STAGE_SHIFT_A, OZ2_STAGE_SHIFT_B, OZ2_STAGE_RES_A, OZ2_STAGE_RES_B, OZ2_STAGE_PROD = range(5)
 
 EXPORTS = [
-    "oz2_dgemm", "oz2_sgemm", "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
+    "oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate", "oz2_shift_table_accurate",
+    "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
     "oz2_constants", "oz2_shift_table", "oz2_stage_ptr", "oz2_int8_gemm", "oz2_set_profiling",
     "oz2_last_stage_times_ms", "oz2_status_string",
 ]
@@ -51,6 +52,9 @@ def load():
     i64, dbl, flt, vp, ci = C.c_int64, C.c_double, C.c_float, C.c_void_p, C.c_int
     lib.oz2_dgemm.argtypes = [i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, ci, vp]
     lib.oz2_sgemm.argtypes = [i64, i64, i64, flt, vp, i64, vp, i64, flt, vp, i64, ci, vp]
+    lib.oz2_dgemm_accurate.argtypes = lib.oz2_dgemm.argtypes
+    lib.oz2_sgemm_accurate.argtypes = lib.oz2_sgemm.argtypes
+    lib.oz2_shift_table_accurate.argtypes = [ci, vp, vp, vp, vp]
     lib.oz2_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     lib.oz2_workspace_bytes.restype = C.c_size_t
     lib.oz2_set_workspace.argtypes = [vp, C.c_size_t]
@@ -65,7 +69,8 @@ def load():
     lib.oz2_last_stage_times_ms.argtypes = [C.POINTER(flt)]
     lib.oz2_status_string.argtypes = [ci]
     lib.oz2_status_string.restype = C.c_char_p
-    for name in ("oz2_dgemm", "oz2_sgemm", "oz2_set_workspace", "oz2_constants", "oz2_shift_table",
+    for name in ("oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate",
+                 "oz2_shift_table_accurate", "oz2_set_workspace", "oz2_constants", "oz2_shift_table",
                  "oz2_stage_ptr", "oz2_int8_gemm", "oz2_last_stage_times_ms"):
         getattr(lib, name).restype = ci
     _lib = lib
@@ -114,6 +119,31 @@ def oz2_sgemm(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=
                             int(num_moduli), _stream(stream)), "oz2_sgemm")
 
 
+def oz2_dgemm_accurate(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=None) -> None:
+    import torch
+    _check(load().oz2_dgemm_accurate(m, n, k, float(alpha), _dev(A, torch.float64), lda,
+                                     _dev(B, torch.float64), ldb, float(beta),
+                                     _dev(C_, torch.float64), ldc, int(num_moduli), _stream(stream)),
+           "oz2_dgemm_accurate")
+
+
+def oz2_sgemm_accurate(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=None) -> None:
+    import torch
+    _check(load().oz2_sgemm_accurate(m, n, k, float(alpha), _dev(A, torch.float32), lda,
+                                     _dev(B, torch.float32), ldb, float(beta),
+                                     _dev(C_, torch.float32), ldc, int(num_moduli), _stream(stream)),
+           "oz2_sgemm_accurate")
+
+
+def oz2_shift_table_accurate(num_moduli: int) -> dict:
+    import numpy as np
+    pa = np.zeros(1, np.float32); f = np.zeros(1, np.int32); lv = np.zeros(1, np.int32)
+    th = np.zeros(20, np.uint64)
+    _check(load().oz2_shift_table_accurate(int(num_moduli), pa.ctypes.data, f.ctypes.data,
+                                           lv.ctypes.data, th.ctypes.data), "oz2_shift_table_accurate")
+    return dict(Paccu=float(pa[0]), f_max=int(f[0]), levels=int(lv[0]), theta=th[:int(lv[0])].copy())
+
+
 def oz2_workspace_bytes(m, n, k, num_moduli, is_double=True) -> int:
     return int(load().oz2_workspace_bytes(m, n, k, int(num_moduli), int(bool(is_double))))
 
@@ -146,7 +176,7 @@ def oz2_constants(num_moduli: int, is_double: bool = True) -> dict:
 
 def oz2_shift_table(num_moduli: int) -> dict:
     import numpy as np
-    f = np.zeros(1, np.int32); lv = np.zeros(1, np.int32); th = np.zeros(16, np.uint64)
+    f = np.zeros(1, np.int32); lv = np.zeros(1, np.int32); th = np.zeros(20, np.uint64)
     _check(load().oz2_shift_table(int(num_moduli), f.ctypes.data, lv.ctypes.data, th.ctypes.data),
            "oz2_shift_table")
     return dict(f_max=int(f[0]), levels=int(lv[0]), theta=th[:int(lv[0])].copy())
@@ -213,8 +243,10 @@ def block_slices(t):
     return t.reshape(n, r, k // 64, 64).permute(0, 2, 1, 3).contiguous()
 
 
-def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=None, stream=None):
-    """C = alpha * A @ B + beta * out for row-major device tensors, via oz2_dgemm / oz2_sgemm."""
+def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=None, stream=None,
+           accurate: bool = False):
+    """C = alpha * A @ B + beta * out for row-major device tensors, via oz2_dgemm / oz2_sgemm
+    (or their _accurate forms)."""
     import torch
     if A.dim() != 2 or B.dim() != 2 or A.shape[1] != B.shape[0] or A.dtype != B.dtype:
         raise ValueError("A (m x k) and B (k x n) of one dtype expected")
@@ -229,6 +261,9 @@ def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=Non
     lda = A.stride(0) if m > 1 else max(k, 1)
     ldb = B.stride(0) if k > 1 else max(n, 1)
     ldc = out.stride(0) if m > 1 else max(n, 1)
-    fn = oz2_dgemm if A.dtype == torch.float64 else oz2_sgemm
+    if accurate:
+        fn = oz2_dgemm_accurate if A.dtype == torch.float64 else oz2_sgemm_accurate
+    else:
+        fn = oz2_dgemm if A.dtype == torch.float64 else oz2_sgemm
     fn(m, n, k, alpha, A, lda, B, ldb, beta, out, ldc, num_moduli, stream)
     return out

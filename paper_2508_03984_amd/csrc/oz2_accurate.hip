@@ -1,0 +1,161 @@
+// Accurate mode of Section 4.2: the scale vectors come from the row and column maxima of
+// Cbar = Abar * Bbar, where Abar = ceil(mu' |A|) and Bbar = ceil(|B| nu') are 7-bit
+// matrices (mu'_i = 2^(5 - floor(log2 max_h |a_ih|)), likewise nu'_j) and the product runs
+// on the INT8 matrix cores like every other slice.  Everything here is integer or exact
+// power-of-two arithmetic, so the shifts are bit-reproducible; the floor(P'_accu - 0.51 log2 c)
+// of the paper is a table lookup on the integer maximum c (built on the host from that
+// formula, see oz2_constants.cpp).
+#include "oz2_kernels.hpp"
+
+namespace oz2 {
+namespace {
+
+__device__ inline uint64_t wave_max_u64(uint64_t v) {
+    for (int off = 32; off > 0; off >>= 1) {
+        uint64_t o = __shfl_xor(v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// rowmax[r] = max_h bits(|X[r][h]|): one workgroup per row.
+template <typename T>
+__global__ __launch_bounds__(256) void k_row_maxbits(const T *__restrict__ X, int64_t ld,
+                                                     int64_t len, unsigned long long *rowmax) {
+    __shared__ uint64_t part[4];
+    const T *x = X + (int64_t)blockIdx.x * ld;
+    uint64_t mx = 0;
+    for (int64_t h = threadIdx.x; h < len; h += 256) {
+        uint64_t b = (uint64_t)__double_as_longlong(fabs((double)x[h]));
+        mx = b > mx ? b : mx;
+    }
+    mx = wave_max_u64(mx);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) mx = part[w] > mx ? part[w] : mx;
+        rowmax[blockIdx.x] = mx;
+    }
+}
+
+// pre[v] = 5 - floor(log2 max) (0 for an all-zero vector: its magnitudes are all 0 anyway).
+__global__ __launch_bounds__(256) void k_preshift(const unsigned long long *__restrict__ maxbits,
+                                                  int64_t count, int32_t *__restrict__ pre) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const uint64_t b = maxbits[i];
+    pre[i] = b ? 5 - floor_log2_of_bits(b) : 0;
+}
+
+__global__ __launch_bounds__(256) void k_fill_i32(int32_t *p, int64_t count, int32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = v;
+}
+
+// rmax[i] = max_j Cbar[i][j] over j < n: one workgroup per row.  Entries are >= 0.
+__global__ __launch_bounds__(256) void k_row_max_i32(const int32_t *__restrict__ Cbar, int64_t ld,
+                                                     int64_t n, int32_t *__restrict__ rmax) {
+    __shared__ int part[4];
+    const int32_t *x = Cbar + (int64_t)blockIdx.x * ld;
+    int mx = 0;
+    for (int64_t j = threadIdx.x; j < n; j += 256) mx = x[j] > mx ? x[j] : mx;
+    for (int off = 32; off > 0; off >>= 1) {
+        int o = __shfl_xor(mx, off, 64);
+        mx = o > mx ? o : mx;
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) mx = part[w] > mx ? part[w] : mx;
+        rmax[blockIdx.x] = mx;
+    }
+}
+
+// cmax[j] = max_i Cbar[i][j] over i < m: (256 columns x 256 rows) per workgroup, atomicMax.
+__global__ __launch_bounds__(256) void k_col_max_i32(const int32_t *__restrict__ Cbar, int64_t ld,
+                                                     int64_t m, int64_t n, int *cmax) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const int64_t i0 = (int64_t)blockIdx.y * 256;
+    const int64_t i1 = i0 + 256 < m ? i0 + 256 : m;
+    int mx = 0;
+#pragma unroll 8
+    for (int64_t i = i0; i < i1; ++i) {
+        int v = Cbar[i * ld + j];
+        mx = v > mx ? v : mx;
+    }
+    if (mx) atomicMax(&cmax[j], mx);
+}
+
+// t[v] = (5 - e_v) + floor(P'_accu - 0.51 log2 max(c_v, 1)); an all-zero vector gets 0.
+__global__ __launch_bounds__(256) void k_accu_finish(const unsigned long long *__restrict__ maxbits,
+                                                     const int32_t *__restrict__ cmax, int64_t count,
+                                                     ShiftArgs sa, int32_t *__restrict__ t) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    const uint64_t b = maxbits[i];
+    if (b == 0) { t[i] = 0; return; }
+    const uint64_t c = cmax[i] > 0 ? (uint64_t)cmax[i] : 1;
+    int j = 0;
+    while (j < sa.levels - 1 && c > sa.theta[j]) ++j;
+    t[i] = (5 - floor_log2_of_bits(b)) + (sa.f_max - j);
+}
+
+struct Scratch {
+    unsigned long long *amax, *bmax;     // bits of max |.| per row of A / column of B
+    int32_t *preA, *preB;                // 5 - e
+    int32_t *crow, *ccol;                // maxima of Cbar
+};
+
+Scratch carve(void *scratch, int64_t m, int64_t n) {
+    Scratch s;
+    s.amax = static_cast<unsigned long long *>(scratch);
+    s.bmax = s.amax + m;
+    s.preA = reinterpret_cast<int32_t *>(s.bmax + n);
+    s.preB = s.preA + m;
+    s.crow = s.preB + n;
+    s.ccol = s.crow + m;
+    return s;
+}
+
+inline unsigned blocks_for(int64_t threads) { return (unsigned)((threads + 255) / 256); }
+
+}  // namespace
+
+size_t accurate_scratch_bytes(int64_t m, int64_t n) { return (size_t)(m + n) * 16; }
+
+template <typename T>
+hipError_t launch_accurate_prescale(const T *A, int64_t lda, const T *B, int64_t ldb, int64_t m,
+                                    int64_t n, int64_t k, void *scratch, int8_t *Abar,
+                                    int8_t *Bbar, int64_t Mp, int64_t Np, int64_t Kp,
+                                    hipStream_t stream) {
+    const Scratch s = carve(scratch, m, n);
+    hipLaunchKernelGGL((k_row_maxbits<T>), dim3((unsigned)m), dim3(256), 0, stream, A, lda, k, s.amax);
+    if (hipError_t e = launch_col_maxbits<T>(B, ldb, k, n, s.bmax, stream)) return e;
+    hipLaunchKernelGGL(k_preshift, dim3(blocks_for(m)), dim3(256), 0, stream, s.amax, m, s.preA);
+    hipLaunchKernelGGL(k_preshift, dim3(blocks_for(n)), dim3(256), 0, stream, s.bmax, n, s.preB);
+    if (hipError_t e = launch_magnitudes<T>(A, lda, m, k, s.preA, Abar, Mp, Kp, stream)) return e;
+    return launch_magnitudes_cols<T>(B, ldb, k, n, s.preB, Bbar, Np, Kp, stream);
+}
+
+hipError_t launch_accurate_shifts(const int32_t *Cbar, int64_t Np, int64_t m, int64_t n,
+                                  const ShiftArgs &sa, void *scratch, int32_t *tA, int32_t *tB,
+                                  hipStream_t stream) {
+    const Scratch s = carve(scratch, m, n);
+    hipLaunchKernelGGL(k_row_max_i32, dim3((unsigned)m), dim3(256), 0, stream, Cbar, Np, n, s.crow);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(n)), dim3(256), 0, stream, s.ccol, n, 0);
+    hipLaunchKernelGGL(k_col_max_i32, dim3(blocks_for(n), (unsigned)((m + 255) / 256)), dim3(256), 0,
+                       stream, Cbar, Np, m, n, s.ccol);
+    hipLaunchKernelGGL(k_accu_finish, dim3(blocks_for(m)), dim3(256), 0, stream, s.amax, s.crow, m, sa, tA);
+    hipLaunchKernelGGL(k_accu_finish, dim3(blocks_for(n)), dim3(256), 0, stream, s.bmax, s.ccol, n, sa, tB);
+    return hipGetLastError();
+}
+
+template hipError_t launch_accurate_prescale<double>(const double *, int64_t, const double *, int64_t,
+                                                     int64_t, int64_t, int64_t, void *, int8_t *,
+                                                     int8_t *, int64_t, int64_t, int64_t, hipStream_t);
+template hipError_t launch_accurate_prescale<float>(const float *, int64_t, const float *, int64_t,
+                                                    int64_t, int64_t, int64_t, void *, int8_t *,
+                                                    int8_t *, int64_t, int64_t, int64_t, hipStream_t);
+
+}  // namespace oz2

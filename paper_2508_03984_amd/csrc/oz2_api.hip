@@ -28,7 +28,7 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int N) {
     L.m = m; L.n = n; L.k = k; L.N = N;
     L.Mp = round_up(m, kPadMN); L.Np = round_up(n, kPadMN); L.Kp = round_up(k, kPadK);
     size_t o = 0;
-    L.off_bt = o;   o += align256(column_scratch_bytes(n));   // per-column max and sum of squares
+    L.off_bt = o;   o += align256(std::max(column_scratch_bytes(n), accurate_scratch_bytes(m, n)));
     L.off_ta = o;   o += align256((size_t)m * 4);
     L.off_tb = o;   o += align256((size_t)n * 4);
     L.off_ra = o;   o += align256((size_t)N * L.Mp * L.Kp);
@@ -81,7 +81,7 @@ oz2_status mark(int i, hipStream_t stream) {
 template <typename T>
 oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, int64_t lda,
                      const T *B, int64_t ldb, double beta, T *C, int64_t ldc, int N,
-                     hipStream_t stream) {
+                     hipStream_t stream, bool accurate) {
     if (m < 0 || n < 0 || k < 0) return OZ2_INVALID_ARG;
     if (!supported(k, N)) return OZ2_UNSUPPORTED;
     if (m == 0 || n == 0) return OZ2_OK;
@@ -109,8 +109,17 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
     int32_t *prod = reinterpret_cast<int32_t *>(g.ws + L.off_prod);
 
     if (oz2_status st = mark(0, stream)) return st;
-    OZ2_TRY(launch_shifts<T>(A, lda, m, k, sa, tA, stream));
-    OZ2_TRY(launch_shifts_cols<T>(B, ldb, k, n, sa, col_scratch, tB, stream));
+    if (accurate) {
+        // Section 4.2, accurate mode: 7-bit matrices into slice 0, Cbar into plane 0.
+        OZ2_TRY(launch_accurate_prescale<T>(A, lda, B, ldb, m, n, k, col_scratch, rA, rB, L.Mp, L.Np,
+                                            L.Kp, stream));
+        OZ2_TRY(launch_int8_gemm(rA, rB, prod, 1, L.Mp, L.Np, L.Kp, stream));
+        OZ2_TRY(launch_accurate_shifts(prod, L.Np, m, n, make_accu_shift_args(tab), col_scratch, tA,
+                                       tB, stream));
+    } else {
+        OZ2_TRY(launch_shifts<T>(A, lda, m, k, sa, tA, stream));
+        OZ2_TRY(launch_shifts_cols<T>(B, ldb, k, n, sa, col_scratch, tB, stream));
+    }
     if (oz2_status st = mark(1, stream)) return st;
     OZ2_TRY(launch_residues<T>(A, lda, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
     OZ2_TRY(launch_residues_cols<T>(B, ldb, k, n, tB, ma, rB, L.Np, L.Kp, stream));
@@ -130,14 +139,27 @@ extern "C" {
 oz2_status oz2_dgemm(int64_t m, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
                      const double *B, int64_t ldb, double beta, double *C, int64_t ldc,
                      int num_moduli, hipStream_t stream) {
-    return gemm_impl<double>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
+    return gemm_impl<double>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream, false);
+}
+
+oz2_status oz2_dgemm_accurate(int64_t m, int64_t n, int64_t k, double alpha, const double *A,
+                              int64_t lda, const double *B, int64_t ldb, double beta, double *C,
+                              int64_t ldc, int num_moduli, hipStream_t stream) {
+    return gemm_impl<double>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream, true);
+}
+
+oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha, const float *A,
+                              int64_t lda, const float *B, int64_t ldb, float beta, float *C,
+                              int64_t ldc, int num_moduli, hipStream_t stream) {
+    return gemm_impl<float>(m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
+                            num_moduli, stream, true);
 }
 
 oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
                      const float *B, int64_t ldb, float beta, float *C, int64_t ldc,
                      int num_moduli, hipStream_t stream) {
     return gemm_impl<float>(m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
-                            num_moduli, stream);
+                            num_moduli, stream, false);
 }
 
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double) {
@@ -193,6 +215,18 @@ oz2_status oz2_shift_table(int num_moduli, int32_t *f_max, int32_t *levels, uint
     if (f_max) *f_max = t.f_max;
     if (levels) *levels = t.levels;
     if (theta) for (int j = 0; j < t.levels; ++j) theta[j] = t.theta[j];
+    return OZ2_OK;
+}
+
+oz2_status oz2_shift_table_accurate(int num_moduli, float *Paccu, int32_t *f_max, int32_t *levels,
+                                    uint64_t *theta) {
+    if (num_moduli < OZ2_MIN_MODULI || num_moduli > OZ2_MAX_MODULI) return OZ2_UNSUPPORTED;
+    const Table &t = table(num_moduli, true);
+    if (t.accu_levels < 1) return OZ2_UNSUPPORTED;
+    if (Paccu) *Paccu = t.Paccu;
+    if (f_max) *f_max = t.accu_f_max;
+    if (levels) *levels = t.accu_levels;
+    if (theta) for (int j = 0; j < t.accu_levels; ++j) theta[j] = t.accu_theta[j];
     return OZ2_OK;
 }
 

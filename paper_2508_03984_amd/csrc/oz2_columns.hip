@@ -17,12 +17,6 @@ namespace {
 constexpr int kColStrip = 64;        // columns per workgroup (one per lane)
 constexpr int kRowChunk = 512;       // rows per workgroup in the shift kernels
 
-__device__ inline int floor_log2_of_bits(uint64_t bits) {            // bits of a finite |x| > 0
-    int ex = (int)(bits >> 52);
-    if (ex) return ex - 1023;
-    return (63 - __clzll((long long)bits)) - 1074;                    // subnormal
-}
-
 __global__ __launch_bounds__(256) void k_fill_u64(uint64_t *p, int64_t count, uint64_t v) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < count) p[i] = v;
@@ -104,7 +98,8 @@ __device__ inline int residue_of(double x, double p, double pinv) {
     return (int)y;
 }
 
-template <typename T, int ROUNDS>
+// KIND as in the row kernel: 0 = residues for all moduli, 1 = the 7-bit magnitudes (slice 0).
+template <typename T, int ROUNDS, int KIND>
 __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, int64_t ld,
                                                        int64_t rows, int64_t cols,
                                                        const int32_t *__restrict__ t, ModArgs ma,
@@ -127,8 +122,9 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
         const int64_t h0 = kb * kBlockK + (wave + 4 * half) * 8;
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            v[half][i] = (c < cols && h0 + i < rows)
-                             ? trunc(ldexp((double)X[(h0 + i) * ld + c], sh)) : 0.0;
+            v[half][i] = !(c < cols && h0 + i < rows) ? 0.0
+                         : KIND == 0 ? trunc(ldexp((double)X[(h0 + i) * ld + c], sh))
+                                     : ceil(ldexp(fabs((double)X[(h0 + i) * ld + c]), sh));
     }
 
     // Write-out: per modulus the 64 columns x 64 bytes of this tile are contiguous in
@@ -137,8 +133,9 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
     const int col = threadIdx.x >> 2, quarter = threadIdx.x & 3;
     int8_t *dst = out + (kb * cols_pad + (int64_t)blockIdx.x * kColStrip) * kBlockK + threadIdx.x * 16;
 
-    for (int s0 = 0; s0 < ma.n; s0 += kGroup) {
-        const int ns = ma.n - s0 < kGroup ? ma.n - s0 : kGroup;
+    const int n_slices = KIND == 0 ? ma.n : 1;
+    for (int s0 = 0; s0 < n_slices; s0 += kGroup) {
+        const int ns = n_slices - s0 < kGroup ? n_slices - s0 : kGroup;
         for (int g = 0; g < ns; ++g) {
             const double p = (double)ma.p[s0 + g], pinv = ma.pinv[s0 + g];
 #pragma unroll
@@ -146,7 +143,8 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
                 uint32_t w[2] = {0u, 0u};
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    uint32_t b = (uint32_t)residue_of<ROUNDS>(v[half][i], p, pinv) & 0xffu;
+                    uint32_t b = (KIND == 0 ? (uint32_t)residue_of<ROUNDS>(v[half][i], p, pinv)
+                                            : (uint32_t)(int)v[half][i]) & 0xffu;
                     w[i >> 2] |= b << (8 * (i & 3));
                 }
                 stage[g][wave + 4 * half][lane] = make_uint2(w[0], w[1]);
@@ -188,17 +186,43 @@ hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t co
                                 hipStream_t stream) {
     dim3 grid((unsigned)(cols_pad / kColStrip), (unsigned)(rows_pad / kBlockK));
     if (ma.rounds == 1)
-        hipLaunchKernelGGL((k_residues_cols<T, 1>), grid, dim3(256), 0, stream, X, ld, rows, cols, t,
+        hipLaunchKernelGGL((k_residues_cols<T, 1, 0>), grid, dim3(256), 0, stream, X, ld, rows, cols, t,
                            ma, out, cols_pad, rows_pad);
     else
-        hipLaunchKernelGGL((k_residues_cols<T, 2>), grid, dim3(256), 0, stream, X, ld, rows, cols, t,
+        hipLaunchKernelGGL((k_residues_cols<T, 2, 0>), grid, dim3(256), 0, stream, X, ld, rows, cols, t,
                            ma, out, cols_pad, rows_pad);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_magnitudes_cols(const T *X, int64_t ld, int64_t rows, int64_t cols,
+                                  const int32_t *pre, int8_t *out, int64_t cols_pad,
+                                  int64_t rows_pad, hipStream_t stream) {
+    dim3 grid((unsigned)(cols_pad / kColStrip), (unsigned)(rows_pad / kBlockK));
+    ModArgs none{};
+    hipLaunchKernelGGL((k_residues_cols<T, 1, 1>), grid, dim3(256), 0, stream, X, ld, rows, cols, pre,
+                       none, out, cols_pad, rows_pad);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_col_maxbits(const T *X, int64_t ld, int64_t rows, int64_t cols,
+                              unsigned long long *colmax, hipStream_t stream) {
+    hipLaunchKernelGGL(k_fill_u64, dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, stream,
+                       reinterpret_cast<uint64_t *>(colmax), cols, 0ull);
+    dim3 grid((unsigned)((cols + kColStrip - 1) / kColStrip), (unsigned)((rows + kRowChunk - 1) / kRowChunk));
+    hipLaunchKernelGGL((k_col_max<T>), grid, dim3(256), 0, stream, X, ld, rows, cols, colmax);
     return hipGetLastError();
 }
 
 #define OZ2_INSTANTIATE_COLS(T)                                                                   \
     template hipError_t launch_shifts_cols<T>(const T *, int64_t, int64_t, int64_t,               \
                                               const ShiftArgs &, void *, int32_t *, hipStream_t); \
+    template hipError_t launch_magnitudes_cols<T>(const T *, int64_t, int64_t, int64_t,           \
+                                                  const int32_t *, int8_t *, int64_t, int64_t,    \
+                                                  hipStream_t);                                   \
+    template hipError_t launch_col_maxbits<T>(const T *, int64_t, int64_t, int64_t,               \
+                                              unsigned long long *, hipStream_t);                 \
     template hipError_t launch_residues_cols<T>(const T *, int64_t, int64_t, int64_t,             \
                                                 const int32_t *, const ModArgs &, int8_t *,       \
                                                 int64_t, int64_t, hipStream_t);

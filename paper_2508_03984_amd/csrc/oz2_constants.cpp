@@ -176,6 +176,10 @@ int32_t level_of(uint64_t T, double Pfast) {
     return (int32_t)std::floor(Pfast - std::fmax(1.0, 0.51 * std::log2(S)));
 }
 
+int32_t accu_level_of(uint64_t c, double Paccu) {
+    return (int32_t)std::floor(Paccu - 0.51 * std::log2((double)c));
+}
+
 Table build(int n, bool is_double) {
     Table t;
     std::memset(&t, 0, sizeof(t));
@@ -235,6 +239,23 @@ Table build(int n, bool is_double) {
         t.theta[j] = lo;
     }
     if (t.levels > kMaxLevels) t.levels = -1;               // cannot happen for N <= 20
+
+    // Accurate-mode table over c in [1, 2^29] (k <= 2^17 entries of at most 64 * 64).
+    t.Paccu = (float)(0.5 * log2_wide(Wide::sub(P, Wide::from_u64(1))) - 0.5);
+    const uint64_t Cmax = 1ull << 29;
+    double Pa = (double)t.Paccu;
+    t.accu_f_max = accu_level_of(1, Pa);
+    t.accu_levels = t.accu_f_max - accu_level_of(Cmax, Pa) + 1;
+    for (int j = 0; j < t.accu_levels && j < kMaxLevels; ++j) {
+        int32_t want = t.accu_f_max - j;
+        uint64_t lo = 1, hi = Cmax;
+        while (lo < hi) {
+            uint64_t mid = lo + (hi - lo + 1) / 2;
+            if (accu_level_of(mid, Pa) >= want) lo = mid; else hi = mid - 1;
+        }
+        t.accu_theta[j] = lo;
+    }
+    if (t.accu_levels > kMaxLevels) t.accu_levels = -1;
     return t;
 }
 

@@ -7,7 +7,7 @@ namespace oz2 {
 
 constexpr int kMinModuli = 2;
 constexpr int kMaxModuli = 20;
-constexpr int kMaxLevels = 16;
+constexpr int kMaxLevels = 20;
 
 struct Table {
     int32_t n;                          // number of moduli
@@ -21,6 +21,12 @@ struct Table {
     // exact integer behind S = T 2^-30 in f = floor(P'_fast - max(1, 0.51 log2 S)).
     int32_t f_max, levels;
     uint64_t theta[kMaxLevels];
+    // Accurate mode (Section 4.2): P'_accu = single(0.5*log2(P-1) - 0.5) and the same kind of
+    // table for f = floor(P'_accu - 0.51 log2 c) over the integer c = max entry of a row or
+    // column of Abar*Bbar, 1 <= c <= 2^29: f = accu_f_max - min{ j : c <= accu_theta[j] }.
+    float Paccu;
+    int32_t accu_f_max, accu_levels;
+    uint64_t accu_theta[kMaxLevels];
 };
 
 // Built on first use, cached for the life of the process.  n must be in 2..20.

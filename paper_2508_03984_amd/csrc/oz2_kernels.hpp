@@ -27,7 +27,8 @@ struct ModArgs {
     double P1, P2, Pinv;
 };
 
-// Shift table of Section 4.2 (see oz2_constants.hpp).
+// Shift table of Section 4.2 (see oz2_constants.hpp); the same shape serves fast mode
+// (argument: sum of squares T) and accurate mode (argument: maximum c of Abar*Bbar).
 struct ShiftArgs {
     int32_t f_max, levels;
     uint64_t theta[kMaxLevels];
@@ -35,6 +36,16 @@ struct ShiftArgs {
 
 ModArgs make_mod_args(const Table &t);
 ShiftArgs make_shift_args(const Table &t);
+ShiftArgs make_accu_shift_args(const Table &t);
+
+#if defined(__HIPCC__)
+// floor(log2 |x|) from the bit pattern of a finite FP64 |x| > 0 (subnormals included).
+__device__ inline int floor_log2_of_bits(uint64_t bits) {
+    int ex = (int)(bits >> 52);
+    if (ex) return ex - 1023;
+    return (63 - __clzll((long long)bits)) - 1074;
+}
+#endif
 
 // Algorithm 1 line 1 (fast mode): one shift per row of X (rows x len, leading dimension ld).
 template <typename T>
@@ -61,6 +72,38 @@ template <typename T>
 hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t cols, const int32_t *t,
                                 const ModArgs &ma, int8_t *out, int64_t cols_pad, int64_t rows_pad,
                                 hipStream_t stream);
+
+// Accurate mode (Section 4.2, second half).  All vectors live in `scratch`
+// (accurate_scratch_bytes(m, n) bytes); the 7-bit matrices go to slice 0 of the residue
+// buffers (same K-blocked layout) and Cbar to plane 0 of the product buffer:
+//   launch_accurate_prescale   max|.| per row of A / column of B, mu' = 2^(5-e), nu', and
+//                              Abar = ceil(mu' |A|), Bbar = ceil(|B| nu') as int8
+//   (the caller then runs launch_int8_gemm with batch 1 to get Cbar = Abar * Bbar)
+//   launch_accurate_shifts     row / column maxima of Cbar over its m x n part and
+//                              t = (5 - e) + floor(P'_accu - 0.51 log2 max), zero vectors -> 0
+size_t accurate_scratch_bytes(int64_t m, int64_t n);
+template <typename T>
+hipError_t launch_accurate_prescale(const T *A, int64_t lda, const T *B, int64_t ldb, int64_t m,
+                                    int64_t n, int64_t k, void *scratch, int8_t *Abar,
+                                    int8_t *Bbar, int64_t Mp, int64_t Np, int64_t Kp,
+                                    hipStream_t stream);
+hipError_t launch_accurate_shifts(const int32_t *Cbar, int64_t Np, int64_t m, int64_t n,
+                                  const ShiftArgs &sa, void *scratch, int32_t *tA, int32_t *tB,
+                                  hipStream_t stream);
+
+// Row / column kernels in "magnitude" form, used by accurate mode:
+// out[h / 64][r][h % 64] = ceil(|X[r][h]| * 2^pre[r]) (int8), zero beyond rows / len.
+template <typename T>
+hipError_t launch_magnitudes(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *pre,
+                             int8_t *out, int64_t rows_pad, int64_t len_pad, hipStream_t stream);
+template <typename T>
+hipError_t launch_magnitudes_cols(const T *X, int64_t ld, int64_t rows, int64_t cols,
+                                  const int32_t *pre, int8_t *out, int64_t cols_pad,
+                                  int64_t rows_pad, hipStream_t stream);
+// colmax[c] = max_h bits(|X[h][c]|) as uint64 (fills colmax with 0 first).
+template <typename T>
+hipError_t launch_col_maxbits(const T *X, int64_t ld, int64_t rows, int64_t cols,
+                              unsigned long long *colmax, hipStream_t stream);
 
 // Algorithm 1 line 6: C[b] = A[b] * B[b]^T for b < batch, int8 in, wrapping int32 out.
 // A: [batch][Kp/64][Mp][64], B: [batch][Kp/64][Np][64] (K-blocked, see launch_residues),

@@ -29,6 +29,14 @@ ShiftArgs make_shift_args(const Table &t) {
     return s;
 }
 
+ShiftArgs make_accu_shift_args(const Table &t) {
+    ShiftArgs s{};
+    s.f_max = t.accu_f_max;
+    s.levels = t.accu_levels;
+    for (int j = 0; j < kMaxLevels; ++j) s.theta[j] = j < t.accu_levels ? t.accu_theta[j] : ~0ull;
+    return s;
+}
+
 namespace {
 
 constexpr int kWave = 64;
@@ -49,12 +57,6 @@ __device__ inline uint64_t wave_max(uint64_t v) {
 __device__ inline uint64_t wave_sum(uint64_t v) {
     for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
     return v;
-}
-
-__device__ inline int floor_log2_of_bits(uint64_t bits) {            // bits of a finite |x| > 0
-    int ex = (int)(bits >> 52);
-    if (ex) return ex - 1023;
-    return (63 - __clzll((long long)bits)) - 1074;                    // subnormal
 }
 
 template <typename T>
@@ -126,7 +128,9 @@ __device__ inline int residue_of(double x, double p, double pinv) {
 
 constexpr int kResPerThread = 8;     // consecutive elements per thread -> 8-byte stores
 
-template <typename T, int ROUNDS>
+// KIND 0: residues of trunc(x 2^t) for all moduli.  KIND 1 (accurate mode): the single
+// 7-bit magnitude matrix ceil(|x| 2^t), written as slice 0.
+template <typename T, int ROUNDS, int KIND>
 __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64_t ld,
                                                   int64_t rows, int64_t len,
                                                   const int32_t *__restrict__ t, ModArgs ma,
@@ -148,7 +152,9 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
         const T *x = X + r * ld + h0;
 #pragma unroll
         for (int i = 0; i < kResPerThread; ++i)
-            v[i] = (h0 + i < len) ? trunc(ldexp((double)x[i], sh)) : 0.0;
+            v[i] = (h0 + i >= len) ? 0.0
+                   : KIND == 0   ? trunc(ldexp((double)x[i], sh))
+                                 : ceil(ldexp(fabs((double)x[i]), sh));
     } else {
 #pragma unroll
         for (int i = 0; i < kResPerThread; ++i) v[i] = 0.0;
@@ -156,6 +162,13 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
 
     const int64_t plane = rows_pad * len_pad;
     int8_t *o = out + (kb * rows_pad + r) * kBlockK + (h0 - kb * kBlockK);
+    if (KIND == 1) {
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < kResPerThread; ++i) w[i >> 2] |= ((uint32_t)(int)v[i] & 0xffu) << (8 * (i & 3));
+        *reinterpret_cast<uint2 *>(o) = make_uint2(w[0], w[1]);
+        return;
+    }
     for (int s = 0; s < ma.n; ++s) {
         const double p = (double)ma.p[s], pinv = ma.pinv[s];
         uint32_t w[2] = {0u, 0u};
@@ -256,11 +269,21 @@ hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, co
                            hipStream_t stream) {
     const int64_t threads = rows_pad * (len_pad / kResPerThread);
     if (ma.rounds == 1)
-        hipLaunchKernelGGL((k_residues<T, 1>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
+        hipLaunchKernelGGL((k_residues<T, 1, 0>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
                            ld, rows, len, t, ma, out, rows_pad, len_pad);
     else
-        hipLaunchKernelGGL((k_residues<T, 2>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
+        hipLaunchKernelGGL((k_residues<T, 2, 0>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
                            ld, rows, len, t, ma, out, rows_pad, len_pad);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_magnitudes(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *pre,
+                             int8_t *out, int64_t rows_pad, int64_t len_pad, hipStream_t stream) {
+    const int64_t threads = rows_pad * (len_pad / kResPerThread);
+    ModArgs none{};
+    hipLaunchKernelGGL((k_residues<T, 1, 1>), dim3(blocks_for(threads)), dim3(256), 0, stream, X, ld,
+                       rows, len, pre, none, out, rows_pad, len_pad);
     return hipGetLastError();
 }
 
@@ -285,6 +308,9 @@ hipError_t launch_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n, double bet
 #define OZ2_INSTANTIATE(T)                                                                        \
     template hipError_t launch_shifts<T>(const T *, int64_t, int64_t, int64_t, const ShiftArgs &, \
                                          int32_t *, hipStream_t);                                 \
+    template hipError_t launch_magnitudes<T>(const T *, int64_t, int64_t, int64_t,               \
+                                             const int32_t *, int8_t *, int64_t, int64_t,        \
+                                             hipStream_t);                                        \
     template hipError_t launch_residues<T>(const T *, int64_t, int64_t, int64_t, const int32_t *, \
                                            const ModArgs &, int8_t *, int64_t, int64_t,           \
                                            hipStream_t);                                          \

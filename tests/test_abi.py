@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol(oz):
     header = open(os.path.join(ROOT, "include", "oz2.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(oz2_[a-z0-9_]+)\s*\(", header))
-    assert {"oz2_dgemm", "oz2_sgemm", "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
+    assert {"oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate", "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
             "oz2_constants", "oz2_stage_ptr", "oz2_int8_gemm"} <= declared
     lib = C.CDLL(oz.lib_path())
     for name in declared:
@@ -81,6 +81,25 @@ def test_shift_table_matches_the_formula_at_every_threshold(oz, oracle, n):
         assert e[0] == 0 and int(Tor[0]) == T
         j = next(i for i, th in enumerate(theta) if T <= th)
         assert t[0] == tab["f_max"] - j, (n, T)
+
+
+@pytest.mark.parametrize("n", range(2, 21))
+def test_accurate_shift_table_matches_the_formula_at_every_threshold(oz, oracle, n):
+    """Accurate mode: f = floor(P'_accu - 0.51 log2 c) is monotone in the integer c, so the
+    kernels' table lookup equals the oracle's formula iff they agree around every threshold."""
+    tab = oz.oz2_shift_table_accurate(n)
+    c = K.constants(n)
+    assert tab["Paccu"] == c.Paccu
+    theta = [int(x) for x in tab["theta"]]
+    assert theta == sorted(theta) and theta[-1] == 2 ** 29 and theta[0] >= 1
+    probes = sorted({1, 2, 2 ** 29} | {v for th in theta for v in (th - 1, th, th + 1) if 1 <= v <= 2 ** 29})
+    e = np.full(len(probes), 3, np.int32)
+    t = oracle.accu_shift_from_max(e, np.array(probes, np.int64), c.Paccu)
+    for cm, tv in zip(probes, t):
+        j = next(i for i, th in enumerate(theta) if cm <= th)
+        assert tv == (5 - 3) + tab["f_max"] - j, (n, cm)
+    # a maximum of 0 (the other matrix is zero) is treated as 1
+    assert oracle.accu_shift_from_max([3], [0], c.Paccu)[0] == 2 + tab["f_max"]
 
 
 def test_argument_checks_need_no_gpu(oz):

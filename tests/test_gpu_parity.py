@@ -26,7 +26,7 @@ def oz():
     oz.oz2_release()
 
 
-def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None):
+def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, accurate=False):
     """Run oz2_dgemm / oz2_sgemm and fetch every stage, trimmed to the logical shapes."""
     import torch
     m, k = A.shape
@@ -38,7 +38,10 @@ def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None):
     dB = torch.zeros((k, ldb), dtype=dt, device="cuda"); dB[:, :n] = torch.from_numpy(B).cuda()
     dC = (torch.from_numpy(np.ascontiguousarray(Cin)).cuda() if Cin is not None
           else torch.full((m, n), float("nan"), dtype=dt, device="cuda"))
-    fn = oz.oz2_dgemm if dt == torch.float64 else oz.oz2_sgemm
+    if accurate:
+        fn = oz.oz2_dgemm_accurate if dt == torch.float64 else oz.oz2_sgemm_accurate
+    else:
+        fn = oz.oz2_dgemm if dt == torch.float64 else oz.oz2_sgemm
     fn(m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
     torch.cuda.synchronize()
     from paper_2508_03984_amd import binding as b
@@ -93,6 +96,38 @@ def test_stage_parity(oz, oracle, m, n, k, N, phi, dtype):
     ref = oracle.gemm(A, B, N, is_double=is_double)
     got = gpu_gemm(oz, A, B, N)
     assert_parity(got, ref, is_double)
+
+
+ACCURATE_CASES = [
+    (256, 256, 256, 14, 0.5, np.float64),
+    (1, 1, 1, 2, 0.5, np.float64),
+    (300, 200, 333, 16, 2.0, np.float64),
+    (520, 390, 1000, 12, 4.0, np.float64),
+    (257, 513, 129, 20, 1.0, np.float64),
+    (300, 200, 333, 7, 1.5, np.float32),
+    (97, 515, 1030, 9, 0.5, np.float32),
+]
+
+
+@pytest.mark.parametrize("m,n,k,N,phi,dtype", ACCURATE_CASES)
+def test_stage_parity_accurate_mode(oz, oracle, m, n, k, N, phi, dtype):
+    A, B = S.gemm_inputs(m, n, k, phi, seed=30 + N, dtype=dtype)
+    is_double = dtype == np.float64
+    ref = oracle.gemm(A, B, N, is_double=is_double, accurate=True)
+    got = gpu_gemm(oz, A, B, N, accurate=True)
+    assert_parity(got, ref, is_double)
+
+
+def test_accurate_mode_degenerate_inputs(oz, oracle):
+    A, B = S.gemm_inputs(40, 50, 60, 1.0, seed=9)
+    A[3, :] = 0.0; B[:, 7] = 0.0
+    A[5, :] *= 2.0 ** -1040; B[:, 9] *= 2.0 ** 900
+    A[7, :] = 1.0; B[:, 11] = -1.0
+    Cin = S.matrix(40, 50, 0.5, seed=2)
+    assert_parity(gpu_gemm(oz, A, B, 16, 0.5, 2.0, Cin.copy(), lda=77, ldb=64, accurate=True),
+                  oracle.gemm(A, B, 16, 0.5, 2.0, Cin, accurate=True), True)
+    Zb = np.zeros((60, 50))                      # B = 0: every maximum of Cbar is 0
+    assert_parity(gpu_gemm(oz, A, Zb, 14, accurate=True), oracle.gemm(A, Zb, 14, accurate=True), True)
 
 
 def test_alpha_beta_and_leading_dimensions(oz, oracle):
@@ -201,16 +236,17 @@ def test_caller_owned_workspace(oz, oracle):
 
 
 # ------------------------------------------------------------------ benchmark-size configurations
-def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries=1500):
+def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries=1500,
+                   accurate=False):
     """Full comparison of shifts and residues, sampled comparison of products and C."""
     import torch
     from paper_2508_03984_amd import binding as b
     is_double = dtype == np.float64
     A, B = S.gemm_inputs(m, n, k, phi, seed, dtype)
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
-    dC = oz.matmul(dA, dB, N)
+    dC = oz.matmul(dA, dB, N, accurate=accurate)
     torch.cuda.synchronize()
-    prep = oracle.prepare(A, B, N, is_double)
+    prep = oracle.prepare(A, B, N, is_double, accurate)
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), prep["tB"])
     ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A, copy=False))    # a permuted view
@@ -243,6 +279,10 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
 def test_config_4096_sampled(oz, oracle):
     for N in (12, 16, 20):
         sampled_parity(oz, oracle, 4096, 4096, 4096, N, 0.5, np.float64, seed=0)
+
+
+def test_config_4096_accurate_sampled(oz, oracle):
+    sampled_parity(oz, oracle, 4096, 4096, 4096, 15, 2.0, np.float64, seed=0, accurate=True)
 
 
 def test_config_16384_dgemm_sampled(oz, oracle):
