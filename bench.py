@@ -169,6 +169,8 @@ def main() -> int:
     ap.add_argument("--sgemm", action="store_true", help="FP32 emulation (oz2_sgemm)")
     ap.add_argument("--accurate", action="store_true",
                     help="accurate mode of Section 4.2 (oz2_dgemm_accurate / oz2_sgemm_accurate)")
+    ap.add_argument("--int32-products", action="store_true",
+                    help="diagnostic pipeline: the GEMM stores int32 sums, the epilogue reduces them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stage", choices=["all", "int8_gemm", "copy"], default="all",
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
@@ -196,6 +198,7 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     oz.load()                                        # raises if liboz2.so is missing
+    oz.oz2_set_int32_products(args.int32_products)
 
     m = n = k = args.size
     N = args.moduli
@@ -246,11 +249,12 @@ def main() -> int:
     gemm_ops = 2.0 * Mp * Np * Kp * N
     gemm_tops = gemm_ops / (stage_ms[2] * 1e-3) / 1e12
     E = 4 if args.sgemm else 8
+    PB = 4 if args.int32_products else 1                        # bytes per product entry
     stage_bytes = [
         E * (m * k + 2 * k * n) + 4 * (m + n),                  # shifts: A once, B twice (max, then sum)
         E * (m * k + k * n) + N * (Mp * Kp + Np * Kp),          # residues
-        N * (Mp * Kp + Np * Kp) + 4 * N * Mp * Np,              # GEMM compulsory traffic
-        4 * N * m * n + E * m * n,                              # epilogue
+        N * (Mp * Kp + Np * Kp) + PB * N * Mp * Np,             # GEMM compulsory traffic
+        PB * N * m * n + E * m * n,                             # epilogue
     ]
     stage_gbs = [b / (t * 1e-3) / 1e9 if t > 0 else 0.0 for b, t in zip(stage_bytes, stage_ms)]
 

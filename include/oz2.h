@@ -42,6 +42,7 @@ typedef enum {
 #define OZ2_MIN_MODULI 2
 #define OZ2_MAX_MODULI 20           /* Section 4.1: the table is kept to N <= 20        */
 #define OZ2_MAX_K (1 << 17)         /* Section 4.3: INT32 accumulation is exact up to it */
+#define OZ2_MAX_K_BLOCKED (1 << 20) /* longer contractions are cut into ranges of OZ2_MAX_K */
 
 /*
  * C <- alpha * (A*B) + beta * C,  A: m x k (lda >= k), B: k x n (ldb >= n),
@@ -55,7 +56,10 @@ typedef enum {
  *
  * alpha, beta are host values.  beta == 0: C is not read (NaNs in it do not
  * propagate).  m == 0 or n == 0: nothing is done.  k == 0: C <- beta * C.
- * k > OZ2_MAX_K returns OZ2_UNSUPPORTED.
+ * OZ2_MAX_K < k <= OZ2_MAX_K_BLOCKED: the contraction is cut into ranges of at most
+ * OZ2_MAX_K ("block matrix multiplication", Section 4.3) whose residues are added
+ * modulo p_s; k > OZ2_MAX_K_BLOCKED returns OZ2_UNSUPPORTED (the exact integer sum of
+ * squares behind the scale vectors needs k * 2^32 < 2^53).
  * oz2_sgemm takes FP32 data; its reconstruction still runs in FP64 and the
  * result is rounded to FP32 once.
  */
@@ -77,7 +81,8 @@ oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha,
  * sum_h |a_ih||b_hj| directly instead of through the Cauchy-Schwarz inequality.  This costs
  * one more INT8 GEMM and gives larger scale factors, i.e. a smaller truncation error for
  * the same number of moduli (it matters for inputs with a wide exponent range).
- * Arguments, conventions and errors are those of oz2_dgemm / oz2_sgemm.
+ * Arguments, conventions and errors are those of oz2_dgemm / oz2_sgemm, except that
+ * k > OZ2_MAX_K returns OZ2_UNSUPPORTED (Cbar is a single INT32 product).
  */
 oz2_status oz2_dgemm_accurate(int64_t m, int64_t n, int64_t k, double alpha,
                               const double *A, int64_t lda, const double *B, int64_t ldb,
@@ -92,7 +97,8 @@ oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha,
 /*
  * Workspace.  A call needs device scratch for the shift vectors (and the
  * per-column partial results behind them), the INT8 residue slices of A and B (Algorithm 1 lines 4-5)
- * and the INT32 products (line 6): oz2_workspace_bytes gives the size for a
+ * and the reduced products U_s (line 7; or the INT32 products of line 6 after
+ * oz2_set_int32_products(1)): oz2_workspace_bytes gives the size for a
  * problem (0 if the arguments are unsupported).  oz2_set_workspace hands the
  * library a caller-owned device buffer (kept, not freed, must stay valid until
  * replaced; 256-byte aligned); with (NULL, 0) the library goes back to
@@ -142,21 +148,29 @@ oz2_status oz2_shift_table_accurate(int num_moduli, float *Paccu, int32_t *f_max
  *   OZ2_STAGE_SHIFT_B  int32 [n]                 dims = { n, 0, 0, 0 }
  *   OZ2_STAGE_RES_A    int8  [N][Kp/64][Mp][64]  dims = { N, Mp, Kp, m }   rows >= m, k-index >= k are 0
  *   OZ2_STAGE_RES_B    int8  [N][Kp/64][Np][64]  dims = { N, Np, Kp, n }   (B slices are stored transposed)
- *   OZ2_STAGE_PROD     int32 [N][Mp][Np]         dims = { N, Mp, Np, 0 }
+ *   OZ2_STAGE_U        uint8 [N][Mp][Np]         dims = { N, Mp, Np, 0 }   U_s = mod(C'_s, p_s) (Alg. 1 line 7)
+ *   OZ2_STAGE_PROD     int32 [N][Mp][Np]         dims = { N, Mp, Np, 0 }   C'_s (Alg. 1 line 6)
+ * By default the INT8 GEMM reduces its sums itself and only OZ2_STAGE_U exists; after
+ * oz2_set_int32_products(1) calls keep the int32 sums instead (4x the workspace and the
+ * traffic; for k > OZ2_MAX_K the planes hold sums of reduced partial results, congruent to
+ * C'_s modulo p_s) and only OZ2_STAGE_PROD exists.  Asking for the other one returns
+ * OZ2_INVALID_ARG.
  * The residue slices are K-blocked: residue (row r, k-index h) of slice s is at
  * ((s * Kp/64 + h/64) * rows + r) * 64 + h%64, so that a (rows x 64) tile is contiguous.
  * Valid until the next call or workspace change; the caller synchronises.
  */
 enum { OZ2_STAGE_SHIFT_A = 0, OZ2_STAGE_SHIFT_B = 1, OZ2_STAGE_RES_A = 2,
-       OZ2_STAGE_RES_B = 3, OZ2_STAGE_PROD = 4 };
+       OZ2_STAGE_RES_B = 3, OZ2_STAGE_PROD = 4, OZ2_STAGE_U = 5 };
 oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims);
+void oz2_set_int32_products(int on);
 
 /*
  * Diagnostics: the batched INT8 GEMM of Algorithm 1 line 6 on its own.
  * dev_A: int8 [batch][Kp/64][Mp][64], dev_B: int8 [batch][Kp/64][Np][64] (the K-blocked
  * layout of the residue slices, see oz2_stage_ptr), dev_C: int32 [batch][Mp][Np];
  * C_b = A_b * B_b^T with wrapping INT32 sums.
- * Mp and Np must be multiples of 256, Kp a multiple of 128 (OZ2_INVALID_ARG otherwise).
+ * Mp and Np must be multiples of 256, Kp a multiple of 128 (OZ2_INVALID_ARG otherwise) and
+ * at most OZ2_MAX_K (OZ2_UNSUPPORTED otherwise).
  */
 oz2_status oz2_int8_gemm(const int8_t *dev_A, const int8_t *dev_B, int32_t *dev_C,
                          int batch, int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream);

@@ -230,6 +230,51 @@ void oz2o_int8_gemm_rows(const int8_t *Ares, const int8_t *Bres, int N,
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* k > 2^17 ("it is possible to apply block matrix multiplication",           */
+/* Section 4.3): the contraction is cut into ranges of `kblock` <= 2^17, each  */
+/* range is accumulated in wrapping INT32 like above, and the range results    */
+/* are added as integers; out is [N][nrows][n] int64.  With kblock >= k this   */
+/* is the plain product.                                                       */
+/* ------------------------------------------------------------------------- */
+void oz2o_int8_gemm_rows_blocked(const int8_t *Ares, const int8_t *Bres, int N,
+                                 int64_t m, int64_t n, int64_t k, int64_t kblock,
+                                 const int64_t *rows, int64_t nrows, int64_t *out)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int s = 0; s < N; ++s) {
+        for (int64_t r = 0; r < nrows; ++r) {
+            const int8_t *a = Ares + ((int64_t)s * m + rows[r]) * k;
+            for (int64_t j = 0; j < n; ++j) {
+                const int8_t *b = Bres + ((int64_t)s * n + j) * k;
+                int64_t total = 0;
+                for (int64_t h0 = 0; h0 < k; h0 += kblock) {
+                    int64_t h1 = h0 + kblock < k ? h0 + kblock : k;
+                    uint32_t acc = 0;
+                    for (int64_t h = h0; h < h1; ++h)
+                        acc += (uint32_t)((int32_t)a[h] * (int32_t)b[h]);
+                    total += (int32_t)acc;
+                }
+                out[((int64_t)s * nrows + r) * n + j] = total;
+            }
+        }
+    }
+}
+
+/* mod for the int64 sums of the blocked product. */
+void oz2o_mod_reduce64(const int64_t *prod, int N, int64_t count,
+                       const int32_t *p, uint8_t *U)
+{
+    for (int s = 0; s < N; ++s) {
+#pragma omp parallel for schedule(static)
+        for (int64_t c = 0; c < count; ++c) {
+            int64_t r = prod[(int64_t)s * count + c] % p[s];
+            if (r < 0) r += p[s];
+            U[(int64_t)s * count + c] = (uint8_t)r;
+        }
+    }
+}
+
 /* Same product for scattered entries (ii[c], jj[c]); out is [N][count]. */
 void oz2o_int8_gemm_entries(const int8_t *Ares, const int8_t *Bres, int N,
                             int64_t m, int64_t n, int64_t k, const int64_t *ii,

@@ -99,6 +99,8 @@ def residues(X: np.ndarray, axis: int, t: np.ndarray, p: Sequence[int]) -> np.nd
 
 def int8_gemm_rows(Ares: np.ndarray, Bres: np.ndarray, rows: np.ndarray) -> np.ndarray:
     """Algorithm 1 line 6 for the listed rows.  Returns int32 [N][len(rows)][n]."""
+    Ares = np.ascontiguousarray(Ares, dtype=np.int8)
+    Bres = np.ascontiguousarray(Bres, dtype=np.int8)
     N, m, k = Ares.shape
     N2, n, k2 = Bres.shape
     assert N == N2 and k == k2
@@ -110,8 +112,35 @@ def int8_gemm_rows(Ares: np.ndarray, Bres: np.ndarray, rows: np.ndarray) -> np.n
     return out
 
 
+MAX_K = 1 << 17           # Section 4.3: longest contraction with exact INT32 accumulation
+
+
+def int8_gemm_rows_blocked(Ares, Bres, rows, kblock: int = MAX_K) -> np.ndarray:
+    """Block matrix multiplication for k > 2^17 (Section 4.3).  Returns int64 [N][len(rows)][n]."""
+    Ares = np.ascontiguousarray(Ares, dtype=np.int8)
+    Bres = np.ascontiguousarray(Bres, dtype=np.int8)
+    N, m, k = Ares.shape
+    _, n, _ = Bres.shape
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    out = np.empty((N, rows.size, n), np.int64)
+    _load().oz2o_int8_gemm_rows_blocked(_p(Ares), _p(Bres), C.c_int(N), _i64(m), _i64(n), _i64(k),
+                                        _i64(kblock), _p(rows), _i64(rows.size), _p(out))
+    return out
+
+
+def mod_reduce64(prod: np.ndarray, p: Sequence[int]) -> np.ndarray:
+    prod = np.ascontiguousarray(prod, dtype=np.int64)
+    N = prod.shape[0]
+    pa = np.asarray(p, dtype=np.int32)
+    U = np.empty(prod.shape, np.uint8)
+    _load().oz2o_mod_reduce64(_p(prod), C.c_int(N), _i64(prod.size // N), _p(pa), _p(U))
+    return U
+
+
 def int8_gemm_entries(Ares, Bres, ii, jj) -> np.ndarray:
     """Algorithm 1 line 6 for scattered entries.  Returns int32 [N][count]."""
+    Ares = np.ascontiguousarray(Ares, dtype=np.int8)
+    Bres = np.ascontiguousarray(Bres, dtype=np.int8)
     N, m, k = Ares.shape
     _, n, _ = Bres.shape
     ii = np.ascontiguousarray(ii, dtype=np.int64)
@@ -261,8 +290,12 @@ def finish_rows(prep: Dict, rows: np.ndarray, alpha=1.0, beta=0.0,
     """Algorithm 1 lines 6-12 for the listed rows of C."""
     c = prep["consts"]
     rows = np.ascontiguousarray(rows, np.int64)
-    prod = int8_gemm_rows(prep["Ares"], prep["Bres"], rows)
-    U = mod_reduce(prod, c.p)
+    if prep["Ares"].shape[2] > MAX_K:
+        prod = int8_gemm_rows_blocked(prep["Ares"], prep["Bres"], rows)
+        U = mod_reduce64(prod, c.p)
+    else:
+        prod = int8_gemm_rows(prep["Ares"], prep["Bres"], rows)
+        U = mod_reduce(prod, c.p)
     Cpp = crt_fold(U, c)
     cin = None if Cin_rows is None else np.asarray(Cin_rows, np.float64)
     C64 = unscale_rows(Cpp, prep["tA"][rows], prep["tB"], float(alpha), float(beta), cin)

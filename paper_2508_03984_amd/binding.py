@@ -13,13 +13,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "liboz2.so")
 _lib = None
 
-OZ2_STAGE_SHIFT_A, OZ2_STAGE_SHIFT_B, OZ2_STAGE_RES_A, OZ2_STAGE_RES_B, OZ2_STAGE_PROD = range(5)
+OZ2_STAGE_SHIFT_A, OZ2_STAGE_SHIFT_B, OZ2_STAGE_RES_A, OZ2_STAGE_RES_B, OZ2_STAGE_PROD, OZ2_STAGE_U = range(6)
 
 EXPORTS = [
     "oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate", "oz2_shift_table_accurate",
     "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
     "oz2_constants", "oz2_shift_table", "oz2_stage_ptr", "oz2_int8_gemm", "oz2_set_profiling",
-    "oz2_last_stage_times_ms", "oz2_status_string",
+    "oz2_last_stage_times_ms", "oz2_status_string", "oz2_set_int32_products",
 ]
 
 
@@ -66,6 +66,8 @@ def load():
     lib.oz2_int8_gemm.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp]
     lib.oz2_set_profiling.argtypes = [ci]
     lib.oz2_set_profiling.restype = None
+    lib.oz2_set_int32_products.argtypes = [ci]
+    lib.oz2_set_int32_products.restype = None
     lib.oz2_last_stage_times_ms.argtypes = [C.POINTER(flt)]
     lib.oz2_status_string.argtypes = [ci]
     lib.oz2_status_string.restype = C.c_char_p
@@ -195,6 +197,10 @@ def oz2_int8_gemm(A, B, C_, batch, Mp, Np, Kp, stream=None) -> None:
                                 int(batch), Mp, Np, Kp, _stream(stream)), "oz2_int8_gemm")
 
 
+def oz2_set_int32_products(on: bool) -> None:
+    load().oz2_set_int32_products(int(bool(on)))
+
+
 def oz2_set_profiling(on: bool) -> None:
     load().oz2_set_profiling(int(bool(on)))
 
@@ -216,9 +222,11 @@ def stage_tensor(stage: int, copy: bool = True):
         shape, dtype = (dims[0],), torch.int32
     elif stage in (OZ2_STAGE_RES_A, OZ2_STAGE_RES_B):
         shape, dtype = (dims[0], dims[2] // 64, dims[1], 64), torch.int8     # K-blocked
+    elif stage == OZ2_STAGE_U:
+        shape, dtype = dims[:3], torch.uint8
     else:
         shape, dtype = dims[:3], torch.int32
-    typestr = {torch.int32: "<i4", torch.int8: "|i1"}[dtype]
+    typestr = {torch.int32: "<i4", torch.int8: "|i1", torch.uint8: "|u1"}[dtype]
     view = torch.as_tensor(_DeviceView(ptr, tuple(shape), typestr), device="cuda")
     return view.clone() if copy else view
 

@@ -20,12 +20,13 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 struct Layout {
     int64_t m, n, k, Mp, Np, Kp;
     int N;
+    bool prod_u8;
     size_t off_bt, off_ta, off_tb, off_ra, off_rb, off_prod, total;
 };
 
-Layout make_layout(int64_t m, int64_t n, int64_t k, int N) {
+Layout make_layout(int64_t m, int64_t n, int64_t k, int N, bool prod_u8) {
     Layout L{};
-    L.m = m; L.n = n; L.k = k; L.N = N;
+    L.m = m; L.n = n; L.k = k; L.N = N; L.prod_u8 = prod_u8;
     L.Mp = round_up(m, kPadMN); L.Np = round_up(n, kPadMN); L.Kp = round_up(k, kPadK);
     size_t o = 0;
     L.off_bt = o;   o += align256(std::max(column_scratch_bytes(n), accurate_scratch_bytes(m, n)));
@@ -33,7 +34,9 @@ Layout make_layout(int64_t m, int64_t n, int64_t k, int N) {
     L.off_tb = o;   o += align256((size_t)n * 4);
     L.off_ra = o;   o += align256((size_t)N * L.Mp * L.Kp);
     L.off_rb = o;   o += align256((size_t)N * L.Np * L.Kp);
-    L.off_prod = o; o += align256((size_t)N * L.Mp * L.Np * 4);
+    // products: N planes of uint8, or of int32 (diagnostic form; accurate mode also keeps
+    // its int32 Cbar in plane 0, hence at least one int32 plane)
+    L.off_prod = o; o += align256(std::max((size_t)N * L.Mp * L.Np * (prod_u8 ? 1 : 4), (size_t)L.Mp * L.Np * 4));
     L.total = o;
     return L;
 }
@@ -46,13 +49,14 @@ struct State {
     Layout last{};
     bool have_last = false;
     bool profiling = false;
+    bool int32_products = false;           // diagnostic form: keep C'_s as int32
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     bool ev_recorded = false;
 };
 State g;
 
 bool supported(int64_t k, int N) {
-    return N >= OZ2_MIN_MODULI && N <= OZ2_MAX_MODULI && k <= OZ2_MAX_K;
+    return N >= OZ2_MIN_MODULI && N <= OZ2_MAX_MODULI && k <= OZ2_MAX_K_BLOCKED;
 }
 
 oz2_status ensure_workspace(size_t need) {
@@ -83,7 +87,7 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
                      const T *B, int64_t ldb, double beta, T *C, int64_t ldc, int N,
                      hipStream_t stream, bool accurate) {
     if (m < 0 || n < 0 || k < 0) return OZ2_INVALID_ARG;
-    if (!supported(k, N)) return OZ2_UNSUPPORTED;
+    if (!supported(k, N) || (accurate && k > OZ2_MAX_K)) return OZ2_UNSUPPORTED;
     if (m == 0 || n == 0) return OZ2_OK;
     if (!C || ldc < n) return OZ2_INVALID_ARG;
     if (k == 0) {
@@ -97,7 +101,7 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
     const Table &tab = table(N, is_double);
     const ModArgs ma = make_mod_args(tab);
     const ShiftArgs sa = make_shift_args(tab);
-    const Layout L = make_layout(m, n, k, N);
+    const Layout L = make_layout(m, n, k, N, !g.int32_products);
     if (oz2_status st = ensure_workspace(L.total)) return st;
     g.last = L; g.have_last = true; g.ev_recorded = false;
 
@@ -106,16 +110,17 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
     int32_t *tB = reinterpret_cast<int32_t *>(g.ws + L.off_tb);
     int8_t *rA = reinterpret_cast<int8_t *>(g.ws + L.off_ra);
     int8_t *rB = reinterpret_cast<int8_t *>(g.ws + L.off_rb);
-    int32_t *prod = reinterpret_cast<int32_t *>(g.ws + L.off_prod);
+    void *prod = g.ws + L.off_prod;
 
     if (oz2_status st = mark(0, stream)) return st;
     if (accurate) {
         // Section 4.2, accurate mode: 7-bit matrices into slice 0, Cbar into plane 0.
         OZ2_TRY(launch_accurate_prescale<T>(A, lda, B, ldb, m, n, k, col_scratch, rA, rB, L.Mp, L.Np,
                                             L.Kp, stream));
-        OZ2_TRY(launch_int8_gemm(rA, rB, prod, 1, L.Mp, L.Np, L.Kp, stream));
-        OZ2_TRY(launch_accurate_shifts(prod, L.Np, m, n, make_accu_shift_args(tab), col_scratch, tA,
-                                       tB, stream));
+        OZ2_TRY(launch_int8_gemm(rA, rB, prod, 1, L.Mp, L.Np, L.Kp, 0, L.Kp, false, false, nullptr,
+                                 stream));
+        OZ2_TRY(launch_accurate_shifts(static_cast<const int32_t *>(prod), L.Np, m, n,
+                                       make_accu_shift_args(tab), col_scratch, tA, tB, stream));
     } else {
         OZ2_TRY(launch_shifts<T>(A, lda, m, k, sa, tA, stream));
         OZ2_TRY(launch_shifts_cols<T>(B, ldb, k, n, sa, col_scratch, tB, stream));
@@ -124,9 +129,16 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
     OZ2_TRY(launch_residues<T>(A, lda, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
     OZ2_TRY(launch_residues_cols<T>(B, ldb, k, n, tB, ma, rB, L.Np, L.Kp, stream));
     if (oz2_status st = mark(2, stream)) return st;
-    OZ2_TRY(launch_int8_gemm(rA, rB, prod, N, L.Mp, L.Np, L.Kp, stream));
+    // Section 4.3: INT32 accumulation is exact for k <= 2^17; a longer contraction is cut into
+    // K ranges of at most 2^17 whose reduced results are folded together modulo p_s.
+    for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
+        const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
+        OZ2_TRY(launch_int8_gemm(rA, rB, prod, N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0, &ma,
+                                 stream));
+    }
     if (oz2_status st = mark(3, stream)) return st;
-    OZ2_TRY(launch_epilogue<T>(prod, L.Mp, L.Np, m, n, tA, tB, ma, alpha, beta, C, ldc, stream));
+    OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, L.Mp, L.Np, m, n, tA, tB, ma, alpha, beta, C, ldc,
+                               stream));
     if (oz2_status st = mark(4, stream)) return st;
     g.ev_recorded = g.profiling;
     return OZ2_OK;
@@ -165,7 +177,7 @@ oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha, const float *
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double) {
     if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
     (void)is_double;                                          // the workspace holds no input-typed data
-    return make_layout(m, n, k, num_moduli).total;
+    return make_layout(m, n, k, num_moduli, !g.int32_products).total;
 }
 
 oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes) {
@@ -239,7 +251,12 @@ oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims) {
     case OZ2_STAGE_SHIFT_B: *dev_ptr = g.ws + L.off_tb; dims[0] = L.n; dims[1] = dims[2] = dims[3] = 0; break;
     case OZ2_STAGE_RES_A: *dev_ptr = g.ws + L.off_ra; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Kp; dims[3] = L.m; break;
     case OZ2_STAGE_RES_B: *dev_ptr = g.ws + L.off_rb; dims[0] = L.N; dims[1] = L.Np; dims[2] = L.Kp; dims[3] = L.n; break;
-    case OZ2_STAGE_PROD: *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
+    case OZ2_STAGE_PROD:
+        if (L.prod_u8) return OZ2_INVALID_ARG;                // not kept in this form: see oz2_set_int32_products
+        *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
+    case OZ2_STAGE_U:
+        if (!L.prod_u8) return OZ2_INVALID_ARG;
+        *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
     default: return OZ2_INVALID_ARG;
     }
     return OZ2_OK;
@@ -250,8 +267,14 @@ oz2_status oz2_int8_gemm(const int8_t *dev_A, const int8_t *dev_B, int32_t *dev_
     if (!dev_A || !dev_B || !dev_C || batch < 1 || batch > 65535 || Mp < kPadMN || Np < kPadMN ||
         Kp < kPadK || Mp % kPadMN || Np % kPadMN || Kp % kPadK)
         return OZ2_INVALID_ARG;
-    OZ2_TRY(launch_int8_gemm(dev_A, dev_B, dev_C, batch, Mp, Np, Kp, stream));
+    if (Kp > OZ2_MAX_K) return OZ2_UNSUPPORTED;
+    OZ2_TRY(launch_int8_gemm(dev_A, dev_B, dev_C, batch, Mp, Np, Kp, 0, Kp, false, false, nullptr, stream));
     return OZ2_OK;
+}
+
+void oz2_set_int32_products(int on) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.int32_products = on != 0;
 }
 
 void oz2_set_profiling(int on) {

@@ -223,8 +223,9 @@ Table build(int n, bool is_double) {
         for (int i = 0; i < n; ++i) { t.s1[i] = w[i].to_double(); t.s2[i] = 0.0; }
     }
 
-    // Shift table: theta[j] = largest T in [2^30, 2^49] with level_of(T) >= f_max - j.
-    const uint64_t Tmin = 1ull << 30, Tmax = 1ull << 49;
+    // Shift table: theta[j] = largest T in [2^30, 2^52] with level_of(T) >= f_max - j
+    // (T <= 2^32 k, and k <= 2^20 is the longest supported contraction).
+    const uint64_t Tmin = 1ull << 30, Tmax = 1ull << 52;
     double Pf = (double)t.Pfast;
     t.f_max = level_of(Tmin, Pf);
     int32_t f_min = level_of(Tmax, Pf);

@@ -75,11 +75,24 @@ __device__ inline void map_tile(const TileMap &tm, int id, int &s, int &tr, int 
     }
 }
 
-template <int WM, int WN, int TM, int TN, int BK, int STAGES>
+// What the store phase writes (Algorithm 1 lines 6-7):
+//   kOutI32      C'_s as int32 (diagnostics: the raw products)
+//   kOutI32Fold  int32: mod(old, p_s) + mod(C'_s, p_s)   (a further K range of a k > 2^17 product)
+//   kOutU8       U_s = mod(C'_s, p_s) as uint8 -- the form the accumulation kernel wants
+//   kOutU8Fold   uint8: (old + mod(C'_s, p_s)) mod p_s
+enum { kOutI32 = 0, kOutI32Fold = 1, kOutU8 = 2, kOutU8Fold = 3 };
+
+struct GemmMods {                       // moduli of the slices and their mulhi multipliers
+    int32_t p[kMaxModuli];
+    int32_t pinv_prime[kMaxModuli];
+};
+
+template <int WM, int WN, int TM, int TN, int BK, int STAGES, int OUT>
 __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__restrict__ A,
                                                    const int8_t *__restrict__ B,
-                                                   int32_t *__restrict__ C, int64_t Mp,
-                                                   int64_t Np, int64_t Kp, TileMap tmap) {
+                                                   void *__restrict__ C, int64_t Mp,
+                                                   int64_t Np, int64_t KB, int kb0, int KT,
+                                                   TileMap tmap, GemmMods mods) {
     constexpr int THREADS = 64 * WM * WN;              // WM x WN wavefronts
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
@@ -103,9 +116,9 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
     int s, tile_r, tile_c;
     map_tile(tmap, (int)blockIdx.x, s, tile_r, tile_c);
     const int64_t bm = (int64_t)tile_r * BM, bn = (int64_t)tile_c * BN;
-    const int64_t KB = Kp / BK;                        // K blocks per slice
-    const int8_t *Ab = A + ((int64_t)s * KB * Mp + bm) * BK;      // K block 0 of this tile
-    const int8_t *Bb = B + ((int64_t)s * KB * Np + bn) * BK;
+    // KB = K blocks per slice; this launch contracts over blocks [kb0, kb0 + KT).
+    const int8_t *Ab = A + (((int64_t)s * KB + kb0) * Mp + bm) * BK;
+    const int8_t *Bb = B + (((int64_t)s * KB + kb0) * Np + bn) * BK;
 
     // Load i of this wavefront fills LDS chunks [64 q, 64 q + 64) of a stage, q = wave*LPT + i,
     // i.e. rows q*ROWS_PER_LOAD ...; lane -> (row, physical chunk) -> logical chunk to fetch.
@@ -130,7 +143,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
     };
     auto issue_tile = [&](int t) { issue_loads(t, 0, LPT); };
 
-    const int KT = (int)(Kp / BK);                     // >= 2: Kp is a multiple of 128
+    // KT >= 2: every K range is a multiple of 128.
 #pragma unroll
     for (int t = 0; t < STAGES - 1; ++t)
         if (t < KT) issue_tile(t);
@@ -181,7 +194,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
             // waited down to zero at that point) does not wait for the new requests.
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][0], fb[cur][j],
+                acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][0],
                                                                   acc[0][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (kk + 1 < KK) load_frags(nxt, kt, kk + 1);
@@ -191,7 +204,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
             for (int i = 1; i < TM; ++i) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][i], fb[cur][j],
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][i],
                                                                       acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 const int slot = kk * (TM - 1) + (i - 1);
@@ -207,30 +220,62 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
         __builtin_amdgcn_s_barrier();
     }
 
-    // Accumulator layout of the 32x32 MFMA: lane l, register r holds
-    // row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-    int32_t *Cb = C + ((int64_t)s * Mp + bm) * Np + bn;
+    // The B fragment is the MFMA's first operand, so the 32x32 accumulator is the transposed
+    // tile: lane l holds row (l % 32) of the C tile and, in registers 4g .. 4g+3, the four
+    // consecutive columns 8g + 4*(l / 32) + {0,1,2,3}.  One 16-byte (int32) or 4-byte (uint8)
+    // store per g.
+    // (the mulhi form: an FP64 floor/fma version of this reduction measured 1.1 ms slower
+    // per launch at 16 x 16384^3)
+    const int p = mods.p[s], pv = mods.pinv_prime[s];
+    const int64_t c_off = ((int64_t)s * Mp + bm) * Np + bn;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = wm * 32 * TM + i * 32 + 8 * (r / 4) + 4 * lhalf + (r % 4);
-                int col = wn * 32 * TN + j * 32 + lrow;
-                Cb[(int64_t)row * Np + col] = acc[i][j][r];
+            for (int g = 0; g < 4; ++g) {
+                const int row = wm * 32 * TM + i * 32 + lrow;
+                const int col = wn * 32 * TN + j * 32 + 8 * g + 4 * lhalf;
+                const int64_t at = c_off + (int64_t)row * Np + col;
+                int v[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
+                if (OUT == kOutI32 || OUT == kOutI32Fold) {
+                    v4i *dst = reinterpret_cast<v4i *>(static_cast<int32_t *>(C) + at);
+                    if (OUT == kOutI32Fold) {
+                        const v4i old = *dst;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) v[c] = mod_small(old[c], p, pv) + mod_small(v[c], p, pv);
+                    }
+                    *dst = v4i{v[0], v[1], v[2], v[3]};
+                } else {
+                    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(C) + at);
+                    uint32_t packed = 0;
+                    const uint32_t old = OUT == kOutU8Fold ? *dst : 0u;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        int u = mod_small(v[c], p, pv);
+                        if (OUT == kOutU8Fold) {
+                            u += (int)((old >> (8 * c)) & 0xffu);
+                            u -= (u >= p) ? p : 0;
+                        }
+                        packed |= (uint32_t)u << (8 * c);
+                    }
+                    *dst = packed;
+                }
             }
 }
 
-template <int WM, int WN, int TM, int TN, int BK, int STAGES>
-hipError_t launch(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64_t Mp, int64_t Np,
-                  int64_t Kp, hipStream_t stream) {
+template <int WM, int WN, int TM, int TN, int BK, int STAGES, int OUT>
+hipError_t launch(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp, int64_t Np,
+                  int64_t Kp, int64_t k_begin, int64_t k_len, const GemmMods &mods,
+                  hipStream_t stream) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(&k_int8_gemm<WM, WN, TM, TN, BK, STAGES>),
+            reinterpret_cast<const void *>(&k_int8_gemm<WM, WN, TM, TN, BK, STAGES, OUT>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -241,22 +286,40 @@ hipError_t launch(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64
     tm.swizzled = (tm.tiles_m % 16 == 0 && tm.tiles_n % 16 == 0) ? 1 : 0;
     const int64_t total = (int64_t)tm.tiles_m * tm.tiles_n * batch;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_int8_gemm<WM, WN, TM, TN, BK, STAGES>), dim3((unsigned)total), dim3(64 * WM * WN), lds_bytes,
-                       stream, A, B, C, Mp, Np, Kp, tm);
+    hipLaunchKernelGGL((k_int8_gemm<WM, WN, TM, TN, BK, STAGES, OUT>), dim3((unsigned)total),
+                       dim3(64 * WM * WN), lds_bytes, stream, A, B, C, Mp, Np, Kp / BK,
+                       (int)(k_begin / BK), (int)(k_len / BK), tm, mods);
     return hipGetLastError();
+}
+
+template <int OUT>
+hipError_t launch_out(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp, int64_t Np,
+                      int64_t Kp, int64_t k_begin, int64_t k_len, const GemmMods &mods,
+                      hipStream_t stream) {
+    // Small problems get the 128 x 128 tile so that more workgroups exist.
+    if (Mp * Np * batch < (int64_t)256 * 256 * 512)
+        return launch<2, 2, 2, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
+    // 8 wavefronts (2 per SIMD), each 128 x 64: measured against 4 wavefronts of 128 x 128 on
+    // the same device it is 2 % faster at 16 x 16384^3 -- a wavefront that is held up issuing
+    // a load leaves the matrix core to its SIMD partner.
+    return launch<2, 4, 4, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
 }
 
 }  // namespace
 
-hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64_t Mp,
-                            int64_t Np, int64_t Kp, hipStream_t stream) {
-    // Small problems get the 128 x 128 tile so that more workgroups exist.
-    if (Mp * Np * batch < (int64_t)256 * 256 * 512)
-        return launch<2, 2, 2, 2, 64, 4>(A, B, C, batch, Mp, Np, Kp, stream);
-    // 8 wavefronts (2 per SIMD), each 128 x 64: measured 58.6 ms at 16 x 16384^3 against
-    // 63.5 ms for 4 wavefronts of 128 x 128 -- a wavefront that is held up issuing a load
-    // leaves the matrix core to its SIMD partner.
-    return launch<2, 4, 4, 2, 64, 4>(A, B, C, batch, Mp, Np, Kp, stream);
+hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp,
+                            int64_t Np, int64_t Kp, int64_t k_begin, int64_t k_len, bool as_u8,
+                            bool fold, const ModArgs *ma, hipStream_t stream) {
+    GemmMods mods{};
+    if (ma)
+        for (int i = 0; i < ma->n; ++i) { mods.p[i] = ma->p[i]; mods.pinv_prime[i] = (int32_t)ma->pinv_prime[i]; }
+    else if (as_u8 || fold)
+        return hipErrorInvalidValue;                       // the reduced forms need the moduli
+    if (as_u8)
+        return fold ? launch_out<kOutU8Fold>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream)
+                    : launch_out<kOutU8>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
+    return fold ? launch_out<kOutI32Fold>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream)
+                : launch_out<kOutI32>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
 }
 
 }  // namespace oz2

@@ -45,6 +45,15 @@ __device__ inline int floor_log2_of_bits(uint64_t bits) {
     if (ex) return ex - 1023;
     return (63 - __clzll((long long)bits)) - 1074;
 }
+
+// mod(x, p) in [0, p) for any int32 x and the moduli of Section 4.1, by the mulhi reduction
+// of Section 4.3: y = x - mulhi(x, pinv') p, then one conditional subtraction and addition.
+__device__ inline int mod_small(int x, int p, int pinv_prime) {
+    int y = x - __mulhi(x, pinv_prime) * p;
+    y -= (y >= p) ? p : 0;
+    y += (y < 0) ? p : 0;
+    return y;
+}
 #endif
 
 // Algorithm 1 line 1 (fast mode): one shift per row of X (rows x len, leading dimension ld).
@@ -105,17 +114,25 @@ template <typename T>
 hipError_t launch_col_maxbits(const T *X, int64_t ld, int64_t rows, int64_t cols,
                               unsigned long long *colmax, hipStream_t stream);
 
-// Algorithm 1 line 6: C[b] = A[b] * B[b]^T for b < batch, int8 in, wrapping int32 out.
-// A: [batch][Kp/64][Mp][64], B: [batch][Kp/64][Np][64] (K-blocked, see launch_residues),
-// C: [batch][Mp][Np]; Mp, Np multiples of kPadMN, Kp a multiple of kPadK.
-hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, int32_t *C, int batch, int64_t Mp,
-                            int64_t Np, int64_t Kp, hipStream_t stream);
+// Algorithm 1 lines 6-7: for b < batch, the contraction of A[b] and B[b]^T over the K range
+// [k_begin, k_begin + k_len) (multiples of kPadK), int8 in, wrapping int32 accumulation.
+// A: [batch][Kp/64][Mp][64], B: [batch][Kp/64][Np][64] (K-blocked, see launch_residues);
+// Mp, Np multiples of kPadMN.  C is [batch][Mp][Np] and receives
+//   as_u8 = false, fold = false   the int32 sums C'_b
+//   as_u8 = true,  fold = false   U_b = mod(C'_b, p_b) as uint8
+//   fold = true                   the same combined with what C already holds, for the
+//                                 second and later K ranges of a product with k > 2^17:
+//                                 int32: mod(old) + mod(new);  uint8: (old + mod(new)) mod p_b
+// ma supplies the moduli (slice b uses p_b); it may be NULL for the plain int32 form.
+hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp,
+                            int64_t Np, int64_t Kp, int64_t k_begin, int64_t k_len, bool as_u8,
+                            bool fold, const ModArgs *ma, hipStream_t stream);
 
 // Algorithm 1 lines 7-12 and the alpha/beta update, fused:
 // C[i][j] = alpha * ldexp(C''(i,j), -(tA[i]+tB[j])) + beta * C[i][j]   (OutT = double or float)
-// prod: [n_mod][Mp][Np] int32.
+// prod: [n_mod][Mp][Np], int32 sums (prod_is_u8 = false; reduced here) or uint8 residues U_s.
 template <typename OutT>
-hipError_t launch_epilogue(const int32_t *prod, int64_t Mp, int64_t Np, int64_t m, int64_t n,
+hipError_t launch_epilogue(const void *prod, bool prod_is_u8, int64_t Mp, int64_t Np, int64_t m, int64_t n,
                            const int32_t *tA, const int32_t *tB, const ModArgs &ma, double alpha,
                            double beta, OutT *C, int64_t ldc, hipStream_t stream);
 

@@ -187,12 +187,6 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
 // Q = rint(P_inv C1), C'' = fma(-P2, Q, fma(-P1, Q, C1) + C2), c = C'' 2^-(tA_i + tB_j).
 // One thread per 4 consecutive columns (16-byte loads of the int32 planes).
 // ----------------------------------------------------------------------------------------
-__device__ inline int mod_small(int x, int p, int pinv_prime) {
-    int y = x - __mulhi(x, pinv_prime) * p;
-    y -= (y >= p) ? p : 0;
-    y += (y < 0) ? p : 0;
-    return y;
-}
 
 template <typename OutT>
 __device__ inline OutT finish(double c, double alpha, double beta, const OutT *Cin) {
@@ -202,8 +196,10 @@ __device__ inline OutT finish(double c, double alpha, double beta, const OutT *C
     return (OutT)r;
 }
 
-template <typename OutT>
-__global__ __launch_bounds__(256) void k_epilogue(const int32_t *__restrict__ prod, int64_t Mp,
+// IN_U8: the GEMM already reduced its sums (prod holds U_s as uint8, 4 bytes per thread and
+// modulus); otherwise prod holds int32 sums (possibly folded partial sums) reduced here.
+template <typename OutT, bool IN_U8>
+__global__ __launch_bounds__(256) void k_epilogue(const void *__restrict__ prod_, int64_t Mp,
                                                   int64_t Np, int64_t m, int64_t n,
                                                   const int32_t *__restrict__ tA,
                                                   const int32_t *__restrict__ tB, ModArgs ma,
@@ -215,16 +211,26 @@ __global__ __launch_bounds__(256) void k_epilogue(const int32_t *__restrict__ pr
     const int64_t i = idx / quads, j0 = (idx % quads) * 4;
 
     const int64_t plane = Mp * Np;
-    const int32_t *src = prod + i * Np + j0;                          // Np % 4 == 0, j0 + 3 < Np
+    const int64_t at = i * Np + j0;                                   // Np % 4 == 0, j0 + 3 < Np
     double C1[4] = {0, 0, 0, 0}, C2[4] = {0, 0, 0, 0};
     for (int s = 0; s < ma.n; ++s) {
-        const int4 x = *reinterpret_cast<const int4 *>(src + (int64_t)s * plane);
-        const int p = ma.p[s], pv = (int)ma.pinv_prime[s];
         const double s1 = ma.s1[s], s2 = ma.s2[s];
-        const int xs[4] = {x.x, x.y, x.z, x.w};
+        int us[4];
+        if (IN_U8) {
+            const uint32_t x = *reinterpret_cast<const uint32_t *>(
+                static_cast<const uint8_t *>(prod_) + (int64_t)s * plane + at);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) us[c] = (int)((x >> (8 * c)) & 0xffu);
+        } else {
+            const int4 x = *reinterpret_cast<const int4 *>(
+                static_cast<const int32_t *>(prod_) + (int64_t)s * plane + at);
+            const int p = ma.p[s], pv = (int)ma.pinv_prime[s];
+            us[0] = mod_small(x.x, p, pv); us[1] = mod_small(x.y, p, pv);
+            us[2] = mod_small(x.z, p, pv); us[3] = mod_small(x.w, p, pv);
+        }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            double u = (double)mod_small(xs[c], p, pv);
+            const double u = (double)us[c];
             C1[c] = fma(s1, u, C1[c]);
             C2[c] = fma(s2, u, C2[c]);
         }
@@ -288,12 +294,16 @@ hipError_t launch_magnitudes(const T *X, int64_t ld, int64_t rows, int64_t len, 
 }
 
 template <typename OutT>
-hipError_t launch_epilogue(const int32_t *prod, int64_t Mp, int64_t Np, int64_t m, int64_t n,
-                           const int32_t *tA, const int32_t *tB, const ModArgs &ma, double alpha,
-                           double beta, OutT *C, int64_t ldc, hipStream_t stream) {
+hipError_t launch_epilogue(const void *prod, bool prod_is_u8, int64_t Mp, int64_t Np, int64_t m,
+                           int64_t n, const int32_t *tA, const int32_t *tB, const ModArgs &ma,
+                           double alpha, double beta, OutT *C, int64_t ldc, hipStream_t stream) {
     const int64_t threads = m * ((n + 3) / 4);
-    hipLaunchKernelGGL((k_epilogue<OutT>), dim3(blocks_for(threads)), dim3(256), 0, stream, prod,
-                       Mp, Np, m, n, tA, tB, ma, alpha, beta, C, ldc);
+    if (prod_is_u8)
+        hipLaunchKernelGGL((k_epilogue<OutT, true>), dim3(blocks_for(threads)), dim3(256), 0, stream,
+                           prod, Mp, Np, m, n, tA, tB, ma, alpha, beta, C, ldc);
+    else
+        hipLaunchKernelGGL((k_epilogue<OutT, false>), dim3(blocks_for(threads)), dim3(256), 0, stream,
+                           prod, Mp, Np, m, n, tA, tB, ma, alpha, beta, C, ldc);
     return hipGetLastError();
 }
 
@@ -314,9 +324,10 @@ hipError_t launch_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n, double bet
     template hipError_t launch_residues<T>(const T *, int64_t, int64_t, int64_t, const int32_t *, \
                                            const ModArgs &, int8_t *, int64_t, int64_t,           \
                                            hipStream_t);                                          \
-    template hipError_t launch_epilogue<T>(const int32_t *, int64_t, int64_t, int64_t, int64_t,  \
-                                           const int32_t *, const int32_t *, const ModArgs &,     \
-                                           double, double, T *, int64_t, hipStream_t);            \
+    template hipError_t launch_epilogue<T>(const void *, bool, int64_t, int64_t, int64_t,        \
+                                           int64_t, const int32_t *, const int32_t *,             \
+                                           const ModArgs &, double, double, T *, int64_t,         \
+                                           hipStream_t);                                          \
     template hipError_t launch_scale_c<T>(T *, int64_t, int64_t, int64_t, double, hipStream_t);
 OZ2_INSTANTIATE(double)
 OZ2_INSTANTIATE(float)

@@ -61,11 +61,11 @@ def test_shift_table_matches_the_formula_at_every_threshold(oz, oracle, n):
     tab = oz.oz2_shift_table(n)
     c = K.constants(n)
     theta = [int(x) for x in tab["theta"]]
-    assert theta == sorted(theta) and theta[-1] == 2 ** 49 and theta[0] >= 2 ** 30
+    assert theta == sorted(theta) and theta[-1] == 2 ** 52 and theta[0] >= 2 ** 30
     probes = [2 ** 30]
     for th in theta:
         probes += [th - 1, th, th + 1]
-    probes = [T for T in probes if 2 ** 30 <= T <= 2 ** 49]
+    probes = [T for T in probes if 2 ** 30 <= T <= 2 ** 52]
     # rows whose integer sum T is exactly a probe: one entry 1.0 (q = 2^15) plus filler
     # entries are not needed -- the oracle's formula is evaluated through its own C code
     # by building vectors with a prescribed T: q values are free integers in [0, 2^16].
@@ -110,12 +110,16 @@ def test_argument_checks_need_no_gpu(oz):
         m, n, k, 1.0, A, k if lda is None else lda, B, n if ldb is None else ldb, 0.0, Cc,
         n if ldc is None else ldc, N, null)
     assert call(4, 4, 4, 1) == 2 and call(4, 4, 4, 21) == 2          # unsupported N
-    assert call(4, 4, 2 ** 17 + 1, 14) == 2                           # k too large
+    assert call(4, 4, 2 ** 20 + 1, 14) == 2                           # k too large
     assert call(-1, 4, 4, 14) == 1
     assert call(4, 4, 4, 14, A=null) == 1 and call(4, 4, 4, 14, Cc=null) == 1
     assert call(4, 4, 4, 14, lda=3) == 1 and call(4, 4, 4, 14, ldb=3) == 1 and call(4, 4, 4, 14, ldc=3) == 1
     assert call(0, 4, 4, 14) == 0 and call(4, 0, 4, 14) == 0          # empty: no-op
     assert oz.oz2_workspace_bytes(4, 4, 4, 1) == 0
+    assert oz.oz2_workspace_bytes(256, 256, 256, 14) >= 14 * (2 * 256 * 256 + 256 * 256)
+    lib.oz2_set_int32_products(1)
     assert oz.oz2_workspace_bytes(256, 256, 256, 14) >= 14 * (2 * 256 * 256 + 4 * 256 * 256)
+    lib.oz2_set_int32_products(0)
+    assert lib.oz2_int8_gemm(one, one, one, 1, 256, 256, 2 ** 17 + 128, null) == 2
     assert lib.oz2_int8_gemm(one, one, one, 1, 100, 256, 128, null) == 1
     assert "moduli" in oz.oz2_status_string(2)

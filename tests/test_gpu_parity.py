@@ -26,8 +26,10 @@ def oz():
     oz.oz2_release()
 
 
-def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, accurate=False):
-    """Run oz2_dgemm / oz2_sgemm and fetch every stage, trimmed to the logical shapes."""
+def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, accurate=False,
+             int32_products=False):
+    """Run oz2_dgemm / oz2_sgemm and fetch every stage, trimmed to the logical shapes.  By
+    default the GEMM emits U_s (uint8); with int32_products the diagnostic form C'_s."""
     import torch
     m, k = A.shape
     n = B.shape[1]
@@ -42,7 +44,11 @@ def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, acc
         fn = oz.oz2_dgemm_accurate if dt == torch.float64 else oz.oz2_sgemm_accurate
     else:
         fn = oz.oz2_dgemm if dt == torch.float64 else oz.oz2_sgemm
-    fn(m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+    oz.oz2_set_int32_products(int32_products)
+    try:
+        fn(m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+    finally:
+        oz.oz2_set_int32_products(False)
     torch.cuda.synchronize()
     from paper_2508_03984_amd import binding as b
     out = dict(C=dC.cpu().numpy())
@@ -50,12 +56,18 @@ def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, acc
     out["tB"] = oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy()
     ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A))
     rb = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_B))
-    pr = oz.stage_tensor(b.OZ2_STAGE_PROD)
+    if int32_products:
+        out["prod"] = oz.stage_tensor(b.OZ2_STAGE_PROD)[:, :m, :n].cpu().numpy()
+        with pytest.raises(oz.OZ2Error):
+            oz.oz2_stage_ptr(b.OZ2_STAGE_U)
+    else:
+        out["U"] = oz.stage_tensor(b.OZ2_STAGE_U)[:, :m, :n].cpu().numpy()
+        with pytest.raises(oz.OZ2Error):
+            oz.oz2_stage_ptr(b.OZ2_STAGE_PROD)
     out["pad_clean"] = bool((ra[:, m:, :] == 0).all() and (ra[:, :, k:] == 0).all()
                             and (rb[:, n:, :] == 0).all() and (rb[:, :, k:] == 0).all())
     out["Ares"] = ra[:, :m, :k].cpu().numpy()
     out["Bres"] = rb[:, :n, :k].cpu().numpy()
-    out["prod"] = pr[:, :m, :n].cpu().numpy()
     return out
 
 
@@ -65,7 +77,10 @@ def assert_parity(got, ref, is_double):
     assert got["pad_clean"], "padding of the residue slices is not zero"
     assert np.array_equal(got["Ares"], ref["Ares"]), "residues of A differ"
     assert np.array_equal(got["Bres"], ref["Bres"]), "residues of B differ"
-    assert np.array_equal(got["prod"], ref["prod"]), "INT32 products differ"
+    if "prod" in got:
+        assert np.array_equal(got["prod"], ref["prod"]), "INT32 products differ"
+    if "U" in got:
+        assert np.array_equal(got["U"], ref["U"]), "reduced products U_s differ"
     c, r = got["C"].astype(np.float64), ref["C"].astype(np.float64)
     denom = np.where(r == 0, 1.0, np.abs(r))
     rel = np.max(np.abs(c - r) / denom) if c.size else 0.0
@@ -94,8 +109,29 @@ def test_stage_parity(oz, oracle, m, n, k, N, phi, dtype):
     A, B = S.gemm_inputs(m, n, k, phi, seed=10 + N, dtype=dtype)
     is_double = dtype == np.float64
     ref = oracle.gemm(A, B, N, is_double=is_double)
-    got = gpu_gemm(oz, A, B, N)
-    assert_parity(got, ref, is_double)
+    assert_parity(gpu_gemm(oz, A, B, N), ref, is_double)
+    assert_parity(gpu_gemm(oz, A, B, N, int32_products=True), ref, is_double)
+
+
+def test_k_beyond_2_pow_17_is_blocked(oz, oracle):
+    """Section 4.3: k > 2^17 by block matrix multiplication; the residues of the K ranges are
+    folded modulo p_s (compare U_s and C; the int32 planes are only congruent to C'_s)."""
+    m, n, k = 64, 96, 2 ** 17 + 3 * 128 + 5
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=7)
+    ref = oracle.gemm(A, B, 14)
+    got = gpu_gemm(oz, A, B, 14)
+    assert_parity(got, ref, True)
+    got = gpu_gemm(oz, A, B, 14, int32_products=True)
+    p = np.array(ref["consts"].p)[:, None, None]
+    assert np.array_equal(np.mod(got.pop("prod").astype(np.int64), p), ref["U"])
+    assert_parity(got, ref, True)
+    A32, B32 = A[:, :2 ** 17 + 128].astype(np.float32), B[:2 ** 17 + 128].astype(np.float32)
+    assert_parity(gpu_gemm(oz, A32, B32, 8), oracle.gemm(A32, B32, 8, is_double=False), False)
+    import torch
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    with pytest.raises(oz.OZ2Error) as e:                 # accurate mode: single INT32 Cbar only
+        oz.matmul(dA, dB, 14, accurate=True)
+    assert e.value.status == 2
 
 
 ACCURATE_CASES = [
@@ -237,14 +273,18 @@ def test_caller_owned_workspace(oz, oracle):
 
 # ------------------------------------------------------------------ benchmark-size configurations
 def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries=1500,
-                   accurate=False):
+                   accurate=False, int32_products=False):
     """Full comparison of shifts and residues, sampled comparison of products and C."""
     import torch
     from paper_2508_03984_amd import binding as b
     is_double = dtype == np.float64
     A, B = S.gemm_inputs(m, n, k, phi, seed, dtype)
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
-    dC = oz.matmul(dA, dB, N, accurate=accurate)
+    oz.oz2_set_int32_products(int32_products)
+    try:
+        dC = oz.matmul(dA, dB, N, accurate=accurate)
+    finally:
+        oz.oz2_set_int32_products(False)
     torch.cuda.synchronize()
     prep = oracle.prepare(A, B, N, is_double, accurate)
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
@@ -260,13 +300,14 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
     rng = np.random.default_rng(seed)
     rows = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, n_rows)]))
     fin = oracle.finish_rows(prep, rows)
-    prod = oz.stage_tensor(b.OZ2_STAGE_PROD, copy=False)
+    stage, key = (b.OZ2_STAGE_PROD, "prod") if int32_products else (b.OZ2_STAGE_U, "U")
+    prod = oz.stage_tensor(stage, copy=False)
     got_rows = prod[:, torch.from_numpy(rows).cuda(), :n].cpu().numpy()
-    assert np.array_equal(got_rows, fin["prod"]), "INT32 products differ on sampled rows"
+    assert np.array_equal(got_rows, fin[key]), f"{key} differs on sampled rows"
     ii = rng.integers(0, m, n_entries); jj = rng.integers(0, n, n_entries)
     ent = oracle.finish_entries(prep, ii, jj)
     ti, tj = torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()
-    assert np.array_equal(prod[:, ti, tj].cpu().numpy(), ent["prod"])
+    assert np.array_equal(prod[:, ti, tj].cpu().numpy(), ent[key])
     del prod
     tol = TOL64 if is_double else TOL32
     for got, ref in ((dC[torch.from_numpy(rows).cuda()].cpu().numpy(), fin["C"]),
@@ -279,6 +320,7 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
 def test_config_4096_sampled(oz, oracle):
     for N in (12, 16, 20):
         sampled_parity(oz, oracle, 4096, 4096, 4096, N, 0.5, np.float64, seed=0)
+    sampled_parity(oz, oracle, 4096, 4096, 4096, 14, 0.5, np.float64, seed=0, int32_products=True)
 
 
 def test_config_4096_accurate_sampled(oz, oracle):

@@ -216,6 +216,30 @@ def test_int32_wraps_only_at_k_2_pow_17_and_harmlessly(oracle):
     assert prod[0, 0, 0] == 2 ** 31 - 128 * 128
 
 
+def test_blocked_product_for_k_beyond_2_pow_17(oracle):
+    """Section 4.3, last sentence: block matrix multiplication.  Range sums wrap like the
+    INT32 engine, their integer sum is congruent to the exact product modulo every p_s."""
+    rng = np.random.default_rng(3)
+    k = 2 ** 17 + 640
+    A = rng.integers(-128, 128, (2, 2, k), dtype=np.int8)
+    B = rng.integers(-128, 128, (2, 3, k), dtype=np.int8)
+    A[0, 0, :] = -128; B[0, 0, :] = -128                   # range 1 sums to 2^31 and wraps
+    got = oracle.int8_gemm_rows_blocked(A, B, np.arange(2))
+    exact = np.einsum("sik,sjk->sij", A.astype(np.int64), B.astype(np.int64))
+    assert got[0, 0, 0] == -2 ** 31 + 640 * 128 * 128 and exact[0, 0, 0] == 2 ** 31 + 640 * 128 * 128
+    got[0, 0, 0] += 2 ** 32
+    assert np.array_equal(got, exact)
+    for p in (256, 255, 173):
+        U = oracle.mod_reduce64(oracle.int8_gemm_rows_blocked(A, B, np.arange(2)), [p, p])
+        if p == 256:                                     # the wrap by 2^32 is invisible modulo 256
+            assert np.array_equal(U, np.mod(exact, p))
+        else:                                            # -128 residues only occur for p = 256
+            assert np.array_equal(U[1], np.mod(exact[1], p))
+    small = oracle.int8_gemm_rows_blocked(A[:, :, :1000], B[:, :, :1000], np.arange(2), kblock=300)
+    assert np.array_equal(small, np.einsum("sik,sjk->sij", A[:, :, :1000].astype(np.int64),
+                                           B[:, :, :1000].astype(np.int64)))
+
+
 # --------------------------------------------------------------------------- line 7: mod
 def test_mod_reduce_against_floor_definition(oracle):
     c = K.constants(20)
