@@ -43,7 +43,8 @@ constexpr int kWave = 64;
 
 // ----------------------------------------------------------------------------------------
 // Shifts.  One workgroup per row: pass 1 finds max|x| (as an integer compare of the FP64
-// bit patterns), pass 2 re-reads the row (from L2) and sums q^2 with
+// bit patterns), pass 2 re-reads the row (mostly from L2 / the memory-side cache; keeping the
+// row in registers instead measured slower, 0.81 against 0.67 ms at 16384^2) and sums q^2 with
 // q = ceil(|x| 2^(15-e)) <= 2^16 in 64-bit integers, which is exact and independent of
 // the order of summation.  f comes from the threshold table, t = f - e.
 // ----------------------------------------------------------------------------------------
@@ -150,11 +151,24 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
     if (r < rows) {
         const int sh = t[r];
         const T *x = X + r * ld + h0;
+        T raw[kResPerThread];
+        if (h0 + kResPerThread <= len && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+            // whole piece in range and 16-byte aligned: 16-byte loads (1.9 -> 1.3 ms at 16384^2)
+            constexpr int kVec = 16 / sizeof(T);
+            typedef T vec_t __attribute__((ext_vector_type(kVec)));
+#pragma unroll
+            for (int i = 0; i < kResPerThread / kVec; ++i) {
+                const vec_t q = reinterpret_cast<const vec_t *>(x)[i];
+#pragma unroll
+                for (int c = 0; c < kVec; ++c) raw[i * kVec + c] = q[c];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kResPerThread; ++i) raw[i] = (h0 + i < len) ? x[i] : T(0);
+        }
 #pragma unroll
         for (int i = 0; i < kResPerThread; ++i)
-            v[i] = (h0 + i >= len) ? 0.0
-                   : KIND == 0   ? trunc(ldexp((double)x[i], sh))
-                                 : ceil(ldexp(fabs((double)x[i]), sh));
+            v[i] = KIND == 0 ? trunc(ldexp((double)raw[i], sh)) : ceil(ldexp(fabs((double)raw[i]), sh));
     } else {
 #pragma unroll
         for (int i = 0; i < kResPerThread; ++i) v[i] = 0.0;
