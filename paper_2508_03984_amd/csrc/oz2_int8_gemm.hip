@@ -223,7 +223,9 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
     // The B fragment is the MFMA's first operand, so the 32x32 accumulator is the transposed
     // tile: lane l holds row (l % 32) of the C tile and, in registers 4g .. 4g+3, the four
     // consecutive columns 8g + 4*(l / 32) + {0,1,2,3}.  One 16-byte (int32) or 4-byte (uint8)
-    // store per g.
+    // store per g.  (Staging the uint8 tile through LDS to store whole 64-byte row segments
+    // was measured 3.5 ms slower per launch at 16 x 16384^3, although the 4-byte stores make
+    // the L2 fetch the lines it merges them into.)
     // (the mulhi form: an FP64 floor/fma version of this reduction measured 1.1 ms slower
     // per launch at 16 x 16384^3)
     const int p = mods.p[s], pv = mods.pinv_prime[s];
