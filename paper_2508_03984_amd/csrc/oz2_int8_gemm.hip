@@ -230,6 +230,34 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
     // per launch at 16 x 16384^3)
     const int p = mods.p[s], pv = mods.pinv_prime[s];
     const int64_t c_off = ((int64_t)s * Mp + bm) * Np + bn;
+    if (OUT == kOutU8) {
+        // Four residues per register quad pack into one dword; the two half-wavefronts hold
+        // alternating dwords of a row (columns 8g + 4*(l/32) ...), so they swap two dwords
+        // each and every lane stores 16 contiguous bytes: a lane pair completes a 32-byte
+        // sector of the row, and the L2 no longer has to fetch lines to merge 4-byte stores.
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                uint32_t d[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    d[g] = 0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        d[g] |= (uint32_t)mod_small(acc[i][j][4 * g + c], p, pv) << (8 * c);
+                }
+                const uint32_t r0 = __shfl_xor(lhalf ? d[0] : d[2], 32, 64);
+                const uint32_t r1 = __shfl_xor(lhalf ? d[1] : d[3], 32, 64);
+                const v4i q = lhalf ? v4i{(int)r0, (int)d[2], (int)r1, (int)d[3]}
+                                    : v4i{(int)d[0], (int)r0, (int)d[1], (int)r1};
+                const int row = wm * 32 * TM + i * 32 + lrow;
+                const int col = wn * 32 * TN + j * 32 + 16 * lhalf;
+                *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * Np + col) = q;
+            }
+        return;
+    }
+
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
