@@ -27,7 +27,7 @@ def oz():
 
 
 def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, accurate=False,
-             int32_products=False):
+             int32_products=False, ldc=None, c_offset=0):
     """Run oz2_dgemm / oz2_sgemm and fetch every stage, trimmed to the logical shapes.  By
     default the GEMM emits U_s (uint8); with int32_products the diagnostic form C'_s."""
     import torch
@@ -38,20 +38,25 @@ def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, acc
     ldb = ldb or n
     dA = torch.zeros((m, lda), dtype=dt, device="cuda"); dA[:, :k] = torch.from_numpy(A).cuda()
     dB = torch.zeros((k, ldb), dtype=dt, device="cuda"); dB[:, :n] = torch.from_numpy(B).cuda()
-    dC = (torch.from_numpy(np.ascontiguousarray(Cin)).cuda() if Cin is not None
-          else torch.full((m, n), float("nan"), dtype=dt, device="cuda"))
+    ldc = ldc or n
+    store = torch.full((m * ldc + c_offset,), float("nan"), dtype=dt, device="cuda")
+    dC = store[c_offset:].view(m, ldc)[:, :n]               # row stride ldc, start offset c_offset
+    if Cin is not None:
+        dC.copy_(torch.from_numpy(np.ascontiguousarray(Cin)).cuda())
     if accurate:
         fn = oz.oz2_dgemm_accurate if dt == torch.float64 else oz.oz2_sgemm_accurate
     else:
         fn = oz.oz2_dgemm if dt == torch.float64 else oz.oz2_sgemm
     oz.oz2_set_int32_products(int32_products)
     try:
-        fn(m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+        fn(m, n, k, alpha, dA, lda, dB, ldb, beta, dC, ldc, N)
     finally:
         oz.oz2_set_int32_products(False)
     torch.cuda.synchronize()
     from paper_2508_03984_amd import binding as b
     out = dict(C=dC.cpu().numpy())
+    if ldc > n:                                              # the gap between rows is untouched
+        assert bool(torch.isnan(store[c_offset:].view(m, ldc)[:, n:]).all())
     out["tA"] = oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy()
     out["tB"] = oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy()
     ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A))
@@ -177,6 +182,34 @@ def test_alpha_beta_and_leading_dimensions(oz, oracle):
     ref = oracle.gemm(A32, B32, 8, 1.5, 0.25, C32, is_double=False)
     got = gpu_gemm(oz, A32, B32, 8, 1.5, 0.25, C32.copy(), lda=151, ldb=128)
     assert_parity(got, ref, False)
+
+
+def test_unaligned_operands_and_strided_c(oz, oracle):
+    """Pointers and leading dimensions that defeat the 16-byte fast paths of the kernels."""
+    import torch
+    A, B = S.gemm_inputs(37, 53, 100, 0.5, seed=12)
+    ref = oracle.gemm(A, B, 14)
+    assert_parity(gpu_gemm(oz, A, B, 14, lda=101, ldb=59, ldc=61, c_offset=1), ref, True)
+    assert_parity(gpu_gemm(oz, A, B, 14, ldc=64, c_offset=2), ref, True)
+    A32, B32 = A.astype(np.float32), B.astype(np.float32)
+    ref = oracle.gemm(A32, B32, 8, is_double=False)
+    assert_parity(gpu_gemm(oz, A32, B32, 8, lda=103, ldb=55, ldc=57, c_offset=3), ref, False)
+    # A and B that start at odd element offsets
+    dt = torch.float64
+    sa = torch.zeros(37 * 100 + 1, dtype=dt, device="cuda"); sb = torch.zeros(100 * 53 + 1, dtype=dt, device="cuda")
+    dA = sa[1:].view(37, 100); dB = sb[1:].view(100, 53)
+    dA.copy_(torch.from_numpy(A).cuda()); dB.copy_(torch.from_numpy(B).cuda())
+    C = oz.matmul(dA, dB, 14)
+    assert np.array_equal(C.cpu().numpy(), oracle.gemm(A, B, 14)["C"])
+
+
+def test_large_tile_kernel_without_the_xcd_swizzle(oz, oracle):
+    """6 x 5 tiles of 256: the 8-wavefront kernel with the plain tile map (the swizzled map
+    needs multiples of 16 tiles), ragged edges, both product forms."""
+    A, B = S.gemm_inputs(1300, 1100, 300, 1.0, seed=13)
+    ref = oracle.gemm(A, B, 20)
+    assert_parity(gpu_gemm(oz, A, B, 20), ref, True)
+    assert_parity(gpu_gemm(oz, A, B, 20, int32_products=True), ref, True)
 
 
 def test_beta_zero_does_not_read_c(oz, oracle):
