@@ -102,12 +102,13 @@ SWEEPS = {
 def sweep(oz, torch, name, args) -> int:
     """Times oz2_dgemm / oz2_sgemm over the moduli counts of a configuration and measures the
     error of each result (and of the native GEMM) against a double-double product on three
-    sampled rows.  One JSON line per (shape, phi, N) goes to gpurun_out/sweep_<name>.jsonl."""
+    sampled rows.  One JSON line per (shape, phi, N) goes to the file named by --out."""
     import numpy as np
     import synth_inputs as S
     from oracle import oz2_oracle as O              # reference leg only
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    path = os.path.join(ROOT, "gpurun_out", f"sweep_{name}.jsonl")
+    path = args.out or f"sweep_{name}.jsonl"
+    if os.path.dirname(path):
+        os.makedirs(os.path.dirname(path), exist_ok=True)
     with open(path, "w") as f:
         for (m, n, k, phi, is_double, moduli) in SWEEPS[name]:
             np_dt, t_dt = (np.float64, torch.float64) if is_double else (np.float32, torch.float32)
@@ -178,7 +179,8 @@ def main() -> int:
                          "counters); both print a reduced JSON line")
     ap.add_argument("--sweep", choices=sorted(SWEEPS), default=None,
                     help="time a whole configuration of the benchmark set over its moduli counts; "
-                         "lines go to gpurun_out/sweep_<name>.jsonl")
+                         "one JSON line per case goes to --out")
+    ap.add_argument("--out", default=None, help="file for --sweep (default: sweep_<name>.jsonl)")
     ap.add_argument("--cpu-block", type=int, default=1024,
                     help="the oracle is timed on C[0:b, 0:b] with the full k")
     args = ap.parse_args()
