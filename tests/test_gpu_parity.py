@@ -106,6 +106,7 @@ CASES = [
     (300, 200, 333, 5, 1.0, np.float32),
     (97, 515, 1030, 9, 0.5, np.float32),
     (64, 64, 512, 2, 0.5, np.float32),
+    (70, 66, 300, 20, 0.5, np.float32),        # more moduli than FP32 needs: still exact
 ]
 
 
@@ -230,6 +231,20 @@ def test_degenerate_inputs(oz, oracle):
     assert_parity(gpu_gemm(oz, A, B, 16), oracle.gemm(A, B, 16), True)
     Z = np.zeros((20, 30)); Zb = np.zeros((30, 10))
     assert_parity(gpu_gemm(oz, Z, Zb, 14), oracle.gemm(Z, Zb, 14), True)
+
+
+def test_nonfinite_inputs_stay_local_and_memory_safe(oz, oracle):
+    """Inf/NaN inputs are outside the method (the result in their row / column is unspecified)
+    but must not disturb anything else: shifts are per row of A and per column of B."""
+    A, B = S.gemm_inputs(48, 40, 70, 0.5, seed=14)
+    A_bad, B_bad = A.copy(), B.copy()
+    A_bad[5, 3] = np.nan; A_bad[9, 0] = np.inf; B_bad[7, 11] = -np.inf; B_bad[0, 2] = np.nan
+    for accurate in (False,):                    # accurate mode couples rows through Cbar's maxima
+        got = gpu_gemm(oz, A_bad, B_bad, 15, accurate=accurate)["C"]
+        ref = oracle.gemm(A, B, 15, accurate=accurate)["C"]
+        rows = np.setdiff1d(np.arange(48), [5, 9]); cols = np.setdiff1d(np.arange(40), [11, 2])
+        assert np.array_equal(got[np.ix_(rows, cols)], ref[np.ix_(rows, cols)])
+    gpu_gemm(oz, A_bad, B_bad, 15, accurate=True)    # must simply return
 
 
 def test_empty_and_k_zero(oz):
