@@ -8,8 +8,8 @@ Prints ONE JSON line on stdout: emulated FP64 TFLOP/s (2mnk / time) at
 m = n = k = 16384, the roofline of the dominant kernel (the batched INT8 MFMA
 GEMM, timed with HIP events on the call's stream inside the timed steps),
 native FP64 GEMM on the same buffers, the accuracy of both against a
-double-double product on sampled rows, and the CPU oracle timed on a sub-block
-of the same problem.  Everything else goes to stderr.
+double-double product on sampled rows, the matrix cores' own rate and the board
+power of both GEMMs, and the CPU oracle timed on a sub-block of the same problem.  Everything else goes to stderr.
 """
 from __future__ import annotations
 
@@ -34,6 +34,82 @@ MEASURED_GEMM_TRAFFIC_BYTES = {("f64", 16384, 16): 116.15e9 + 4.30e9}
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+class PowerSampler:
+    """Samples the board power (and shader clock) that the amdgpu driver publishes in sysfs.
+
+    A thread reads hwmon's power1_input (microwatts) and freq1_input (Hz) every few
+    milliseconds; nothing of it touches the GPU.  `None` figures when the files are absent."""
+
+    def __init__(self, torch, period_s: float = 0.005):
+        import glob
+        self.period = period_s
+        self.power_file = self.freq_file = None
+        cards = sorted(glob.glob("/sys/class/drm/card[0-9]*/device/hwmon/hwmon*/power1_input"))
+        want = None
+        try:
+            want = "%02x:00" % torch.cuda.get_device_properties(0).pci_bus_id
+        except Exception:
+            pass
+        for f in cards:
+            dev = os.path.realpath(os.path.join(os.path.dirname(f), "..", ".."))
+            if len(cards) == 1 or (want and want in os.path.basename(dev)):
+                self.power_file = f
+                fq = os.path.join(os.path.dirname(f), "freq1_input")
+                self.freq_file = fq if os.path.exists(fq) else None
+                break
+        self.samples = []
+
+    @staticmethod
+    def _read(path):
+        try:
+            with open(path) as fh:
+                return float(fh.read().strip())
+        except (OSError, ValueError):
+            return None
+
+    def cap_watts(self):
+        if not self.power_file:
+            return None
+        v = self._read(os.path.join(os.path.dirname(self.power_file), "power1_cap"))
+        return v / 1e6 if v else None
+
+    def run(self, torch, launch, seconds: float, settle_s: float):
+        """Calls launch() back to back for about `seconds`; returns (calls per second, mean W,
+        mean shader MHz) with the first `settle_s` of samples dropped."""
+        import threading
+        stop = threading.Event()
+        samples = []
+
+        def loop():
+            while not stop.is_set():
+                w = self._read(self.power_file) if self.power_file else None
+                f = self._read(self.freq_file) if self.freq_file else None
+                samples.append((time.perf_counter(), w, f))
+                time.sleep(self.period)
+
+        launch()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        launch()
+        torch.cuda.synchronize()
+        one = max(time.perf_counter() - t1, 1e-4)
+        calls = max(3, int(seconds / one))
+        th = threading.Thread(target=loop, daemon=True)
+        th.start()
+        t0 = time.perf_counter()
+        for _ in range(calls):
+            launch()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        stop.set()
+        th.join()
+        ws = [w for t, w, f in samples if w is not None and t - t0 >= settle_s]
+        fs = [f for t, w, f in samples if f is not None and t - t0 >= settle_s]
+        watts = sum(ws) / len(ws) / 1e6 if ws else None
+        mhz = sum(fs) / len(fs) / 1e6 if fs else None
+        return calls / elapsed, watts, mhz
 
 
 def gemm_only(oz, torch, size, N, args) -> int:
@@ -173,6 +249,8 @@ def main() -> int:
     ap.add_argument("--int32-products", action="store_true",
                     help="diagnostic pipeline: the GEMM stores int32 sums, the epilogue reduces them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the MFMA-only probe, the library INT8 GEMM and the power legs")
     ap.add_argument("--stage", choices=["all", "int8_gemm", "copy"], default="all",
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
                          "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
@@ -271,6 +349,44 @@ def main() -> int:
     native_tflops = 2.0 * m * n * k / ((time.perf_counter() - t1) / reps) / 1e12
     log(f"native {'SGEMM' if args.sgemm else 'DGEMM'}: {native_tflops:.1f} TFLOP/s")
 
+    # the matrix cores alone, the library's INT8 GEMM, and board power (Section 5.3 of the paper
+    # reports power efficiency; here: sysfs board power while each GEMM runs back to back)
+    device = power = None
+    if not args.no_extras:
+        const_tops, cus, mhz = oz.oz2_mfma_probe(False, 0.25)
+        rand_tops, _, _ = oz.oz2_mfma_probe(True, 0.25)
+        device = {"name": torch.cuda.get_device_name(0), "compute_units": cus, "nominal_clock_mhz": mhz,
+                  "mfma_only_TOPs": {"constant_operands": const_tops, "random_operands": rand_tops},
+                  "int8_gemm_frac_of_mfma_only_random": gemm_tops / rand_tops}
+        try:
+            g = torch.Generator(device="cuda").manual_seed(0)
+            ia = torch.randint(-128, 128, (Mp, Kp), dtype=torch.int8, device="cuda", generator=g)
+            ib = torch.randint(-128, 128, (Np, Kp), dtype=torch.int8, device="cuda", generator=g).t()
+            torch._int_mm(ia, ib)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(N):                                # as many slices as one launch of ours
+                torch._int_mm(ia, ib)
+            e1.record()
+            torch.cuda.synchronize()
+            device["library_int8_gemm_TOPs"] = gemm_ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            del ia, ib
+        except Exception as ex:                               # not every build of torch has it
+            device["library_int8_gemm_TOPs"] = None
+            log(f"torch._int_mm not usable: {ex!r}"[:200])
+        log(f"device {device}")
+        ps = PowerSampler(torch)
+        if ps.power_file:
+            cps_e, w_e, f_e = ps.run(torch, step, 2.5, 1.0)
+            cps_n, w_n, f_n = ps.run(torch, lambda: torch.mm(dA, dB, out=dC), 2.5, 1.0)
+            gf = 2.0 * m * n * k / 1e9
+            power = {"source": "amdgpu hwmon power1_input / freq1_input, mean over 1.5 s of back-to-back calls",
+                     "cap_W": ps.cap_watts(),
+                     "emulated": {"W": w_e, "shader_MHz": f_e, "GFLOPS_per_W": gf * cps_e / w_e if w_e else None},
+                     "native": {"W": w_n, "shader_MHz": f_n, "GFLOPS_per_W": gf * cps_n / w_n if w_n else None}}
+            log(f"power {power}")
+
     # accuracy of both on a few sampled rows against a double-double product (CPU)
     from oracle import oz2_oracle as O              # allowed here: baseline / reference leg only
     rows = np.array([0, m // 3, m - 1])
@@ -332,6 +448,8 @@ def main() -> int:
         "native_gemm_tflops": native_tflops,
         "speedup_vs_native": tflops / native_tflops,
         "accuracy": accuracy,
+        "device": device,
+        "power": power,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

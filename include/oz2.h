@@ -176,6 +176,20 @@ oz2_status oz2_int8_gemm(const int8_t *dev_A, const int8_t *dev_B, int32_t *dev_
                          int batch, int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream);
 
 /*
+ * Diagnostics: the rate of the INT8 matrix cores on their own (the instruction of the
+ * GEMM of Algorithm 1 line 6, v_mfma_i32_32x32x32_i8, issued back to back from registers by
+ * two wavefronts per SIMD, no memory traffic), sustained over about `seconds` (0 < seconds
+ * <= 5) on the current device's default stream; blocks until done.
+ * random_operands = 0: constant operands; 1: pseudo-random bytes, which is what residues
+ * look like -- the sustained clock depends on it.
+ * Outputs (HOST pointers): *tops in 1e12 INT8 operations per second (a multiply-add
+ * counts as two), and, if not NULL, the device's compute-unit count and its nominal
+ * maximum clock in MHz.  Allocates and frees a small device buffer of its own.
+ */
+oz2_status oz2_mfma_probe(int random_operands, double seconds, double *tops, int *compute_units,
+                          int *clock_mhz);
+
+/*
  * Per-stage timing.  With profiling on, each call records HIP events around its
  * stages on the call's stream; oz2_last_stage_times_ms waits for the last call
  * and writes { scale+exponent, residues, INT8 GEMM, epilogue } in milliseconds

@@ -7,7 +7,7 @@ only marshal arguments; torch supplies device memory and streams.
 """
 from .binding import (  # noqa: F401
     OZ2Error, lib_path, load, oz2_constants, oz2_dgemm, oz2_dgemm_accurate, oz2_int8_gemm,
-    oz2_sgemm_accurate, oz2_shift_table_accurate,
+    oz2_sgemm_accurate, oz2_shift_table_accurate, oz2_mfma_probe,
     oz2_last_stage_times_ms, oz2_release, oz2_set_int32_products, oz2_set_profiling, oz2_set_workspace,
     oz2_sgemm, oz2_shift_table, oz2_stage_ptr, oz2_status_string, oz2_workspace_bytes,
     stage_tensor, matmul, block_slices, unblock_slices,

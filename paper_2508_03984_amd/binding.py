@@ -19,7 +19,7 @@ EXPORTS = [
     "oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate", "oz2_shift_table_accurate",
     "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
     "oz2_constants", "oz2_shift_table", "oz2_stage_ptr", "oz2_int8_gemm", "oz2_set_profiling",
-    "oz2_last_stage_times_ms", "oz2_status_string", "oz2_set_int32_products",
+    "oz2_last_stage_times_ms", "oz2_status_string", "oz2_set_int32_products", "oz2_mfma_probe",
 ]
 
 
@@ -64,6 +64,7 @@ def load():
     lib.oz2_shift_table.argtypes = [ci, vp, vp, vp]
     lib.oz2_stage_ptr.argtypes = [ci, C.POINTER(vp), C.POINTER(i64)]
     lib.oz2_int8_gemm.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp]
+    lib.oz2_mfma_probe.argtypes = [ci, C.c_double, C.POINTER(C.c_double), C.POINTER(ci), C.POINTER(ci)]
     lib.oz2_set_profiling.argtypes = [ci]
     lib.oz2_set_profiling.restype = None
     lib.oz2_set_int32_products.argtypes = [ci]
@@ -73,7 +74,7 @@ def load():
     lib.oz2_status_string.restype = C.c_char_p
     for name in ("oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate",
                  "oz2_shift_table_accurate", "oz2_set_workspace", "oz2_constants", "oz2_shift_table",
-                 "oz2_stage_ptr", "oz2_int8_gemm", "oz2_last_stage_times_ms"):
+                 "oz2_stage_ptr", "oz2_int8_gemm", "oz2_last_stage_times_ms", "oz2_mfma_probe"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -195,6 +196,14 @@ def oz2_int8_gemm(A, B, C_, batch, Mp, Np, Kp, stream=None) -> None:
     import torch
     _check(load().oz2_int8_gemm(_dev(A, torch.int8), _dev(B, torch.int8), _dev(C_, torch.int32),
                                 int(batch), Mp, Np, Kp, _stream(stream)), "oz2_int8_gemm")
+
+
+def oz2_mfma_probe(random_operands: bool, seconds: float = 0.25):
+    """(1e12 INT8 op/s of the matrix cores alone, compute units, nominal clock in MHz)."""
+    tops, cus, mhz = C.c_double(), C.c_int(), C.c_int()
+    _check(load().oz2_mfma_probe(int(bool(random_operands)), float(seconds), C.byref(tops), C.byref(cus),
+                                 C.byref(mhz)), "oz2_mfma_probe")
+    return float(tops.value), int(cus.value), int(mhz.value)
 
 
 def oz2_set_int32_products(on: bool) -> None:

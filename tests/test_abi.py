@@ -122,4 +122,8 @@ def test_argument_checks_need_no_gpu(oz):
     lib.oz2_set_int32_products(0)
     assert lib.oz2_int8_gemm(one, one, one, 1, 256, 256, 2 ** 17 + 128, null) == 2
     assert lib.oz2_int8_gemm(one, one, one, 1, 100, 256, 128, null) == 1
+    t = C.c_double()
+    assert lib.oz2_mfma_probe(1, 0.0, C.byref(t), None, None) == 1    # no duration
+    assert lib.oz2_mfma_probe(1, 60.0, C.byref(t), None, None) == 1   # longer than the limit
+    assert lib.oz2_mfma_probe(1, 0.1, None, None, None) == 1
     assert "moduli" in oz.oz2_status_string(2)

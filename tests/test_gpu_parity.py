@@ -263,6 +263,16 @@ def test_empty_and_k_zero(oz):
     assert bool((C == 0.0).all())
 
 
+def test_mfma_probe_reports_a_plausible_rate(oz):
+    # the matrix cores alone: below the published dense INT8 peak (5.0e15 op/s, with a margin
+    # for a boost above the nominal clock) and far above anything the vector ALUs could do
+    import torch
+    for random_operands in (False, True):
+        tops, cus, mhz = oz.oz2_mfma_probe(random_operands, 0.05)
+        assert cus == torch.cuda.get_device_properties(0).multi_processor_count
+        assert 500.0 < tops < 5600.0 and mhz > 0
+
+
 def test_int8_gemm_random_and_extreme(oz, oracle):
     import torch
     rng = np.random.default_rng(0)
