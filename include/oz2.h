@@ -7,8 +7,10 @@
  * INT8 Matrix Engines", Uchino, Ozaki, Imamura, SC'25).
  *
  * C ABI.  Conventions shared by every entry point:
- *   - matrices are ROW-MAJOR and not transposed; a column-major caller obtains
- *     C = A*B by passing (B, A) and (n, m), since C^T = B^T A^T;
+ *   - matrices are ROW-MAJOR; oz2_dgemm / oz2_sgemm take them as they are, the
+ *     oz2_*gemm_op entry points take an optional transposition of each.  A
+ *     column-major caller obtains C = A*B by passing (B, A) and (n, m), since
+ *     C^T = B^T A^T;
  *   - pointers named A, B, C, dev_* are DEVICE pointers owned by the caller;
  *     A and B are only read; host pointers are marked "host";
  *   - calls are asynchronous on `stream`; the returned status reports argument
@@ -95,6 +97,58 @@ oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha,
                               hipStream_t stream);
 
 /*
+ * General form: C <- alpha * op(A) * op(B) + beta * C with op(X) = X (OZ2_OP_N) or X^T
+ * (OZ2_OP_T), in fast (accurate = 0) or accurate (accurate != 0) mode of Section 4.2.
+ * op(A) is m x k and op(B) is k x n; the stored A is m x k (lda >= k) or, transposed,
+ * k x m (lda >= m); the stored B is k x n (ldb >= n) or n x k (ldb >= k).  Nothing is
+ * transposed in memory: the scale vectors and residues of Algorithm 1 lines 1-5 are taken
+ * along rows or along columns of the stored matrix as needed.  Everything else is as for
+ * oz2_dgemm / oz2_sgemm, which are the (OZ2_OP_N, OZ2_OP_N, accurate = 0) case.
+ */
+typedef enum { OZ2_OP_N = 0, OZ2_OP_T = 1 } oz2_op;
+
+oz2_status oz2_dgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                        double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
+                        double beta, double *C, int64_t ldc, int num_moduli, hipStream_t stream);
+
+oz2_status oz2_sgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                        float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                        float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream);
+
+/*
+ * Prepared operands: Algorithm 1 lines 1-5 (fast mode) for ONE matrix, kept for reuse.
+ * In fast mode the scale vector and the residues of A do not depend on B and vice versa,
+ * so a matrix that enters many products (the panel of a blocked factorisation, a fixed
+ * weight matrix) needs them only once.  oz2_prepare_* computes, on `stream`, the shifts
+ * and the num_moduli INT8 residue slices of
+ *     side = 0: the LEFT factor  op(X), rows x k   (its rows are scaled);
+ *     side = 1: the RIGHT factor op(X), k x rows   (its columns are scaled; "rows" is then n);
+ * X is stored as for oz2_dgemm_op.  The handle owns its device memory (allocated with
+ * hipMalloc in the call: about num_moduli * rows * k bytes, rounded up to whole tiles);
+ * oz2_operand_free releases it (the caller makes sure no product that uses it is still
+ * running).  *out is written only on success.  X may be changed or freed once the work
+ * queued on `stream` by the call has run.
+ * oz2_*gemm_prepared: C <- alpha * L * R + beta * C for a left and a right operand prepared
+ * with the same k, num_moduli and element type (OZ2_INVALID_ARG otherwise); C is
+ * L.rows x R.rows with ldc >= R.rows.  The result is bit-identical to the oz2_*gemm_op call
+ * on the original matrices in fast mode.  The stream of the product must be ordered after
+ * the streams of the two preparations by the caller.
+ */
+typedef struct oz2_operand oz2_operand;
+
+oz2_status oz2_prepare_d(int side, oz2_op op, int64_t rows, int64_t k, const double *X, int64_t ld,
+                         int num_moduli, hipStream_t stream, oz2_operand **out);
+oz2_status oz2_prepare_s(int side, oz2_op op, int64_t rows, int64_t k, const float *X, int64_t ld,
+                         int num_moduli, hipStream_t stream, oz2_operand **out);
+void oz2_operand_free(oz2_operand *operand);
+size_t oz2_operand_bytes(const oz2_operand *operand);      /* device bytes it holds; 0 for NULL */
+
+oz2_status oz2_dgemm_prepared(const oz2_operand *left, const oz2_operand *right, double alpha,
+                              double beta, double *C, int64_t ldc, hipStream_t stream);
+oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right, float alpha,
+                              float beta, float *C, int64_t ldc, hipStream_t stream);
+
+/*
  * Workspace.  A call needs device scratch for the shift vectors (and the
  * per-column partial results behind them), the INT8 residue slices of A and B (Algorithm 1 lines 4-5)
  * and the reduced products U_s (line 7; or the INT32 products of line 6 after
@@ -103,11 +157,30 @@ oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha,
  * library a caller-owned device buffer (kept, not freed, must stay valid until
  * replaced; 256-byte aligned); with (NULL, 0) the library goes back to
  * allocating its own buffer with hipMalloc, growing it on demand and keeping
- * it until oz2_release.  A call whose need exceeds a caller-owned buffer
- * returns OZ2_WORKSPACE.
+ * it until oz2_release.
+ *
+ * Bounded workspace ("block matrix multiplication" over the rows and columns of C): the
+ * products U_s are the largest part (num_moduli * m * n bytes).  When the workspace may
+ * not hold them all -- a caller-owned buffer smaller than oz2_workspace_bytes, or a limit
+ * set with oz2_set_workspace_limit for the library's own buffer (0 = no limit) -- the call
+ * computes C panel by panel: the shifts and residues of the whole of A and B once, then
+ * for each (row panel, column panel) the INT8 GEMMs and the accumulation of that panel
+ * only.  The result is bit-identical.  oz2_workspace_min_bytes is the smallest workspace
+ * such a call can run in (one 256 x 256 panel); below it the call returns OZ2_WORKSPACE.
+ * Accurate mode computes its Cbar panel by panel in the same place (only the row and column
+ * maxima are kept).  oz2_plan_panels says, without touching the GPU, how a product of this
+ * shape is cut in a workspace of `workspace_bytes` (host pointers, may be NULL: rows and
+ * columns of a panel, multiples of 256, the last panels of a row or column may be smaller;
+ * and the number of panels); oz2_last_panels reports the same for the most recent product
+ * (OZ2_INVALID_ARG if there was none).
  */
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double);
+size_t oz2_workspace_min_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double);
 oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes);
+void oz2_set_workspace_limit(size_t bytes);
+oz2_status oz2_plan_panels(int64_t m, int64_t n, int64_t k, int num_moduli, size_t workspace_bytes,
+                           int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
+oz2_status oz2_last_panels(int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
 void oz2_release(void);
 
 /*
@@ -157,7 +230,9 @@ oz2_status oz2_shift_table_accurate(int num_moduli, float *Paccu, int32_t *f_max
  * OZ2_INVALID_ARG.
  * The residue slices are K-blocked: residue (row r, k-index h) of slice s is at
  * ((s * Kp/64 + h/64) * rows + r) * 64 + h%64, so that a (rows x 64) tile is contiguous.
- * Valid until the next call or workspace change; the caller synchronises.
+ * Valid until the next call or workspace change; the caller synchronises.  After a call
+ * that was cut into panels the product planes hold the last panel only and the two product
+ * stages return OZ2_INVALID_ARG; after a product of prepared operands no stage is available.
  */
 enum { OZ2_STAGE_SHIFT_A = 0, OZ2_STAGE_SHIFT_B = 1, OZ2_STAGE_RES_A = 2,
        OZ2_STAGE_RES_B = 3, OZ2_STAGE_PROD = 4, OZ2_STAGE_U = 5 };

@@ -11,4 +11,7 @@ from .binding import (  # noqa: F401
     oz2_last_stage_times_ms, oz2_release, oz2_set_int32_products, oz2_set_profiling, oz2_set_workspace,
     oz2_sgemm, oz2_shift_table, oz2_stage_ptr, oz2_status_string, oz2_workspace_bytes,
     stage_tensor, matmul, block_slices, unblock_slices,
+    OZ2_OP_N, OZ2_OP_T, Operand, oz2_dgemm_op, oz2_sgemm_op, oz2_prepare_d, oz2_prepare_s, oz2_operand_free,
+    oz2_operand_bytes, oz2_dgemm_prepared, oz2_sgemm_prepared, oz2_workspace_min_bytes,
+    oz2_set_workspace_limit, oz2_last_panels, oz2_plan_panels,
 )

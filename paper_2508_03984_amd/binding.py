@@ -20,7 +20,12 @@ EXPORTS = [
     "oz2_workspace_bytes", "oz2_set_workspace", "oz2_release",
     "oz2_constants", "oz2_shift_table", "oz2_stage_ptr", "oz2_int8_gemm", "oz2_set_profiling",
     "oz2_last_stage_times_ms", "oz2_status_string", "oz2_set_int32_products", "oz2_mfma_probe",
+    "oz2_dgemm_op", "oz2_sgemm_op", "oz2_prepare_d", "oz2_prepare_s", "oz2_operand_free",
+    "oz2_operand_bytes", "oz2_dgemm_prepared", "oz2_sgemm_prepared", "oz2_workspace_min_bytes",
+    "oz2_set_workspace_limit", "oz2_last_panels", "oz2_plan_panels",
 ]
+
+OZ2_OP_N, OZ2_OP_T = 0, 1
 
 
 class OZ2Error(RuntimeError):
@@ -55,8 +60,24 @@ def load():
     lib.oz2_dgemm_accurate.argtypes = lib.oz2_dgemm.argtypes
     lib.oz2_sgemm_accurate.argtypes = lib.oz2_sgemm.argtypes
     lib.oz2_shift_table_accurate.argtypes = [ci, vp, vp, vp, vp]
+    lib.oz2_dgemm_op.argtypes = [ci, ci, ci] + lib.oz2_dgemm.argtypes
+    lib.oz2_sgemm_op.argtypes = [ci, ci, ci] + lib.oz2_sgemm.argtypes
+    lib.oz2_prepare_d.argtypes = [ci, ci, i64, i64, vp, i64, ci, vp, C.POINTER(vp)]
+    lib.oz2_prepare_s.argtypes = lib.oz2_prepare_d.argtypes
+    lib.oz2_operand_free.argtypes = [vp]
+    lib.oz2_operand_free.restype = None
+    lib.oz2_operand_bytes.argtypes = [vp]
+    lib.oz2_operand_bytes.restype = C.c_size_t
+    lib.oz2_dgemm_prepared.argtypes = [vp, vp, dbl, dbl, vp, i64, vp]
+    lib.oz2_sgemm_prepared.argtypes = [vp, vp, flt, flt, vp, i64, vp]
     lib.oz2_workspace_bytes.argtypes = [i64, i64, i64, ci, ci]
     lib.oz2_workspace_bytes.restype = C.c_size_t
+    lib.oz2_workspace_min_bytes.argtypes = [i64, i64, i64, ci, ci]
+    lib.oz2_workspace_min_bytes.restype = C.c_size_t
+    lib.oz2_set_workspace_limit.argtypes = [C.c_size_t]
+    lib.oz2_set_workspace_limit.restype = None
+    lib.oz2_last_panels.argtypes = [C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.oz2_plan_panels.argtypes = [i64, i64, i64, ci, C.c_size_t] + lib.oz2_last_panels.argtypes
     lib.oz2_set_workspace.argtypes = [vp, C.c_size_t]
     lib.oz2_release.argtypes = []
     lib.oz2_release.restype = None
@@ -74,7 +95,9 @@ def load():
     lib.oz2_status_string.restype = C.c_char_p
     for name in ("oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate",
                  "oz2_shift_table_accurate", "oz2_set_workspace", "oz2_constants", "oz2_shift_table",
-                 "oz2_stage_ptr", "oz2_int8_gemm", "oz2_last_stage_times_ms", "oz2_mfma_probe"):
+                 "oz2_stage_ptr", "oz2_int8_gemm", "oz2_last_stage_times_ms", "oz2_mfma_probe",
+                 "oz2_dgemm_op", "oz2_sgemm_op", "oz2_prepare_d", "oz2_prepare_s", "oz2_dgemm_prepared",
+                 "oz2_sgemm_prepared", "oz2_last_panels", "oz2_plan_panels"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -136,6 +159,106 @@ def oz2_sgemm_accurate(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli
                                      _dev(B, torch.float32), ldb, float(beta),
                                      _dev(C_, torch.float32), ldc, int(num_moduli), _stream(stream)),
            "oz2_sgemm_accurate")
+
+
+def oz2_dgemm_op(opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli,
+                 stream=None) -> None:
+    import torch
+    _check(load().oz2_dgemm_op(int(opA), int(opB), int(bool(accurate)), m, n, k, float(alpha),
+                               _dev(A, torch.float64), lda, _dev(B, torch.float64), ldb, float(beta),
+                               _dev(C_, torch.float64), ldc, int(num_moduli), _stream(stream)),
+           "oz2_dgemm_op")
+
+
+def oz2_sgemm_op(opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli,
+                 stream=None) -> None:
+    import torch
+    _check(load().oz2_sgemm_op(int(opA), int(opB), int(bool(accurate)), m, n, k, float(alpha),
+                               _dev(A, torch.float32), lda, _dev(B, torch.float32), ldb, float(beta),
+                               _dev(C_, torch.float32), ldc, int(num_moduli), _stream(stream)),
+           "oz2_sgemm_op")
+
+
+class Operand:
+    """Owner of an oz2_operand handle (oz2_prepare_d / oz2_prepare_s); freed with the object."""
+
+    def __init__(self, handle: int, side: int, rows: int, k: int, is_double: bool):
+        self.handle, self.side, self.rows, self.k, self.is_double = handle, side, rows, k, is_double
+
+    @property
+    def nbytes(self) -> int:
+        return int(load().oz2_operand_bytes(C.c_void_p(self.handle)))
+
+    def free(self) -> None:
+        if self.handle:
+            load().oz2_operand_free(C.c_void_p(self.handle))
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _prepare(fn_name, dtype, side, op, rows, k, X, ld, num_moduli, stream) -> Operand:
+    out = C.c_void_p(0)
+    _check(getattr(load(), fn_name)(int(side), int(op), rows, k, _dev(X, dtype), ld, int(num_moduli),
+                                    _stream(stream), C.byref(out)), fn_name)
+    return Operand(int(out.value), int(side), rows, k, fn_name.endswith("_d"))
+
+
+def oz2_prepare_d(side, op, rows, k, X, ld, num_moduli, stream=None) -> Operand:
+    import torch
+    return _prepare("oz2_prepare_d", torch.float64, side, op, rows, k, X, ld, num_moduli, stream)
+
+
+def oz2_prepare_s(side, op, rows, k, X, ld, num_moduli, stream=None) -> Operand:
+    import torch
+    return _prepare("oz2_prepare_s", torch.float32, side, op, rows, k, X, ld, num_moduli, stream)
+
+
+def oz2_operand_free(operand: Operand) -> None:
+    operand.free()
+
+
+def oz2_operand_bytes(operand: Operand) -> int:
+    return operand.nbytes
+
+
+def oz2_dgemm_prepared(left: Operand, right: Operand, alpha, beta, C_, ldc, stream=None) -> None:
+    import torch
+    _check(load().oz2_dgemm_prepared(C.c_void_p(left.handle), C.c_void_p(right.handle), float(alpha),
+                                     float(beta), _dev(C_, torch.float64), ldc, _stream(stream)),
+           "oz2_dgemm_prepared")
+
+
+def oz2_sgemm_prepared(left: Operand, right: Operand, alpha, beta, C_, ldc, stream=None) -> None:
+    import torch
+    _check(load().oz2_sgemm_prepared(C.c_void_p(left.handle), C.c_void_p(right.handle), float(alpha),
+                                     float(beta), _dev(C_, torch.float32), ldc, _stream(stream)),
+           "oz2_sgemm_prepared")
+
+
+def oz2_workspace_min_bytes(m, n, k, num_moduli, is_double=True) -> int:
+    return int(load().oz2_workspace_min_bytes(m, n, k, int(num_moduli), int(bool(is_double))))
+
+
+def oz2_set_workspace_limit(nbytes: int) -> None:
+    load().oz2_set_workspace_limit(int(nbytes))
+
+
+def oz2_last_panels() -> Tuple[int, int, int]:
+    pr, pc, cnt = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(load().oz2_last_panels(C.byref(pr), C.byref(pc), C.byref(cnt)), "oz2_last_panels")
+    return int(pr.value), int(pc.value), int(cnt.value)
+
+
+def oz2_plan_panels(m, n, k, num_moduli, workspace_bytes) -> Tuple[int, int, int]:
+    pr, pc, cnt = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(load().oz2_plan_panels(m, n, k, int(num_moduli), int(workspace_bytes), C.byref(pr), C.byref(pc),
+                                  C.byref(cnt)), "oz2_plan_panels")
+    return int(pr.value), int(pc.value), int(cnt.value)
 
 
 def oz2_shift_table_accurate(num_moduli: int) -> dict:
@@ -260,27 +383,36 @@ def block_slices(t):
     return t.reshape(n, r, k // 64, 64).permute(0, 2, 1, 3).contiguous()
 
 
+def _ld(t):
+    """(is a transposed view?, leading dimension of the stored matrix) of a 2-D tensor that is
+    row-major or the transposed view of a row-major one."""
+    r, c = t.shape
+    if c == 1 or t.stride(1) == 1:
+        return False, (t.stride(0) if r > 1 else max(c, 1))
+    if r == 1 or t.stride(0) == 1:
+        return True, (t.stride(1) if c > 1 else max(r, 1))
+    raise ValueError("row-major operands, or transposed views of them, expected")
+
+
 def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=None, stream=None,
            accurate: bool = False):
-    """C = alpha * A @ B + beta * out for row-major device tensors, via oz2_dgemm / oz2_sgemm
-    (or their _accurate forms)."""
+    """C = alpha * A @ B + beta * out for device tensors that are row-major or transposed views
+    (`X.t()`) of row-major ones, via oz2_dgemm_op / oz2_sgemm_op."""
     import torch
     if A.dim() != 2 or B.dim() != 2 or A.shape[1] != B.shape[0] or A.dtype != B.dtype:
         raise ValueError("A (m x k) and B (k x n) of one dtype expected")
-    if A.stride(1) != 1 and A.shape[1] > 1 or B.stride(1) != 1 and B.shape[1] > 1:
-        raise ValueError("row-major operands expected")
     m, k = A.shape
     n = B.shape[1]
+    ta, lda = _ld(A)
+    tb, ldb = _ld(B)
     if out is None:
         if beta != 0.0:
             raise ValueError("beta != 0 needs `out`")
         out = torch.empty((m, n), dtype=A.dtype, device=A.device)
-    lda = A.stride(0) if m > 1 else max(k, 1)
-    ldb = B.stride(0) if k > 1 else max(n, 1)
+    if out.stride(1) != 1 and n > 1:
+        raise ValueError("row-major `out` expected")
     ldc = out.stride(0) if m > 1 else max(n, 1)
-    if accurate:
-        fn = oz2_dgemm_accurate if A.dtype == torch.float64 else oz2_sgemm_accurate
-    else:
-        fn = oz2_dgemm if A.dtype == torch.float64 else oz2_sgemm
-    fn(m, n, k, alpha, A, lda, B, ldb, beta, out, ldc, num_moduli, stream)
+    fn = oz2_dgemm_op if A.dtype == torch.float64 else oz2_sgemm_op
+    fn(OZ2_OP_T if ta else OZ2_OP_N, OZ2_OP_T if tb else OZ2_OP_N, accurate, m, n, k, alpha, A, lda, B, ldb,
+       beta, out, ldc, num_moduli, stream)
     return out

@@ -52,9 +52,11 @@ __global__ __launch_bounds__(256) void k_fill_i32(int32_t *p, int64_t count, int
     if (i < count) p[i] = v;
 }
 
-// rmax[i] = max_j Cbar[i][j] over j < n: one workgroup per row.  Entries are >= 0.
+// rmax[i] = max(rmax[i], max_j Cbar[i][j] over j < n): one workgroup per row.  Entries are
+// >= 0 and rmax starts at 0, so the integer atomic maximum over several column panels is
+// the maximum over the whole row whatever the order.
 __global__ __launch_bounds__(256) void k_row_max_i32(const int32_t *__restrict__ Cbar, int64_t ld,
-                                                     int64_t n, int32_t *__restrict__ rmax) {
+                                                     int64_t n, int *rmax) {
     __shared__ int part[4];
     const int32_t *x = Cbar + (int64_t)blockIdx.x * ld;
     int mx = 0;
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(256) void k_row_max_i32(const int32_t *__restrict__
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int w = 1; w < 4; ++w) mx = part[w] > mx ? part[w] : mx;
-        rmax[blockIdx.x] = mx;
+        if (mx) atomicMax(&rmax[blockIdx.x], mx);
     }
 }
 
@@ -125,37 +127,59 @@ inline unsigned blocks_for(int64_t threads) { return (unsigned)((threads + 255) 
 size_t accurate_scratch_bytes(int64_t m, int64_t n) { return (size_t)(m + n) * 16; }
 
 template <typename T>
-hipError_t launch_accurate_prescale(const T *A, int64_t lda, const T *B, int64_t ldb, int64_t m,
-                                    int64_t n, int64_t k, void *scratch, int8_t *Abar,
-                                    int8_t *Bbar, int64_t Mp, int64_t Np, int64_t Kp,
-                                    hipStream_t stream) {
+hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous, const T *B,
+                                    int64_t ldb, bool b_k_contiguous, int64_t m, int64_t n,
+                                    int64_t k, void *scratch, int8_t *Abar, int8_t *Bbar,
+                                    int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream) {
     const Scratch s = carve(scratch, m, n);
-    hipLaunchKernelGGL((k_row_maxbits<T>), dim3((unsigned)m), dim3(256), 0, stream, A, lda, k, s.amax);
-    if (hipError_t e = launch_col_maxbits<T>(B, ldb, k, n, s.bmax, stream)) return e;
+    // A vector of the product (a row of op(A), a column of op(B)) is either contiguous in
+    // memory (one workgroup per vector) or strided by the leading dimension (column kernels).
+    if (a_k_contiguous)
+        hipLaunchKernelGGL((k_row_maxbits<T>), dim3((unsigned)m), dim3(256), 0, stream, A, lda, k, s.amax);
+    else if (hipError_t e = launch_col_maxbits<T>(A, lda, k, m, s.amax, stream)) return e;
+    if (b_k_contiguous)
+        hipLaunchKernelGGL((k_row_maxbits<T>), dim3((unsigned)n), dim3(256), 0, stream, B, ldb, k, s.bmax);
+    else if (hipError_t e = launch_col_maxbits<T>(B, ldb, k, n, s.bmax, stream)) return e;
     hipLaunchKernelGGL(k_preshift, dim3(blocks_for(m)), dim3(256), 0, stream, s.amax, m, s.preA);
     hipLaunchKernelGGL(k_preshift, dim3(blocks_for(n)), dim3(256), 0, stream, s.bmax, n, s.preB);
-    if (hipError_t e = launch_magnitudes<T>(A, lda, m, k, s.preA, Abar, Mp, Kp, stream)) return e;
-    return launch_magnitudes_cols<T>(B, ldb, k, n, s.preB, Bbar, Np, Kp, stream);
+    if (hipError_t e = a_k_contiguous ? launch_magnitudes<T>(A, lda, m, k, s.preA, Abar, Mp, Kp, stream)
+                                      : launch_magnitudes_cols<T>(A, lda, k, m, s.preA, Abar, Mp, Kp, stream))
+        return e;
+    return b_k_contiguous ? launch_magnitudes<T>(B, ldb, n, k, s.preB, Bbar, Np, Kp, stream)
+                          : launch_magnitudes_cols<T>(B, ldb, k, n, s.preB, Bbar, Np, Kp, stream);
 }
 
-hipError_t launch_accurate_shifts(const int32_t *Cbar, int64_t Np, int64_t m, int64_t n,
-                                  const ShiftArgs &sa, void *scratch, int32_t *tA, int32_t *tB,
+hipError_t launch_accurate_maxima_clear(int64_t m, int64_t n, void *scratch, hipStream_t stream) {
+    const Scratch s = carve(scratch, m, n);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(m + n)), dim3(256), 0, stream, s.crow, m + n, 0);   // crow, ccol adjoin
+    return hipGetLastError();
+}
+
+hipError_t launch_accurate_maxima(const int32_t *Cbar, int64_t ld, int64_t row0, int64_t rows,
+                                  int64_t col0, int64_t cols, int64_t m, int64_t n, void *scratch,
                                   hipStream_t stream) {
     const Scratch s = carve(scratch, m, n);
-    hipLaunchKernelGGL(k_row_max_i32, dim3((unsigned)m), dim3(256), 0, stream, Cbar, Np, n, s.crow);
-    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(n)), dim3(256), 0, stream, s.ccol, n, 0);
-    hipLaunchKernelGGL(k_col_max_i32, dim3(blocks_for(n), (unsigned)((m + 255) / 256)), dim3(256), 0,
-                       stream, Cbar, Np, m, n, s.ccol);
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_row_max_i32, dim3((unsigned)rows), dim3(256), 0, stream, Cbar, ld, cols,
+                       s.crow + row0);
+    hipLaunchKernelGGL(k_col_max_i32, dim3(blocks_for(cols), (unsigned)((rows + 255) / 256)), dim3(256), 0,
+                       stream, Cbar, ld, rows, cols, s.ccol + col0);
+    return hipGetLastError();
+}
+
+hipError_t launch_accurate_finish(int64_t m, int64_t n, const ShiftArgs &sa, void *scratch,
+                                  int32_t *tA, int32_t *tB, hipStream_t stream) {
+    const Scratch s = carve(scratch, m, n);
     hipLaunchKernelGGL(k_accu_finish, dim3(blocks_for(m)), dim3(256), 0, stream, s.amax, s.crow, m, sa, tA);
     hipLaunchKernelGGL(k_accu_finish, dim3(blocks_for(n)), dim3(256), 0, stream, s.bmax, s.ccol, n, sa, tB);
     return hipGetLastError();
 }
 
-template hipError_t launch_accurate_prescale<double>(const double *, int64_t, const double *, int64_t,
-                                                     int64_t, int64_t, int64_t, void *, int8_t *,
+template hipError_t launch_accurate_prescale<double>(const double *, int64_t, bool, const double *, int64_t,
+                                                     bool, int64_t, int64_t, int64_t, void *, int8_t *,
                                                      int8_t *, int64_t, int64_t, int64_t, hipStream_t);
-template hipError_t launch_accurate_prescale<float>(const float *, int64_t, const float *, int64_t,
-                                                    int64_t, int64_t, int64_t, void *, int8_t *,
+template hipError_t launch_accurate_prescale<float>(const float *, int64_t, bool, const float *, int64_t,
+                                                    bool, int64_t, int64_t, int64_t, void *, int8_t *,
                                                     int8_t *, int64_t, int64_t, int64_t, hipStream_t);
 
 }  // namespace oz2

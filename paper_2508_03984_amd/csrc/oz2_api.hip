@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstring>
 #include <mutex>
+#include <new>
 
 #include "../../include/oz2.h"
 #include "oz2_constants.hpp"
@@ -17,28 +18,65 @@ using namespace oz2;
 inline int64_t round_up(int64_t x, int64_t to) { return (x + to - 1) / to * to; }
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// Workspace: [scratch | tA | tB | residues of A | residues of B | products].  A product of
+// prepared operands uses the product part only (its shifts and residues live in the operands).
 struct Layout {
     int64_t m, n, k, Mp, Np, Kp;
     int N;
     bool prod_u8;
-    size_t off_bt, off_ta, off_tb, off_ra, off_rb, off_prod, total;
+    size_t off_bt, off_ta, off_tb, off_ra, off_rb, off_prod;
+    size_t prod_whole, prod_min;           // product part: all of C at once / one 256 x 256 panel
 };
 
-Layout make_layout(int64_t m, int64_t n, int64_t k, int N, bool prod_u8) {
+// Bytes of product workspace per entry of C: N planes of uint8, or of int32 (diagnostic form);
+// accurate mode keeps its int32 Cbar in the same place, hence at least one int32 plane.
+inline size_t bytes_per_entry(int N, bool prod_u8) { return std::max<size_t>((size_t)N * (prod_u8 ? 1 : 4), 4); }
+
+Layout make_layout(int64_t m, int64_t n, int64_t k, int N, bool prod_u8, bool with_operands = true) {
     Layout L{};
     L.m = m; L.n = n; L.k = k; L.N = N; L.prod_u8 = prod_u8;
     L.Mp = round_up(m, kPadMN); L.Np = round_up(n, kPadMN); L.Kp = round_up(k, kPadK);
     size_t o = 0;
-    L.off_bt = o;   o += align256(std::max(column_scratch_bytes(n), accurate_scratch_bytes(m, n)));
-    L.off_ta = o;   o += align256((size_t)m * 4);
-    L.off_tb = o;   o += align256((size_t)n * 4);
-    L.off_ra = o;   o += align256((size_t)N * L.Mp * L.Kp);
-    L.off_rb = o;   o += align256((size_t)N * L.Np * L.Kp);
-    // products: N planes of uint8, or of int32 (diagnostic form; accurate mode also keeps
-    // its int32 Cbar in plane 0, hence at least one int32 plane)
-    L.off_prod = o; o += align256(std::max((size_t)N * L.Mp * L.Np * (prod_u8 ? 1 : 4), (size_t)L.Mp * L.Np * 4));
-    L.total = o;
+    if (with_operands) {
+        L.off_bt = o;   o += align256(std::max(column_scratch_bytes(std::max(m, n)), accurate_scratch_bytes(m, n)));
+        L.off_ta = o;   o += align256((size_t)m * 4);
+        L.off_tb = o;   o += align256((size_t)n * 4);
+        L.off_ra = o;   o += align256((size_t)N * L.Mp * L.Kp);
+        L.off_rb = o;   o += align256((size_t)N * L.Np * L.Kp);
+    }
+    L.off_prod = o;
+    L.prod_whole = align256((size_t)L.Mp * L.Np * bytes_per_entry(N, prod_u8));
+    L.prod_min = align256((size_t)kPadMN * kPadMN * bytes_per_entry(N, prod_u8));
     return L;
+}
+
+// How C is cut: panels of (pr x pc) entries (multiples of 256; the last ones may be smaller).
+struct Panels {
+    int64_t pr, pc, count;
+};
+
+// The largest panels whose N product planes fit into `avail` bytes: all of C if possible,
+// otherwise as square as the shape allows (the INT8 GEMM re-reads a row panel of the A slices
+// once per column panel and vice versa), multiples of 4096 when that large so that the
+// GEMM's tile map stays XCD-aware.
+bool plan_panels(const Layout &L, size_t avail, Panels *out) {
+    const size_t per = bytes_per_entry(L.N, L.prod_u8);
+    if (avail >= L.prod_whole) { *out = Panels{L.Mp, L.Np, 1}; return true; }
+    const int64_t entries = (int64_t)(avail / per);
+    if (entries < kPadMN * kPadMN) return false;
+    int64_t s = kPadMN;
+    while ((s + kPadMN) * (s + kPadMN) <= entries) s += kPadMN;
+    if (s >= 4096) s = s / 4096 * 4096;
+    int64_t pr = std::min(L.Mp, s), pc = std::min(L.Np, s);
+    auto widen = [&](int64_t other, int64_t now, int64_t limit) {   // what fits beside `other`
+        int64_t w = entries / other / kPadMN * kPadMN;
+        if (w >= 4096) w = w / 4096 * 4096;
+        return std::max(now, std::min(limit, w));
+    };
+    pc = widen(pr, pc, L.Np);
+    pr = widen(pc, pr, L.Mp);
+    *out = Panels{pr, pc, ((L.Mp + pr - 1) / pr) * ((L.Np + pc - 1) / pc)};
+    return true;
 }
 
 struct State {
@@ -46,8 +84,12 @@ struct State {
     char *ws = nullptr;
     size_t ws_bytes = 0;
     bool ws_owned = false;
+    size_t ws_limit = 0;                   // for the library's own buffer; 0 = none
     Layout last{};
-    bool have_last = false;
+    Panels last_panels{0, 0, 0};
+    bool have_last = false;                // shifts and residues of the last call are in the workspace
+    bool have_last_prod = false;           // ... and so are all its products
+    bool have_panels = false;
     bool profiling = false;
     bool int32_products = false;           // diagnostic form: keep C'_s as int32
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
@@ -59,17 +101,28 @@ bool supported(int64_t k, int N) {
     return N >= OZ2_MIN_MODULI && N <= OZ2_MAX_MODULI && k <= OZ2_MAX_K_BLOCKED;
 }
 
-oz2_status ensure_workspace(size_t need) {
-    if (g.ws && g.ws_bytes >= need) return OZ2_OK;
-    if (g.ws && !g.ws_owned) return OZ2_WORKSPACE;            // caller-owned and too small
-    if (g.ws) {
-        if (hipDeviceSynchronize() != hipSuccess) return OZ2_HIP_ERROR;
-        (void)hipFree(g.ws);
-        g.ws = nullptr; g.ws_bytes = 0;
+// Makes at least `need_min` bytes of workspace available, `need_whole` if nothing limits it;
+// *have receives the bytes the call may use.
+oz2_status ensure_workspace(size_t need_whole, size_t need_min, size_t *have) {
+    if (g.ws && !g.ws_owned) {                                // caller-owned: take it as it is
+        if (g.ws_bytes < need_min) return OZ2_WORKSPACE;
+        *have = g.ws_bytes;
+        return OZ2_OK;
     }
-    void *p = nullptr;
-    if (hipMalloc(&p, need) != hipSuccess) { (void)hipGetLastError(); return OZ2_WORKSPACE; }
-    g.ws = static_cast<char *>(p); g.ws_bytes = need; g.ws_owned = true;
+    size_t want = need_whole;
+    if (g.ws_limit && want > g.ws_limit) want = g.ws_limit;
+    if (want < need_min) return OZ2_WORKSPACE;
+    if (!g.ws || g.ws_bytes < want) {
+        if (g.ws) {
+            if (hipDeviceSynchronize() != hipSuccess) return OZ2_HIP_ERROR;
+            (void)hipFree(g.ws);
+            g.ws = nullptr; g.ws_bytes = 0;
+        }
+        void *p = nullptr;
+        if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return OZ2_WORKSPACE; }
+        g.ws = static_cast<char *>(p); g.ws_bytes = want; g.ws_owned = true;
+    }
+    *have = g.ws_limit ? std::min(g.ws_bytes, std::max(g.ws_limit, need_min)) : g.ws_bytes;
     return OZ2_OK;
 }
 
@@ -82,11 +135,57 @@ oz2_status mark(int i, hipStream_t stream) {
     return OZ2_OK;
 }
 
+// Algorithm 1 lines 1-5 (fast mode) for one factor: its shifts and its residue slices.  The
+// vectors that get a scale factor (rows of op(A), columns of op(B)) are either contiguous in the
+// stored matrix (row kernels) or strided by its leading dimension (column kernels).
 template <typename T>
-oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, int64_t lda,
-                     const T *B, int64_t ldb, double beta, T *C, int64_t ldc, int N,
+hipError_t launch_fast_shifts(const T *X, int64_t ld, bool k_contiguous, int64_t rows, int64_t k,
+                              const ShiftArgs &sa, void *scratch, int32_t *t, hipStream_t stream) {
+    return k_contiguous ? launch_shifts<T>(X, ld, rows, k, sa, t, stream)
+                        : launch_shifts_cols<T>(X, ld, k, rows, sa, scratch, t, stream);
+}
+
+template <typename T>
+hipError_t launch_any_residues(const T *X, int64_t ld, bool k_contiguous, int64_t rows, int64_t k,
+                               const int32_t *t, const ModArgs &ma, int8_t *out, int64_t rows_pad,
+                               int64_t Kp, hipStream_t stream) {
+    return k_contiguous ? launch_residues<T>(X, ld, rows, k, t, ma, out, rows_pad, Kp, stream)
+                        : launch_residues_cols<T>(X, ld, k, rows, t, ma, out, rows_pad, Kp, stream);
+}
+
+// Algorithm 1 lines 6-12 panel by panel: the INT8 GEMMs of one panel of C (Section 4.3: exact
+// INT32 accumulation for k <= 2^17; a longer contraction is cut into K ranges of at most 2^17
+// whose reduced results are folded together modulo p_s), then its accumulation and unscaling.
+template <typename T>
+oz2_status run_products(const Layout &L, const Panels &P, const int8_t *rA, const int8_t *rB,
+                        const int32_t *tA, const int32_t *tB, void *prod, const ModArgs &ma,
+                        double alpha, double beta, T *C, int64_t ldc, hipStream_t stream) {
+    int64_t done = 0;
+    for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
+        for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
+            const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);
+            const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
+            for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
+                const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
+                OZ2_TRY(launch_int8_gemm(rA, rB, prod, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0,
+                                         &ma, stream, &pn));
+            }
+            if (++done == P.count)                            // stage times: the last accumulation only
+                if (oz2_status st = mark(3, stream)) return st;
+            OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, rows, cols, std::min(L.m - row0, rows),
+                                       std::min(L.n - col0, cols), tA + row0, tB + col0, ma, alpha, beta,
+                                       C + row0 * ldc + col0, ldc, stream));
+        }
+    return mark(4, stream);
+}
+
+template <typename T>
+oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, double alpha, const T *A,
+                     int64_t lda, const T *B, int64_t ldb, double beta, T *C, int64_t ldc, int N,
                      hipStream_t stream, bool accurate) {
-    if (m < 0 || n < 0 || k < 0) return OZ2_INVALID_ARG;
+    if (m < 0 || n < 0 || k < 0 || (opA != OZ2_OP_N && opA != OZ2_OP_T) ||
+        (opB != OZ2_OP_N && opB != OZ2_OP_T))
+        return OZ2_INVALID_ARG;
     if (!supported(k, N) || (accurate && k > OZ2_MAX_K)) return OZ2_UNSUPPORTED;
     if (m == 0 || n == 0) return OZ2_OK;
     if (!C || ldc < n) return OZ2_INVALID_ARG;
@@ -94,7 +193,8 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
         OZ2_TRY(launch_scale_c<T>(C, ldc, m, n, beta, stream));
         return OZ2_OK;
     }
-    if (!A || !B || lda < k || ldb < n) return OZ2_INVALID_ARG;
+    const bool a_kc = opA == OZ2_OP_N, b_kc = opB == OZ2_OP_T;   // is k the contiguous index?
+    if (!A || !B || lda < (a_kc ? k : m) || ldb < (b_kc ? k : n)) return OZ2_INVALID_ARG;
 
     std::lock_guard<std::mutex> lock(g.mu);
     const bool is_double = sizeof(T) == 8;
@@ -102,10 +202,14 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
     const ModArgs ma = make_mod_args(tab);
     const ShiftArgs sa = make_shift_args(tab);
     const Layout L = make_layout(m, n, k, N, !g.int32_products);
-    if (oz2_status st = ensure_workspace(L.total)) return st;
-    g.last = L; g.have_last = true; g.ev_recorded = false;
+    size_t have = 0;
+    Panels P{};
+    if (oz2_status st = ensure_workspace(L.off_prod + L.prod_whole, L.off_prod + L.prod_min, &have)) return st;
+    if (!plan_panels(L, have - L.off_prod, &P)) return OZ2_WORKSPACE;
+    g.last = L; g.last_panels = P; g.have_panels = true;
+    g.have_last = true; g.have_last_prod = P.count == 1; g.ev_recorded = false;
 
-    void *col_scratch = g.ws + L.off_bt;
+    void *scratch = g.ws + L.off_bt;
     int32_t *tA = reinterpret_cast<int32_t *>(g.ws + L.off_ta);
     int32_t *tB = reinterpret_cast<int32_t *>(g.ws + L.off_tb);
     int8_t *rA = reinterpret_cast<int8_t *>(g.ws + L.off_ra);
@@ -114,32 +218,104 @@ oz2_status gemm_impl(int64_t m, int64_t n, int64_t k, double alpha, const T *A, 
 
     if (oz2_status st = mark(0, stream)) return st;
     if (accurate) {
-        // Section 4.2, accurate mode: 7-bit matrices into slice 0, Cbar into plane 0.
-        OZ2_TRY(launch_accurate_prescale<T>(A, lda, B, ldb, m, n, k, col_scratch, rA, rB, L.Mp, L.Np,
-                                            L.Kp, stream));
-        OZ2_TRY(launch_int8_gemm(rA, rB, prod, 1, L.Mp, L.Np, L.Kp, 0, L.Kp, false, false, nullptr,
-                                 stream));
-        OZ2_TRY(launch_accurate_shifts(static_cast<const int32_t *>(prod), L.Np, m, n,
-                                       make_accu_shift_args(tab), col_scratch, tA, tB, stream));
+        // Section 4.2, accurate mode: 7-bit matrices into slice 0, Cbar panel by panel into the
+        // product part, of which only the row and column maxima are kept.
+        OZ2_TRY(launch_accurate_prescale<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, scratch, rA, rB, L.Mp,
+                                            L.Np, L.Kp, stream));
+        OZ2_TRY(launch_accurate_maxima_clear(m, n, scratch, stream));
+        for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
+            for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
+                const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);
+                const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
+                OZ2_TRY(launch_int8_gemm(rA, rB, prod, 1, L.Mp, L.Np, L.Kp, 0, L.Kp, false, false, nullptr,
+                                         stream, &pn));
+                OZ2_TRY(launch_accurate_maxima(static_cast<const int32_t *>(prod), cols, row0,
+                                               std::min(m - row0, rows), col0, std::min(n - col0, cols), m,
+                                               n, scratch, stream));
+            }
+        OZ2_TRY(launch_accurate_finish(m, n, make_accu_shift_args(tab), scratch, tA, tB, stream));
     } else {
-        OZ2_TRY(launch_shifts<T>(A, lda, m, k, sa, tA, stream));
-        OZ2_TRY(launch_shifts_cols<T>(B, ldb, k, n, sa, col_scratch, tB, stream));
+        OZ2_TRY(launch_fast_shifts<T>(A, lda, a_kc, m, k, sa, scratch, tA, stream));
+        OZ2_TRY(launch_fast_shifts<T>(B, ldb, b_kc, n, k, sa, scratch, tB, stream));
     }
     if (oz2_status st = mark(1, stream)) return st;
-    OZ2_TRY(launch_residues<T>(A, lda, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
-    OZ2_TRY(launch_residues_cols<T>(B, ldb, k, n, tB, ma, rB, L.Np, L.Kp, stream));
+    OZ2_TRY(launch_any_residues<T>(A, lda, a_kc, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
+    OZ2_TRY(launch_any_residues<T>(B, ldb, b_kc, n, k, tB, ma, rB, L.Np, L.Kp, stream));
     if (oz2_status st = mark(2, stream)) return st;
-    // Section 4.3: INT32 accumulation is exact for k <= 2^17; a longer contraction is cut into
-    // K ranges of at most 2^17 whose reduced results are folded together modulo p_s.
-    for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
-        const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
-        OZ2_TRY(launch_int8_gemm(rA, rB, prod, N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0, &ma,
-                                 stream));
-    }
-    if (oz2_status st = mark(3, stream)) return st;
-    OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, L.Mp, L.Np, m, n, tA, tB, ma, alpha, beta, C, ldc,
-                               stream));
-    if (oz2_status st = mark(4, stream)) return st;
+    if (oz2_status st = run_products<T>(L, P, rA, rB, tA, tB, prod, ma, alpha, beta, C, ldc, stream)) return st;
+    g.ev_recorded = g.profiling;
+    return OZ2_OK;
+}
+
+}  // namespace
+
+// A prepared factor (oz2_prepare_*): the shifts and residue slices of Algorithm 1 lines 1-5.
+struct oz2_operand {
+    int side;                              // 0 = left factor, 1 = right factor
+    bool is_double;
+    int N;
+    int64_t rows, k, rows_pad, Kp;
+    char *mem;                             // one device allocation: [t | residues | scratch]
+    size_t bytes;
+    int32_t *t;
+    int8_t *res;
+};
+
+namespace {
+
+template <typename T>
+oz2_status prepare_impl(int side, oz2_op op, int64_t rows, int64_t k, const T *X, int64_t ld, int N,
+                        hipStream_t stream, oz2_operand **out) {
+    if (!out || (side != 0 && side != 1) || (op != OZ2_OP_N && op != OZ2_OP_T) || rows < 1 || k < 1 || !X)
+        return OZ2_INVALID_ARG;
+    if (!supported(k, N)) return OZ2_UNSUPPORTED;
+    const bool k_contiguous = (side == 0) == (op == OZ2_OP_N);
+    if (ld < (k_contiguous ? k : rows)) return OZ2_INVALID_ARG;
+
+    const bool is_double = sizeof(T) == 8;
+    const Table &tab = table(N, is_double);
+    oz2_operand *o = new (std::nothrow) oz2_operand{};
+    if (!o) return OZ2_WORKSPACE;
+    o->side = side; o->is_double = is_double; o->N = N; o->rows = rows; o->k = k;
+    o->rows_pad = round_up(rows, kPadMN); o->Kp = round_up(k, kPadK);
+    const size_t off_res = align256((size_t)rows * 4);
+    const size_t off_scratch = off_res + align256((size_t)N * o->rows_pad * o->Kp);
+    o->bytes = off_scratch + align256(column_scratch_bytes(rows));
+    void *p = nullptr;
+    if (hipMalloc(&p, o->bytes) != hipSuccess) { (void)hipGetLastError(); delete o; return OZ2_WORKSPACE; }
+    o->mem = static_cast<char *>(p);
+    o->t = reinterpret_cast<int32_t *>(o->mem);
+    o->res = reinterpret_cast<int8_t *>(o->mem + off_res);
+    hipError_t e = launch_fast_shifts<T>(X, ld, k_contiguous, rows, k, make_shift_args(tab),
+                                         o->mem + off_scratch, o->t, stream);
+    if (e == hipSuccess)
+        e = launch_any_residues<T>(X, ld, k_contiguous, rows, k, o->t, make_mod_args(tab), o->res,
+                                   o->rows_pad, o->Kp, stream);
+    if (e != hipSuccess) { (void)hipFree(o->mem); delete o; return OZ2_HIP_ERROR; }
+    *out = o;
+    return OZ2_OK;
+}
+
+template <typename T>
+oz2_status prepared_impl(const oz2_operand *l, const oz2_operand *r, double alpha, double beta, T *C,
+                         int64_t ldc, hipStream_t stream) {
+    const bool is_double = sizeof(T) == 8;
+    if (!l || !r || l->side != 0 || r->side != 1 || l->k != r->k || l->N != r->N ||
+        l->is_double != is_double || r->is_double != is_double || !C || ldc < r->rows)
+        return OZ2_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g.mu);
+    const ModArgs ma = make_mod_args(table(l->N, is_double));
+    const Layout L = make_layout(l->rows, r->rows, l->k, l->N, !g.int32_products, false);
+    size_t have = 0;
+    Panels P{};
+    if (oz2_status st = ensure_workspace(L.prod_whole, L.prod_min, &have)) return st;
+    if (!plan_panels(L, have, &P)) return OZ2_WORKSPACE;
+    g.last_panels = P; g.have_panels = true;
+    g.have_last = g.have_last_prod = false; g.ev_recorded = false;
+    for (int i = 0; i < 3; ++i)
+        if (oz2_status st = mark(i, stream)) return st;
+    if (oz2_status st = run_products<T>(L, P, l->res, r->res, l->t, r->t, g.ws, ma, alpha, beta, C, ldc, stream))
+        return st;
     g.ev_recorded = g.profiling;
     return OZ2_OK;
 }
@@ -151,33 +327,112 @@ extern "C" {
 oz2_status oz2_dgemm(int64_t m, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
                      const double *B, int64_t ldb, double beta, double *C, int64_t ldc,
                      int num_moduli, hipStream_t stream) {
-    return gemm_impl<double>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream, false);
+    return gemm_impl<double>(OZ2_OP_N, OZ2_OP_N, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli,
+                             stream, false);
 }
 
 oz2_status oz2_dgemm_accurate(int64_t m, int64_t n, int64_t k, double alpha, const double *A,
                               int64_t lda, const double *B, int64_t ldb, double beta, double *C,
                               int64_t ldc, int num_moduli, hipStream_t stream) {
-    return gemm_impl<double>(m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream, true);
+    return gemm_impl<double>(OZ2_OP_N, OZ2_OP_N, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli,
+                             stream, true);
 }
 
 oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha, const float *A,
                               int64_t lda, const float *B, int64_t ldb, float beta, float *C,
                               int64_t ldc, int num_moduli, hipStream_t stream) {
-    return gemm_impl<float>(m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
+    return gemm_impl<float>(OZ2_OP_N, OZ2_OP_N, m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
                             num_moduli, stream, true);
 }
 
 oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
                      const float *B, int64_t ldb, float beta, float *C, int64_t ldc,
                      int num_moduli, hipStream_t stream) {
-    return gemm_impl<float>(m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
+    return gemm_impl<float>(OZ2_OP_N, OZ2_OP_N, m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
                             num_moduli, stream, false);
+}
+
+oz2_status oz2_dgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                        double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
+                        double beta, double *C, int64_t ldc, int num_moduli, hipStream_t stream) {
+    return gemm_impl<double>(opA, opB, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream,
+                             accurate != 0);
+}
+
+oz2_status oz2_sgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                        float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                        float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream) {
+    return gemm_impl<float>(opA, opB, m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
+                            num_moduli, stream, accurate != 0);
+}
+
+oz2_status oz2_prepare_d(int side, oz2_op op, int64_t rows, int64_t k, const double *X, int64_t ld,
+                         int num_moduli, hipStream_t stream, oz2_operand **out) {
+    return prepare_impl<double>(side, op, rows, k, X, ld, num_moduli, stream, out);
+}
+
+oz2_status oz2_prepare_s(int side, oz2_op op, int64_t rows, int64_t k, const float *X, int64_t ld,
+                         int num_moduli, hipStream_t stream, oz2_operand **out) {
+    return prepare_impl<float>(side, op, rows, k, X, ld, num_moduli, stream, out);
+}
+
+void oz2_operand_free(oz2_operand *operand) {
+    if (!operand) return;
+    (void)hipFree(operand->mem);
+    delete operand;
+}
+
+size_t oz2_operand_bytes(const oz2_operand *operand) { return operand ? operand->bytes : 0; }
+
+oz2_status oz2_dgemm_prepared(const oz2_operand *left, const oz2_operand *right, double alpha,
+                              double beta, double *C, int64_t ldc, hipStream_t stream) {
+    return prepared_impl<double>(left, right, alpha, beta, C, ldc, stream);
+}
+
+oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right, float alpha,
+                              float beta, float *C, int64_t ldc, hipStream_t stream) {
+    return prepared_impl<float>(left, right, (double)alpha, (double)beta, C, ldc, stream);
 }
 
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double) {
     if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
     (void)is_double;                                          // the workspace holds no input-typed data
-    return make_layout(m, n, k, num_moduli, !g.int32_products).total;
+    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
+    return L.off_prod + L.prod_whole;
+}
+
+size_t oz2_workspace_min_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double) {
+    if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
+    (void)is_double;
+    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
+    return L.off_prod + L.prod_min;
+}
+
+void oz2_set_workspace_limit(size_t bytes) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.ws_limit = bytes;
+}
+
+oz2_status oz2_plan_panels(int64_t m, int64_t n, int64_t k, int num_moduli, size_t workspace_bytes,
+                           int64_t *panel_rows, int64_t *panel_cols, int64_t *count) {
+    if (m <= 0 || n <= 0 || k <= 0) return OZ2_INVALID_ARG;
+    if (!supported(k, num_moduli)) return OZ2_UNSUPPORTED;
+    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
+    Panels P{};
+    if (workspace_bytes < L.off_prod || !plan_panels(L, workspace_bytes - L.off_prod, &P)) return OZ2_WORKSPACE;
+    if (panel_rows) *panel_rows = P.pr;
+    if (panel_cols) *panel_cols = P.pc;
+    if (count) *count = P.count;
+    return OZ2_OK;
+}
+
+oz2_status oz2_last_panels(int64_t *panel_rows, int64_t *panel_cols, int64_t *count) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (!g.have_panels) return OZ2_INVALID_ARG;
+    if (panel_rows) *panel_rows = g.last_panels.pr;
+    if (panel_cols) *panel_cols = g.last_panels.pc;
+    if (count) *count = g.last_panels.count;
+    return OZ2_OK;
 }
 
 oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes) {
@@ -190,7 +445,7 @@ oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes) {
     g.ws = static_cast<char *>(dev_ptr);
     g.ws_bytes = dev_ptr ? bytes : 0;
     g.ws_owned = false;
-    g.have_last = false;
+    g.have_last = g.have_last_prod = false;
     return OZ2_OK;
 }
 
@@ -200,7 +455,7 @@ void oz2_release(void) {
         (void)hipDeviceSynchronize();
         (void)hipFree(g.ws);
     }
-    g.ws = nullptr; g.ws_bytes = 0; g.ws_owned = false; g.have_last = false;
+    g.ws = nullptr; g.ws_bytes = 0; g.ws_owned = false; g.have_last = g.have_last_prod = false;
     for (auto &e : g.ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
     g.ev_recorded = false;
 }
@@ -252,10 +507,10 @@ oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims) {
     case OZ2_STAGE_RES_A: *dev_ptr = g.ws + L.off_ra; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Kp; dims[3] = L.m; break;
     case OZ2_STAGE_RES_B: *dev_ptr = g.ws + L.off_rb; dims[0] = L.N; dims[1] = L.Np; dims[2] = L.Kp; dims[3] = L.n; break;
     case OZ2_STAGE_PROD:
-        if (L.prod_u8) return OZ2_INVALID_ARG;                // not kept in this form: see oz2_set_int32_products
+        if (L.prod_u8 || !g.have_last_prod) return OZ2_INVALID_ARG;                // not kept in this form: see oz2_set_int32_products
         *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
     case OZ2_STAGE_U:
-        if (!L.prod_u8) return OZ2_INVALID_ARG;
+        if (!L.prod_u8 || !g.have_last_prod) return OZ2_INVALID_ARG;
         *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
     default: return OZ2_INVALID_ARG;
     }

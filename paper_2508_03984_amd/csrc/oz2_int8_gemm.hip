@@ -92,6 +92,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
                                                    const int8_t *__restrict__ B,
                                                    void *__restrict__ C, int64_t Mp,
                                                    int64_t Np, int64_t KB, int kb0, int KT,
+                                                   int64_t c_ld, int64_t c_plane,
                                                    TileMap tmap, GemmMods mods) {
     constexpr int THREADS = 64 * WM * WN;              // WM x WN wavefronts
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
     // (the mulhi form: an FP64 floor/fma version of this reduction measured 1.1 ms slower
     // per launch at 16 x 16384^3)
     const int p = mods.p[s], pv = mods.pinv_prime[s];
-    const int64_t c_off = ((int64_t)s * Mp + bm) * Np + bn;
+    const int64_t c_off = (int64_t)s * c_plane + bm * c_ld + bn;   // C: [slice][row][column]
     if (OUT == kOutU8) {
         // Four residues per register quad pack into one dword; the two half-wavefronts hold
         // alternating dwords of a row (columns 8g + 4*(l/32) ...), so they swap two dwords
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
                                     : v4i{(int)d[0], (int)r0, (int)d[1], (int)r1};
                 const int row = wm * 32 * TM + i * 32 + lrow;
                 const int col = wn * 32 * TN + j * 32 + 16 * lhalf;
-                *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * Np + col) = q;
+                *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * c_ld + col) = q;
             }
         return;
     }
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
             for (int g = 0; g < 4; ++g) {
                 const int row = wm * 32 * TM + i * 32 + lrow;
                 const int col = wn * 32 * TN + j * 32 + 8 * g + 4 * lhalf;
-                const int64_t at = c_off + (int64_t)row * Np + col;
+                const int64_t at = c_off + (int64_t)row * c_ld + col;
                 int v[4];
 #pragma unroll
                 for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
@@ -298,8 +299,8 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
 
 template <int WM, int WN, int TM, int TN, int BK, int STAGES, int OUT>
 hipError_t launch(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp, int64_t Np,
-                  int64_t Kp, int64_t k_begin, int64_t k_len, const GemmMods &mods,
-                  hipStream_t stream) {
+                  int64_t Kp, int64_t k_begin, int64_t k_len, const GemmPanel &pn,
+                  const GemmMods &mods, hipStream_t stream) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
     static bool attr_set = false;
@@ -311,45 +312,51 @@ hipError_t launch(const int8_t *A, const int8_t *B, void *C, int batch, int64_t 
         attr_set = true;
     }
     TileMap tm;
-    tm.tiles_m = (int)(Mp / BM);
-    tm.tiles_n = (int)(Np / BN);
+    tm.tiles_m = (int)(pn.rows / BM);
+    tm.tiles_n = (int)(pn.cols / BN);
     tm.swizzled = (tm.tiles_m % 16 == 0 && tm.tiles_n % 16 == 0) ? 1 : 0;
     const int64_t total = (int64_t)tm.tiles_m * tm.tiles_n * batch;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL((k_int8_gemm<WM, WN, TM, TN, BK, STAGES, OUT>), dim3((unsigned)total),
-                       dim3(64 * WM * WN), lds_bytes, stream, A, B, C, Mp, Np, Kp / BK,
-                       (int)(k_begin / BK), (int)(k_len / BK), tm, mods);
+                       dim3(64 * WM * WN), lds_bytes, stream, A + pn.row0 * BK, B + pn.col0 * BK, C, Mp,
+                       Np, Kp / BK, (int)(k_begin / BK), (int)(k_len / BK), pn.c_ld, pn.c_plane, tm, mods);
     return hipGetLastError();
 }
 
 template <int OUT>
 hipError_t launch_out(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp, int64_t Np,
-                      int64_t Kp, int64_t k_begin, int64_t k_len, const GemmMods &mods,
-                      hipStream_t stream) {
+                      int64_t Kp, int64_t k_begin, int64_t k_len, const GemmPanel &pn,
+                      const GemmMods &mods, hipStream_t stream) {
     // Small problems get the 128 x 128 tile so that more workgroups exist.
-    if (Mp * Np * batch < (int64_t)256 * 256 * 512)
-        return launch<2, 2, 2, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
+    if (pn.rows * pn.cols * batch < (int64_t)256 * 256 * 512)
+        return launch<2, 2, 2, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream);
     // 8 wavefronts (2 per SIMD), each 128 x 64: measured against 4 wavefronts of 128 x 128 on
     // the same device it is 2 % faster at 16 x 16384^3 -- a wavefront that is held up issuing
     // a load leaves the matrix core to its SIMD partner.
-    return launch<2, 4, 4, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
+    return launch<2, 4, 4, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream);
 }
 
 }  // namespace
 
 hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp,
                             int64_t Np, int64_t Kp, int64_t k_begin, int64_t k_len, bool as_u8,
-                            bool fold, const ModArgs *ma, hipStream_t stream) {
+                            bool fold, const ModArgs *ma, hipStream_t stream, const GemmPanel *panel) {
+    const GemmPanel whole{0, Mp, 0, Np, Np, Mp * Np};
+    const GemmPanel &pn = panel ? *panel : whole;
+    if (pn.row0 < 0 || pn.col0 < 0 || pn.rows < kPadMN || pn.cols < kPadMN || pn.row0 % kPadMN ||
+        pn.col0 % kPadMN || pn.rows % kPadMN || pn.cols % kPadMN || pn.row0 + pn.rows > Mp ||
+        pn.col0 + pn.cols > Np || pn.c_ld < pn.cols || pn.c_ld % 16 || pn.c_plane % 16)
+        return hipErrorInvalidValue;                       // whole tiles, 16-byte stores
     GemmMods mods{};
     if (ma)
         for (int i = 0; i < ma->n; ++i) { mods.p[i] = ma->p[i]; mods.pinv_prime[i] = (int32_t)ma->pinv_prime[i]; }
     else if (as_u8 || fold)
         return hipErrorInvalidValue;                       // the reduced forms need the moduli
     if (as_u8)
-        return fold ? launch_out<kOutU8Fold>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream)
-                    : launch_out<kOutU8>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
-    return fold ? launch_out<kOutI32Fold>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream)
-                : launch_out<kOutI32>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, mods, stream);
+        return fold ? launch_out<kOutU8Fold>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream)
+                    : launch_out<kOutU8>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream);
+    return fold ? launch_out<kOutI32Fold>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream)
+                : launch_out<kOutI32>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream);
 }
 
 }  // namespace oz2

@@ -88,17 +88,23 @@ hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t co
 //   launch_accurate_prescale   max|.| per row of A / column of B, mu' = 2^(5-e), nu', and
 //                              Abar = ceil(mu' |A|), Bbar = ceil(|B| nu') as int8
 //   (the caller then runs launch_int8_gemm with batch 1 to get Cbar = Abar * Bbar)
-//   launch_accurate_shifts     row / column maxima of Cbar over its m x n part and
-//                              t = (5 - e) + floor(P'_accu - 0.51 log2 max), zero vectors -> 0
+//   launch_accurate_maxima*    row / column maxima of Cbar over its m x n part
+//   launch_accurate_finish     t = (5 - e) + floor(P'_accu - 0.51 log2 max), zero vectors -> 0
 size_t accurate_scratch_bytes(int64_t m, int64_t n);
 template <typename T>
-hipError_t launch_accurate_prescale(const T *A, int64_t lda, const T *B, int64_t ldb, int64_t m,
-                                    int64_t n, int64_t k, void *scratch, int8_t *Abar,
-                                    int8_t *Bbar, int64_t Mp, int64_t Np, int64_t Kp,
-                                    hipStream_t stream);
-hipError_t launch_accurate_shifts(const int32_t *Cbar, int64_t Np, int64_t m, int64_t n,
-                                  const ShiftArgs &sa, void *scratch, int32_t *tA, int32_t *tB,
+hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous, const T *B,
+                                    int64_t ldb, bool b_k_contiguous, int64_t m, int64_t n,
+                                    int64_t k, void *scratch, int8_t *Abar, int8_t *Bbar,
+                                    int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream);
+// Maxima of Cbar, panel by panel: _clear zeroes them; _maxima folds in the (rows x cols) valid
+// part of one panel of Cbar (leading dimension ld) whose top-left entry is (row0, col0) of the
+// whole product; _finish turns them into the shifts.
+hipError_t launch_accurate_maxima_clear(int64_t m, int64_t n, void *scratch, hipStream_t stream);
+hipError_t launch_accurate_maxima(const int32_t *Cbar, int64_t ld, int64_t row0, int64_t rows,
+                                  int64_t col0, int64_t cols, int64_t m, int64_t n, void *scratch,
                                   hipStream_t stream);
+hipError_t launch_accurate_finish(int64_t m, int64_t n, const ShiftArgs &sa, void *scratch,
+                                  int32_t *tA, int32_t *tB, hipStream_t stream);
 
 // Row / column kernels in "magnitude" form, used by accurate mode:
 // out[h / 64][r][h % 64] = ceil(|X[r][h]| * 2^pre[r]) (int8), zero beyond rows / len.
@@ -124,9 +130,19 @@ hipError_t launch_col_maxbits(const T *X, int64_t ld, int64_t rows, int64_t cols
 //                                 second and later K ranges of a product with k > 2^17:
 //                                 int32: mod(old) + mod(new);  uint8: (old + mod(new)) mod p_b
 // ma supplies the moduli (slice b uses p_b); it may be NULL for the plain int32 form.
+// The part of the product that one launch computes and where it goes: rows [row0, row0+rows)
+// of the A slices times rows [col0, col0+cols) of the B slices (all multiples of 256), written
+// to C[slice * c_plane + (row - row0) * c_ld + (column - col0)].
+struct GemmPanel {
+    int64_t row0, rows, col0, cols;
+    int64_t c_ld, c_plane;              // in elements; multiples of 16
+};
+
+// panel == nullptr: the whole product, C = [batch][Mp][Np].
 hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp,
                             int64_t Np, int64_t Kp, int64_t k_begin, int64_t k_len, bool as_u8,
-                            bool fold, const ModArgs *ma, hipStream_t stream);
+                            bool fold, const ModArgs *ma, hipStream_t stream,
+                            const GemmPanel *panel = nullptr);
 
 // Algorithm 1 lines 7-12 and the alpha/beta update, fused:
 // C[i][j] = alpha * ldexp(C''(i,j), -(tA[i]+tB[j])) + beta * C[i][j]   (OutT = double or float)

@@ -127,3 +127,58 @@ def test_argument_checks_need_no_gpu(oz):
     assert lib.oz2_mfma_probe(1, 60.0, C.byref(t), None, None) == 1   # longer than the limit
     assert lib.oz2_mfma_probe(1, 0.1, None, None, None) == 1
     assert "moduli" in oz.oz2_status_string(2)
+
+
+def test_general_entry_points_check_their_arguments_without_a_gpu(oz):
+    lib = oz.load()
+    null, one = C.c_void_p(0), C.c_void_p(256)
+    op = lambda opA, opB, m, n, k, lda, ldb, ldc, N=14, acc=0: lib.oz2_dgemm_op(
+        opA, opB, acc, m, n, k, 1.0, one, lda, one, ldb, 0.0, one, ldc, N, null)
+    assert op(2, 0, 4, 4, 4, 4, 4, 4) == 1 and op(0, 3, 4, 4, 4, 4, 4, 4) == 1
+    assert op(1, 0, 4, 6, 5, 3, 6, 6) == 1                    # A^T is stored 5 x 4: lda >= 4
+    assert op(0, 1, 4, 6, 5, 5, 4, 6) == 1                    # B^T is stored 6 x 5: ldb >= 5
+    assert op(1, 1, 0, 6, 5, 1, 5, 6) == 0                    # empty: no-op
+    assert op(1, 1, 4, 6, 2 ** 17 + 1, 4, 2 ** 17 + 1, 6, acc=1) == 2   # accurate mode: k <= 2^17
+    out = C.c_void_p(0)
+    prep = lambda side, o, rows, k, ld, N=14, X=one: lib.oz2_prepare_d(side, o, rows, k, X, ld, N, null,
+                                                                      C.byref(out))
+    assert prep(2, 0, 4, 4, 4) == 1 and prep(0, 2, 4, 4, 4) == 1 and prep(0, 0, 0, 4, 4) == 1
+    assert prep(0, 0, 4, 0, 4) == 1 and prep(0, 0, 4, 4, 4, X=null) == 1
+    assert prep(0, 0, 4, 8, 7) == 1 and prep(0, 1, 4, 8, 3) == 1      # left: ld >= k, or >= rows if stored transposed
+    assert prep(1, 0, 4, 8, 3) == 1 and prep(1, 1, 4, 8, 7) == 1      # right: ld >= rows, or >= k if stored transposed
+    assert prep(0, 0, 4, 4, 4, N=21) == 2 and prep(0, 0, 4, 2 ** 20 + 1, 2 ** 20 + 1) == 2
+    assert out.value is None                                  # written only on success
+    assert lib.oz2_dgemm_prepared(null, null, 1.0, 0.0, one, 4, null) == 1
+    assert lib.oz2_operand_bytes(null) == 0
+    lib.oz2_operand_free(null)
+    assert lib.oz2_last_panels(None, None, None) in (0, 1)
+
+
+@pytest.mark.parametrize("m,n,k,N", [(700, 1100, 200, 15), (16384, 16384, 16384, 16), (8192, 300, 1000, 20),
+                                     (256, 40000, 512, 2), (100000, 5000, 128, 12)])
+def test_panel_plan_covers_c_within_the_workspace(oz, m, n, k, N):
+    """Host logic of the bounded workspace: every plan fits, covers C, and uses whole tiles."""
+    need = oz.oz2_workspace_bytes(m, n, k, N)
+    least = oz.oz2_workspace_min_bytes(m, n, k, N)
+    Mp, Np = -(-m // 256) * 256, -(-n // 256) * 256
+    per = max(N, 4)
+    fixed = need - Mp * Np * per
+    assert fixed == least - 256 * 256 * per and fixed >= N * (Mp + Np) * k
+    assert oz.oz2_plan_panels(m, n, k, N, need) == (Mp, Np, 1)
+    assert oz.oz2_plan_panels(m, n, k, N, need + 12345) == (Mp, Np, 1)
+    with pytest.raises(oz.OZ2Error) as e:
+        oz.oz2_plan_panels(m, n, k, N, least - 1)
+    assert e.value.status == 3
+    rng = np.random.default_rng(m + n)
+    sizes = [least, least + 1, need - 1] + [int(x) for x in rng.integers(least, need, 40)]
+    last = 0
+    for ws in sorted(sizes):
+        pr, pc, count = oz.oz2_plan_panels(m, n, k, N, ws)
+        assert pr % 256 == 0 and pc % 256 == 0 and 256 <= pr <= Mp and 256 <= pc <= Np
+        assert fixed + pr * pc * per <= ws                     # fits
+        assert count == -(-Mp // pr) * -(-Np // pc) and (count > 1 or ws >= need)
+        assert pr * pc * 4 > min((ws - fixed) // per, Mp * Np) or pr * pc >= 4096 * 4096 // 4   # not wasteful
+        assert pr * pc >= last or pr * pc >= 4096 * 256       # more room never shrinks small panels
+        last = pr * pc
+    with pytest.raises(oz.OZ2Error):
+        oz.oz2_plan_panels(m, n, 2 ** 20 + 1, N, need)

@@ -1,0 +1,279 @@
+"""GPU parity of the general entry points: transposed operands (oz2_*gemm_op), prepared
+operands (oz2_prepare_* / oz2_*gemm_prepared) and products cut into panels by a bounded
+workspace.  The oracle knows none of these: a transposed operand is handed to it as the matrix
+it stands for, and a panelled or prepared product must equal the plain one bit for bit."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+TOL64 = 1e-14
+TOL32 = 2.0 ** -23
+
+
+@pytest.fixture(scope="module")
+def oz():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2508_03984_amd as oz
+    oz.load()
+    yield oz
+    oz.oz2_set_workspace_limit(0)
+    oz.oz2_release()
+
+
+def stored(X, transposed, ld_extra, dt):
+    """X (numpy) on the device as op(stored): stored = X or X^T, rows padded by ld_extra."""
+    import torch
+    M = np.ascontiguousarray(X.T) if transposed else X
+    buf = torch.full((M.shape[0], M.shape[1] + ld_extra), 7.0, dtype=dt, device="cuda")
+    buf[:, :M.shape[1]] = torch.from_numpy(M).cuda()
+    return buf, M.shape[1] + ld_extra
+
+
+def run_op(oz, A, B, N, opA, opB, accurate=False, alpha=1.0, beta=0.0, Cin=None, lda_extra=3, ldb_extra=5):
+    import torch
+    from paper_2508_03984_amd import binding as b
+    m, k = A.shape
+    n = B.shape[1]
+    is_double = A.dtype == np.float64
+    dt = torch.float64 if is_double else torch.float32
+    dA, lda = stored(A, opA, lda_extra, dt)
+    dB, ldb = stored(B, opB, ldb_extra, dt)
+    dC = torch.full((m, n), float("nan"), dtype=dt, device="cuda")
+    if Cin is not None:
+        dC.copy_(torch.from_numpy(Cin).cuda())
+    fn = oz.oz2_dgemm_op if is_double else oz.oz2_sgemm_op
+    fn(int(opA), int(opB), accurate, m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+    torch.cuda.synchronize()
+    ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A))
+    rb = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_B))
+    assert bool((ra[:, m:, :] == 0).all() and (ra[:, :, k:] == 0).all())
+    assert bool((rb[:, n:, :] == 0).all() and (rb[:, :, k:] == 0).all())
+    return dict(C=dC.cpu().numpy(), tA=oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(),
+                tB=oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(),
+                Ares=ra[:, :m, :k].cpu().numpy(), Bres=rb[:, :n, :k].cpu().numpy(),
+                U=oz.stage_tensor(b.OZ2_STAGE_U)[:, :m, :n].cpu().numpy())
+
+
+def check(got, ref, is_double):
+    for key in ("tA", "tB", "Ares", "Bres", "U"):
+        assert np.array_equal(got[key], ref[key]), key
+    c, r = got["C"].astype(np.float64), ref["C"].astype(np.float64)
+    rel = np.max(np.abs(c - r) / np.where(r == 0, 1.0, np.abs(r)))
+    assert rel <= (TOL64 if is_double else TOL32), rel
+
+
+OP_CASES = [
+    # m, n, k, N, phi, dtype
+    (300, 200, 333, 16, 0.5, np.float64),
+    (70, 130, 515, 13, 2.0, np.float64),
+    (1, 1, 1, 2, 0.5, np.float64),
+    (257, 65, 129, 20, 1.0, np.float64),
+    (300, 200, 333, 8, 0.5, np.float32),
+    (97, 515, 260, 5, 1.0, np.float32),
+]
+
+
+@pytest.mark.parametrize("opA,opB", [(0, 1), (1, 0), (1, 1), (0, 0)])
+@pytest.mark.parametrize("m,n,k,N,phi,dtype", OP_CASES)
+def test_transposed_operands_fast_mode(oz, oracle, m, n, k, N, phi, dtype, opA, opB):
+    A, B = S.gemm_inputs(m, n, k, phi, seed=50 + N, dtype=dtype)
+    is_double = dtype == np.float64
+    check(run_op(oz, A, B, N, opA, opB), oracle.gemm(A, B, N, is_double=is_double), is_double)
+
+
+@pytest.mark.parametrize("opA,opB", [(0, 1), (1, 0), (1, 1)])
+def test_transposed_operands_accurate_mode_alpha_beta(oz, oracle, opA, opB):
+    A, B = S.gemm_inputs(150, 260, 300, 2.0, seed=61)
+    A[4, :] = 0.0; B[:, 9] = 0.0
+    Cin = S.matrix(150, 260, 0.5, seed=62)
+    ref = oracle.gemm(A, B, 15, -0.75, 1.5, Cin, accurate=True)
+    check(run_op(oz, A, B, 15, opA, opB, True, -0.75, 1.5, Cin), ref, True)
+    A32, B32 = A.astype(np.float32), B.astype(np.float32)
+    ref = oracle.gemm(A32, B32, 7, is_double=False, accurate=True)
+    check(run_op(oz, A32, B32, 7, opA, opB, True), ref, False)
+
+
+def test_matmul_accepts_transposed_views(oz, oracle):
+    import torch
+    A, B = S.gemm_inputs(90, 70, 110, 0.5, seed=63)
+    want = oracle.gemm(A, B, 14)["C"]
+    dAt = torch.from_numpy(np.ascontiguousarray(A.T)).cuda()
+    dBt = torch.from_numpy(np.ascontiguousarray(B.T)).cuda()
+    assert np.array_equal(oz.matmul(dAt.t(), dBt.t(), 14).cpu().numpy(), want)
+    assert np.array_equal(oz.matmul(torch.from_numpy(A).cuda(), dBt.t(), 14).cpu().numpy(), want)
+    # the Gram matrix A A^T from one stored matrix
+    dA = torch.from_numpy(A).cuda()
+    assert np.array_equal(oz.matmul(dA, dA.t(), 14).cpu().numpy(),
+                          oracle.gemm(A, np.ascontiguousarray(A.T), 14)["C"])
+
+
+def test_op_argument_checks(oz):
+    import torch
+    X = torch.zeros((8, 8), dtype=torch.float64, device="cuda")
+    for bad in (dict(opA=2), dict(opB=-1), dict(lda=3), dict(ldb=3)):
+        a = dict(opA=1, opB=0, lda=4, ldb=6)
+        a.update(bad)
+        with pytest.raises(oz.OZ2Error) as e:               # op(A) = A^T: stored 5 x 4, lda >= 4
+            oz.oz2_dgemm_op(a["opA"], a["opB"], 0, 4, 6, 5, 1.0, X, a["lda"], X, a["ldb"], 0.0, X, 8, 14)
+        assert e.value.status == 1
+
+
+# ------------------------------------------------------------------ bounded workspace
+@pytest.mark.parametrize("accurate", [False, True])
+@pytest.mark.parametrize("dtype,N", [(np.float64, 15), (np.float32, 6)])
+def test_panelled_product_is_bit_identical(oz, oracle, dtype, N, accurate):
+    import torch
+    m, n, k = 700, 1100, 200                               # 3 x 5 tiles of 256
+    A, B = S.gemm_inputs(m, n, k, 1.0, seed=70, dtype=dtype)
+    Cin = S.matrix(m, n, 0.5, seed=71, dtype=dtype)
+    is_double = dtype == np.float64
+    ref = oracle.gemm(A, B, N, 0.5, -2.0, Cin, is_double=is_double, accurate=accurate)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    whole = oz.matmul(dA, dB, N, 0.5, -2.0, torch.from_numpy(Cin).cuda(), accurate=accurate)
+    assert oz.oz2_last_panels() == (768, 1280, 1)
+    need = oz.oz2_workspace_bytes(m, n, k, N, is_double)
+    least = oz.oz2_workspace_min_bytes(m, n, k, N, is_double)
+    per_entry = max(N, 4)
+    seen = set()
+    try:
+        for entries in (256 * 256, 2 * 256 * 256, 512 * 512 + 7, 768 * 512, 768 * 1024 + 100):
+            limit = least - 256 * 256 * per_entry + entries * per_entry
+            assert limit < need
+            oz.oz2_set_workspace_limit(limit)
+            oz.oz2_release()                               # a buffer allocated earlier may be larger
+            got = oz.matmul(dA, dB, N, 0.5, -2.0, torch.from_numpy(Cin).cuda(), accurate=accurate)
+            pr, pc, count = oz.oz2_last_panels()
+            assert (pr, pc, count) == oz.oz2_plan_panels(m, n, k, N, limit)
+            assert count > 1 and pr * pc <= entries and pr % 256 == 0 and pc % 256 == 0
+            seen.add((pr, pc))
+            assert torch.equal(got, whole), (pr, pc)
+            from paper_2508_03984_amd import binding as b
+            assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), ref["tA"])
+            assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), ref["tB"])
+            with pytest.raises(oz.OZ2Error):               # only the last panel's products remain
+                oz.oz2_stage_ptr(b.OZ2_STAGE_U)
+        oz.oz2_set_workspace_limit(least - 256)
+        oz.oz2_release()
+        with pytest.raises(oz.OZ2Error) as e:
+            oz.matmul(dA, dB, N)
+        assert e.value.status == 3
+    finally:
+        oz.oz2_set_workspace_limit(0)
+        oz.oz2_release()
+    assert len(seen) >= 4                                  # different cuts were exercised
+    c, r = whole.cpu().numpy().astype(np.float64), ref["C"].astype(np.float64)
+    assert np.max(np.abs(c - r) / np.where(r == 0, 1.0, np.abs(r))) <= (TOL64 if is_double else TOL32)
+
+
+def test_panelled_product_with_k_ranges_and_caller_workspace(oz, oracle):
+    """k > 2^17 (two K ranges folded modulo p_s) inside each of several panels, in a
+    caller-owned workspace that is too small for all of C."""
+    import torch
+    m, n, k = 260, 24, 2 ** 17 + 200
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=72)
+    ref = oracle.gemm(A, B, 14)
+    least = oz.oz2_workspace_min_bytes(m, n, k, 14, True)
+    buf = torch.empty(least, dtype=torch.uint8, device="cuda")     # one tile of C at a time
+    oz.oz2_set_workspace(buf)
+    try:
+        got = oz.matmul(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), 14)
+        assert oz.oz2_last_panels() == (256, 256, 2)
+        assert np.array_equal(got.cpu().numpy(), ref["C"])
+    finally:
+        oz.oz2_set_workspace(None)
+
+
+# ------------------------------------------------------------------ prepared operands
+@pytest.mark.parametrize("dtype,N", [(np.float64, 16), (np.float32, 8)])
+def test_prepared_operands_equal_the_plain_call(oz, oracle, dtype, N):
+    import torch
+    m, n, k = 300, 200, 333
+    is_double = dtype == np.float64
+    dt = torch.float64 if is_double else torch.float32
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=80, dtype=dtype)
+    B2 = S.matrix(k, 90, 1.0, seed=82, dtype=dtype)
+    Cin = S.matrix(m, n, 0.5, seed=81, dtype=dtype)
+    prep = oz.oz2_prepare_d if is_double else oz.oz2_prepare_s
+    prod = oz.oz2_dgemm_prepared if is_double else oz.oz2_sgemm_prepared
+    tol = TOL64 if is_double else TOL32
+    for opA in (0, 1):
+        for opB in (0, 1):
+            dA, lda = stored(A, opA, 2, dt)
+            dB, ldb = stored(B, opB, 1, dt)
+            L = prep(0, opA, m, k, dA, lda, N)
+            R = prep(1, opB, n, k, dB, ldb, N)
+            assert L.nbytes >= N * 512 * 384 and R.nbytes >= N * 256 * 384
+            dA.fill_(1.0); dB.fill_(1.0)                   # the operands hold everything needed
+            dC = torch.from_numpy(Cin).cuda()
+            prod(L, R, 1.5, 0.25, dC, n)
+            want = oracle.gemm(A, B, N, 1.5, 0.25, Cin, is_double=is_double)["C"]
+            c, r = dC.cpu().numpy().astype(np.float64), want.astype(np.float64)
+            assert np.max(np.abs(c - r) / np.where(r == 0, 1.0, np.abs(r))) <= tol
+            # the left operand again, with another right factor
+            dB2, ldb2 = stored(B2, opB, 0, dt)
+            R2 = prep(1, opB, 90, k, dB2, ldb2, N)
+            dC2 = torch.empty((m, 90), dtype=dt, device="cuda")
+            prod(L, R2, 1.0, 0.0, dC2, 90)
+            assert np.array_equal(dC2.cpu().numpy(), oracle.gemm(A, B2, N, is_double=is_double)["C"])
+            with pytest.raises(oz.OZ2Error):               # no stage of a prepared product is kept
+                oz.oz2_stage_ptr(0)
+            for h in (L, R, R2):
+                h.free()
+
+
+def test_prepared_operand_checks(oz):
+    import torch
+    X = torch.zeros((300, 300), dtype=torch.float64, device="cuda")
+    X32 = X.float()
+    L = oz.oz2_prepare_d(0, 0, 300, 200, X, 300, 14)
+    R = oz.oz2_prepare_d(1, 0, 300, 200, X, 300, 14)
+    C = torch.empty((300, 300), dtype=torch.float64, device="cuda")
+    bad = [(R, R), (L, L), (L, oz.oz2_prepare_d(1, 0, 300, 100, X, 300, 14)),
+           (L, oz.oz2_prepare_d(1, 0, 300, 200, X, 300, 15)), (L, oz.oz2_prepare_s(1, 0, 300, 200, X32, 300, 14))]
+    for l, r in bad:
+        with pytest.raises(oz.OZ2Error) as e:
+            oz.oz2_dgemm_prepared(l, r, 1.0, 0.0, C, 300)
+        assert e.value.status == 1
+    with pytest.raises(oz.OZ2Error):
+        oz.oz2_dgemm_prepared(L, R, 1.0, 0.0, C, 299)      # ldc < n
+    with pytest.raises(oz.OZ2Error):
+        oz.oz2_sgemm_prepared(L, R, 1.0, 0.0, C.float(), 300)
+    oz.oz2_dgemm_prepared(L, R, 1.0, 0.0, C, 300)
+    torch.cuda.synchronize()
+    assert bool((C == 0).all())
+    L.free(); L.free()                                     # idempotent
+
+
+def test_prepared_operands_at_4096_with_panels(oz, oracle):
+    """A 4096^3 product of prepared operands, whole and cut into 4 panels, against sampled
+    oracle rows."""
+    import torch
+    m = n = k = 4096
+    N = 15
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=0)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    L = oz.oz2_prepare_d(0, 0, m, k, dA, k, N)
+    R = oz.oz2_prepare_d(1, 0, n, k, dB, n, N)
+    C1 = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    oz.oz2_dgemm_prepared(L, R, 1.0, 0.0, C1, n)
+    assert oz.oz2_last_panels() == (4096, 4096, 1)
+    assert torch.equal(C1, oz.matmul(dA, dB, N))
+    try:
+        oz.oz2_set_workspace_limit(N * 2048 * 2048 + 4096)
+        oz.oz2_release()
+        C2 = torch.empty_like(C1)
+        oz.oz2_dgemm_prepared(L, R, 1.0, 0.0, C2, n)
+        assert oz.oz2_last_panels() == (2048, 2048, 4)
+        assert torch.equal(C1, C2)
+    finally:
+        oz.oz2_set_workspace_limit(0)
+        oz.oz2_release()
+    prep = oracle.prepare(A, B, N, True, False)
+    rows = np.array([0, 1777, 4095])
+    fin = oracle.finish_rows(prep, rows)
+    assert np.array_equal(C1[torch.from_numpy(rows).cuda()].cpu().numpy(), fin["C"])
+    L.free(); R.free()

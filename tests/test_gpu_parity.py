@@ -316,7 +316,9 @@ def test_caller_owned_workspace(oz, oracle):
     import torch
     A, B = S.gemm_inputs(100, 120, 140, 0.5, seed=6)
     need = oz.oz2_workspace_bytes(100, 120, 140, 14, True)
-    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    least = oz.oz2_workspace_min_bytes(100, 120, 140, 14, True)
+    assert least == need                                   # C fits one 256 x 256 panel
+    small = torch.empty(least - 256, dtype=torch.uint8, device="cuda")
     oz.oz2_set_workspace(small)
     with pytest.raises(oz.OZ2Error) as e:
         oz.matmul(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), 14)
