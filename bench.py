@@ -235,6 +235,86 @@ def sweep(oz, torch, name, args) -> int:
     return 0
 
 
+def sweep_general(oz, torch, args) -> int:
+    """Times the general entry points on one shape (--size, --moduli, FP64): the four
+    transposition cases of oz2_dgemm_op, a product of prepared operands (and the
+    preparation itself), and products cut into panels by a workspace limit.  Every result is
+    compared with the plain call's bit for bit.  One JSON line per case goes to --out."""
+    import numpy as np
+    import synth_inputs as S
+    m = n = k = args.size
+    N = args.moduli
+    path = args.out or "sweep_general.jsonl"
+    if os.path.dirname(path):
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+    A, B = S.gemm_inputs(m, n, k, args.phi, seed=0)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dAt, dBt = dA.t().contiguous(), dB.t().contiguous()
+    want = oz.matmul(dA, dB, N).clone()
+    dC = torch.empty_like(want)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        oz.oz2_set_profiling(True)
+        stage_ms = np.zeros(4)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+            stage_ms += np.array(oz.oz2_last_stage_times_ms())
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        oz.oz2_set_profiling(False)
+        return dt, (stage_ms / args.steps).round(3).tolist()
+
+    with open(path, "w") as f:
+        def emit(case, dt, stage_ms, **extra):
+            rec = {"case": case, "m": m, "n": n, "k": k, "num_moduli": N, "ms": 1e3 * dt,
+                   "emulated_tflops": 2.0 * m * n * k / dt / 1e12, "stage_ms": stage_ms,
+                   "equals_plain_call": bool(torch.equal(dC, want))}
+            rec.update(extra)
+            log(json.dumps(rec))
+            f.write(json.dumps(rec) + "\n")
+            f.flush()
+
+        for opA, opB, X, Y in ((0, 0, dA, dB), (0, 1, dA, dBt), (1, 0, dAt, dB), (1, 1, dAt, dBt)):
+            dC.zero_()
+            dt, st = timed(lambda: oz.oz2_dgemm_op(opA, opB, 0, m, n, k, 1.0, X, X.shape[1], Y, Y.shape[1],
+                                                   0.0, dC, n, N))
+            emit(f"op(A)={'NT'[opA]} op(B)={'NT'[opB]}", dt, st)
+
+        # prepared operands: Algorithm 1 lines 1-5 once per matrix, then products only
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        L = oz.oz2_prepare_d(0, 0, m, k, dA, k, N)
+        R = oz.oz2_prepare_d(1, 0, n, k, dB, n, N)
+        torch.cuda.synchronize()
+        prep_ms = 1e3 * (time.perf_counter() - t0)
+        dC.zero_()
+        dt, st = timed(lambda: oz.oz2_dgemm_prepared(L, R, 1.0, 0.0, dC, n))
+        emit("prepared operands (product only)", dt, st, prepare_both_ms_incl_alloc=prep_ms,
+             operand_bytes=[L.nbytes, R.nbytes])
+        L.free(); R.free()
+
+        # bounded workspace: C in 4 and in 16 panels
+        least = oz.oz2_workspace_min_bytes(m, n, k, N)
+        for frac in (4, 16):
+            if m // 256 < frac:
+                continue
+            limit = least - max(N, 4) * 256 * 256 + max(N, 4) * (m * n // frac)
+            oz.oz2_set_workspace_limit(limit)
+            oz.oz2_release()
+            dC.zero_()
+            dt, st = timed(lambda: oz.oz2_dgemm(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N))
+            emit(f"workspace limited to 1/{frac} of the products", dt, st,
+                 panels=list(oz.oz2_last_panels()), workspace_bytes=limit)
+        oz.oz2_set_workspace_limit(0)
+    print(json.dumps({"sweep": "general", "file": path}), flush=True)
+    oz.oz2_release()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -255,7 +335,7 @@ def main() -> int:
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
                          "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
                          "counters); both print a reduced JSON line")
-    ap.add_argument("--sweep", choices=sorted(SWEEPS), default=None,
+    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general"], default=None,
                     help="time a whole configuration of the benchmark set over its moduli counts; "
                          "one JSON line per case goes to --out")
     ap.add_argument("--out", default=None, help="file for --sweep (default: sweep_<name>.jsonl)")
@@ -282,6 +362,8 @@ def main() -> int:
 
     m = n = k = args.size
     N = args.moduli
+    if args.sweep == "general":
+        return sweep_general(oz, torch, args)
     if args.sweep:
         return sweep(oz, torch, args.sweep, args)
     if args.stage == "int8_gemm":
