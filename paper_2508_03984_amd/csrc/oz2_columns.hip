@@ -91,11 +91,11 @@ __global__ __launch_bounds__(256) void k_col_finish(const unsigned long long *__
 }
 
 // Same reduction as in the row kernel (see oz2_prepost.hip for why it is exact).
-template <int ROUNDS>
-__device__ inline int residue_of(double x, double p, double pinv) {
-    double y = fma(-rint(x * pinv), p, x);
-    if (ROUNDS == 2) y = fma(-rint(y * pinv), p, y);
-    return (int)y;
+__device__ inline double group_reduce(double x, double M, double Minv) {
+    return fma(-rint(x * Minv), M, x);
+}
+__device__ inline int residue_of(double y, double p, double pinv) {
+    return (int)fma(-rint(y * pinv), p, y);
 }
 
 // KIND as in the row kernel: 0 = residues for all moduli, 1 = the 7-bit magnitudes (slice 0).
@@ -108,8 +108,9 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
     // LDS: per modulus 8 pieces x 64 columns x 8 bytes, piece-major so that the writes of a
     // wavefront (one piece, 64 columns) are contiguous; 8 bytes of padding per piece row.
     // Moduli are processed kGroup at a time to keep the LDS footprint (and so the number of
-    // resident workgroups) independent of N.
-    constexpr int kGroup = 4;
+    // resident workgroups) independent of N; a group is also what shares the first reduction
+    // round when two are needed.
+    constexpr int kGroup = kModGroup;
     __shared__ uint2 stage[kGroup][8][65];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t c = (int64_t)blockIdx.x * kColStrip + lane;         // column of X = row of the output
@@ -136,6 +137,14 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
     const int n_slices = KIND == 0 ? ma.n : 1;
     for (int s0 = 0; s0 < n_slices; s0 += kGroup) {
         const int ns = n_slices - s0 < kGroup ? n_slices - s0 : kGroup;
+        double y[2][8];
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                y[half][i] = (KIND == 0 && ROUNDS == 2)
+                                 ? group_reduce(v[half][i], ma.group_mod[s0 / kGroup], ma.group_inv[s0 / kGroup])
+                                 : v[half][i];
         for (int g = 0; g < ns; ++g) {
             const double p = (double)ma.p[s0 + g], pinv = ma.pinv[s0 + g];
 #pragma unroll
@@ -143,8 +152,8 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
                 uint32_t w[2] = {0u, 0u};
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    uint32_t b = (KIND == 0 ? (uint32_t)residue_of<ROUNDS>(v[half][i], p, pinv)
-                                            : (uint32_t)(int)v[half][i]) & 0xffu;
+                    uint32_t b = (KIND == 0 ? (uint32_t)residue_of(y[half][i], p, pinv)
+                                            : (uint32_t)(int)y[half][i]) & 0xffu;
                     w[i >> 2] |= b << (8 * (i & 3));
                 }
                 stage[g][wave + 4 * half][lane] = make_uint2(w[0], w[1]);

@@ -17,9 +17,13 @@ constexpr int64_t kPadK = 128;    // contraction length
 constexpr int kBlockK = 64;       // K block of the residue-slice layout [Kp/64][rows][64]
 
 // Per-modulus constants handed to kernels by value (Section 4.1).
+constexpr int kModGroup = 5;             // moduli per pre-reduction group: 256^5 = 2^40 < 2^45
 struct ModArgs {
     int32_t n;
     int32_t rounds;                      // 1 or 2 reduction rounds in the residue kernel
+    // rounds == 2: the product of the moduli of group g = moduli [5g, 5g+5) and double(1/product);
+    // the first round reduces modulo the group's product once for all its members.
+    double group_mod[(kMaxModuli + kModGroup - 1) / kModGroup], group_inv[(kMaxModuli + kModGroup - 1) / kModGroup];
     int32_t p[kMaxModuli];
     uint32_t pinv_prime[kMaxModuli];
     double pinv[kMaxModuli];

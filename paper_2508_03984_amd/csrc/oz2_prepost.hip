@@ -17,6 +17,12 @@ ModArgs make_mod_args(const Table &t) {
         a.s1[i] = t.s1[i];
         a.s2[i] = t.s2[i];
     }
+    for (int g = 0; g * kModGroup < t.n; ++g) {
+        double M = 1.0;                                  // exact: an integer below 2^40
+        for (int i = g * kModGroup; i < t.n && i < (g + 1) * kModGroup; ++i) M *= (double)t.p[i];
+        a.group_mod[g] = M;
+        a.group_inv[g] = 1.0 / M;
+    }
     a.P1 = t.P1; a.P2 = t.P2; a.Pinv = t.Pinv;
     return a;
 }
@@ -116,15 +122,19 @@ __global__ __launch_bounds__(256) void k_shifts(const T *__restrict__ X, int64_t
 //   |y| <= p/2 + 2^-52 |x'|;  for |x'| < 2^46 the quotient estimate is within 2^-13 of
 //   x'/p, closer than any integer/p can be to a half-integer for odd p, so rint returns
 //   round(x'/p) and y is already the residue in [-(p-1)/2, (p-1)/2];
-//   otherwise a second round, now on |y| < 2^26, does the same.
+//   otherwise two rounds.  The first one is shared by up to five moduli: it reduces
+//   modulo their product M < 2^40 (group_reduce), which is exact for the same reason (the
+//   difference is an integer, |y| <= M/2 + 2^-51 |x'| < 2^45) and y = x' (mod M) implies
+//   y = x' (mod p) for every p that divides M; the second round, on |y| < 2^46, is the
+//   one-round case above for each of these p.
 // p = 256: 1/p is exact, y lands in [-128, 128] and the int8 cast wraps 128 to -128,
 // which is the same class (Section 4.1).
 // ----------------------------------------------------------------------------------------
-template <int ROUNDS>
-__device__ inline int residue_of(double x, double p, double pinv) {
-    double y = fma(-rint(x * pinv), p, x);
-    if (ROUNDS == 2) y = fma(-rint(y * pinv), p, y);
-    return (int)y;
+__device__ inline double group_reduce(double x, double M, double Minv) {
+    return fma(-rint(x * Minv), M, x);
+}
+__device__ inline int residue_of(double y, double p, double pinv) {
+    return (int)fma(-rint(y * pinv), p, y);
 }
 
 constexpr int kResPerThread = 8;     // consecutive elements per thread -> 8-byte stores
@@ -183,15 +193,22 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
         *reinterpret_cast<uint2 *>(o) = make_uint2(w[0], w[1]);
         return;
     }
-    for (int s = 0; s < ma.n; ++s) {
-        const double p = (double)ma.p[s], pinv = ma.pinv[s];
-        uint32_t w[2] = {0u, 0u};
+    for (int s0 = 0; s0 < ma.n; s0 += kModGroup) {
+        double y[kResPerThread];
 #pragma unroll
-        for (int i = 0; i < kResPerThread; ++i) {
-            uint32_t b = (uint32_t)residue_of<ROUNDS>(v[i], p, pinv) & 0xffu;
-            w[i >> 2] |= b << (8 * (i & 3));
+        for (int i = 0; i < kResPerThread; ++i)
+            y[i] = ROUNDS == 2 ? group_reduce(v[i], ma.group_mod[s0 / kModGroup], ma.group_inv[s0 / kModGroup]) : v[i];
+        const int s1 = s0 + kModGroup < ma.n ? s0 + kModGroup : ma.n;
+        for (int s = s0; s < s1; ++s) {
+            const double p = (double)ma.p[s], pinv = ma.pinv[s];
+            uint32_t w[2] = {0u, 0u};
+#pragma unroll
+            for (int i = 0; i < kResPerThread; ++i) {
+                uint32_t b = (uint32_t)residue_of(y[i], p, pinv) & 0xffu;
+                w[i >> 2] |= b << (8 * (i & 3));
+            }
+            *reinterpret_cast<uint2 *>(o + (int64_t)s * plane) = make_uint2(w[0], w[1]);
         }
-        *reinterpret_cast<uint2 *>(o + (int64_t)s * plane) = make_uint2(w[0], w[1]);
     }
 }
 
