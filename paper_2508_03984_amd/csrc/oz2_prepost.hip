@@ -1,6 +1,8 @@
 // Bandwidth-bound kernels of the emulation for gfx950 (row side: A, and the output):
 // fast-mode shifts (Algorithm 1 line 1), residue slices (lines 2-5) and the fused
 // mod-reduce + CRT + unscale epilogue (lines 7-12).  64-wide wavefronts throughout.
+#include <type_traits>
+
 #include "oz2_kernels.hpp"
 
 namespace oz2 {
@@ -49,10 +51,10 @@ constexpr int kWave = 64;
 
 // ----------------------------------------------------------------------------------------
 // Shifts.  One workgroup per row: pass 1 finds max|x| (as an integer compare of the FP64
-// bit patterns), pass 2 re-reads the row (mostly from L2 / the memory-side cache; keeping the
-// row in registers instead measured slower, 0.81 against 0.67 ms at 16384^2) and sums q^2 with
-// q = ceil(|x| 2^(15-e)) <= 2^16 in 64-bit integers, which is exact and independent of
-// the order of summation.  f comes from the threshold table, t = f - e.
+// bit patterns), pass 2 sums q^2 with q = ceil(|x| 2^(15-e)) <= 2^16 in 64-bit integers, which
+// is exact and independent of the order of summation.  f comes from the threshold table,
+// t = f - e.  k_shifts re-reads the row for pass 2 (rows of any length); k_shifts_cached
+// further down keeps rows of up to 16384 elements in registers between the passes.
 // ----------------------------------------------------------------------------------------
 __device__ inline uint64_t wave_max(uint64_t v) {
     for (int off = kWave / 2; off > 0; off >>= 1) {
@@ -213,6 +215,86 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
 }
 
 // ----------------------------------------------------------------------------------------
+// Shifts of rows of up to 16384 elements, reading each row once: the row is held in registers
+// (CH pieces of 8 elements per thread, 8 threads per 64 elements), its maximum and then its
+// integer sum of squares come from two workgroup reductions.  Same result as k_shifts, half
+// its memory traffic (0.34 against 0.67 ms at 16384^2 FP64).  (Computing the residues from
+// the same registers as well was measured: no faster than the separate residue kernel, because
+// a workgroup that owns one row writes 64-byte pieces 1 MiB apart.)
+// ----------------------------------------------------------------------------------------
+template <typename T, int THREADS, int CH>
+__global__ __launch_bounds__(THREADS) void k_shifts_cached(const T *__restrict__ X, int64_t ld,
+                                                           int64_t len, ShiftArgs sa,
+                                                           int32_t *__restrict__ t_out) {
+    constexpr int kPer = 8;                                           // elements per piece
+    constexpr int kWaves = THREADS / kWave;
+    __shared__ uint64_t part[kWaves];
+    __shared__ uint64_t bcast;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const T *x = X + (int64_t)blockIdx.x * ld;
+    const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+
+    double v[CH][kPer];
+    uint64_t mx = 0;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int64_t h0 = ((int64_t)c * THREADS + threadIdx.x) * kPer;
+        if (h0 + kPer <= len && aligned) {
+            constexpr int kVec = 16 / sizeof(T);
+            typedef T vec_t __attribute__((ext_vector_type(kVec)));
+#pragma unroll
+            for (int i = 0; i < kPer / kVec; ++i) {
+                const vec_t q = reinterpret_cast<const vec_t *>(x + h0)[i];
+#pragma unroll
+                for (int e = 0; e < kVec; ++e) v[c][i * kVec + e] = (double)q[e];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) v[c][i] = (h0 + i < len) ? (double)x[h0 + i] : 0.0;
+        }
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const uint64_t bits = (uint64_t)__double_as_longlong(fabs(v[c][i]));
+            mx = bits > mx ? bits : mx;
+        }
+    }
+    mx = wave_max(mx);
+    if (lane == 0) part[wave] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t m = part[0];
+        for (int w = 1; w < kWaves; ++w) m = part[w] > m ? part[w] : m;
+        bcast = m;
+    }
+    __syncthreads();
+    mx = bcast;
+    if (mx == 0) {                                                    // all-zero row
+        if (threadIdx.x == 0) t_out[blockIdx.x] = 0;
+        return;
+    }
+    const int e = floor_log2_of_bits(mx);
+    uint64_t sum = 0;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const uint64_t qi = (uint64_t)ceil(ldexp(fabs(v[c][i]), 15 - e));
+            sum += qi * qi;
+        }
+    sum = wave_sum(sum);
+    __syncthreads();                                                  // part[] is reused
+    if (lane == 0) part[wave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t T_ = 0;
+        for (int w = 0; w < kWaves; ++w) T_ += part[w];
+        int j = 0;
+        while (j < sa.levels - 1 && T_ > sa.theta[j]) ++j;
+        t_out[blockIdx.x] = (sa.f_max - j) - e;
+    }
+}
+
+// ----------------------------------------------------------------------------------------
 // Epilogue: for each (i, j) read the N int32 products once, U_s = mod(C'_s, p_s) by the
 // mulhi reduction of Section 4.3, C1 += s_s1 U_s, C2 += s_s2 U_s (s = 1..N, one FMA each),
 // Q = rint(P_inv C1), C'' = fma(-P2, Q, fma(-P1, Q, C1) + C2), c = C'' 2^-(tA_i + tB_j).
@@ -319,7 +401,20 @@ inline unsigned blocks_for(int64_t threads) { return (unsigned)((threads + 255) 
 template <typename T>
 hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, const ShiftArgs &sa,
                          int32_t *t, hipStream_t stream) {
-    hipLaunchKernelGGL((k_shifts<T>), dim3((unsigned)rows), dim3(256), 0, stream, X, ld, len, sa, t);
+    // rows of up to 16384 elements are read once (pieces of 8 elements: 128 threads hold 1024
+    // elements per piece, 512 threads 4096); longer rows are read twice
+    auto cached = [&](auto threads, auto ch) {
+        hipLaunchKernelGGL((k_shifts_cached<T, decltype(threads)::value, decltype(ch)::value>), dim3((unsigned)rows),
+                           dim3(decltype(threads)::value), 0, stream, X, ld, len, sa, t);
+    };
+    using std::integral_constant;
+    if (len <= 1024) cached(integral_constant<int, 128>{}, integral_constant<int, 1>{});
+    else if (len <= 2048) cached(integral_constant<int, 128>{}, integral_constant<int, 2>{});
+    else if (len <= 4096) cached(integral_constant<int, 512>{}, integral_constant<int, 1>{});
+    else if (len <= 8192) cached(integral_constant<int, 512>{}, integral_constant<int, 2>{});
+    else if (len <= 12288) cached(integral_constant<int, 512>{}, integral_constant<int, 3>{});
+    else if (len <= 16384) cached(integral_constant<int, 512>{}, integral_constant<int, 4>{});
+    else hipLaunchKernelGGL((k_shifts<T>), dim3((unsigned)rows), dim3(256), 0, stream, X, ld, len, sa, t);
     return hipGetLastError();
 }
 

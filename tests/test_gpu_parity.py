@@ -107,6 +107,13 @@ CASES = [
     (97, 515, 1030, 9, 0.5, np.float32),
     (64, 64, 512, 2, 0.5, np.float32),
     (70, 66, 300, 20, 0.5, np.float32),        # more moduli than FP32 needs: still exact
+    # rows of A long enough for every form of the shift kernel that reads a row once
+    (40, 50, 2000, 14, 0.5, np.float64),       # 128 threads, 2 pieces per thread
+    (40, 50, 2500, 14, 0.5, np.float64),       # 512 threads, 1 piece
+    (20, 30, 5000, 16, 1.0, np.float32),       # 512 threads, 2 pieces
+    (33, 20, 9000, 13, 0.5, np.float64),       # 512 threads, 3 pieces
+    (17, 19, 16384, 15, 2.0, np.float64),      # 512 threads, 4 pieces: the longest row it takes
+    (18, 21, 16385, 12, 0.5, np.float64),      # one more: the kernel that reads a row twice
 ]
 
 
