@@ -55,10 +55,19 @@ struct Panels {
     int64_t pr, pc, count;
 };
 
-// The largest panels whose N product planes fit into `avail` bytes: all of C if possible,
-// otherwise as square as the shape allows (the INT8 GEMM re-reads a row panel of the A slices
-// once per column panel and vice versa), multiples of 4096 when that large so that the
-// GEMM's tile map stays XCD-aware.
+// Panels whose N product planes fit into `avail` bytes: all of C if possible, otherwise as
+// square as the shape allows (the INT8 GEMM re-reads a row panel of the A slices once per
+// column panel and vice versa).  Panel sides below the full side are 256 times a power of two
+// up to 4096 and multiples of 4096 beyond: then the workgroups of a launch (tiles x moduli) fill
+// the 256 compute units evenly and the GEMM's tile map stays XCD-aware (measured at 16384^3,
+// N = 16: panels of 2816^2 72 ms against 67.8 ms for 2048^2 and 62.9 ms for 4096^2).
+inline int64_t panel_side(int64_t w) {
+    if (w >= 4096) return w / 4096 * 4096;
+    int64_t s = kPadMN;
+    while (2 * s <= w) s *= 2;
+    return s;
+}
+
 bool plan_panels(const Layout &L, size_t avail, Panels *out) {
     const size_t per = bytes_per_entry(L.N, L.prod_u8);
     if (avail >= L.prod_whole) { *out = Panels{L.Mp, L.Np, 1}; return true; }
@@ -66,12 +75,11 @@ bool plan_panels(const Layout &L, size_t avail, Panels *out) {
     if (entries < kPadMN * kPadMN) return false;
     int64_t s = kPadMN;
     while ((s + kPadMN) * (s + kPadMN) <= entries) s += kPadMN;
-    if (s >= 4096) s = s / 4096 * 4096;
+    s = panel_side(s);
     int64_t pr = std::min(L.Mp, s), pc = std::min(L.Np, s);
     auto widen = [&](int64_t other, int64_t now, int64_t limit) {   // what fits beside `other`
-        int64_t w = entries / other / kPadMN * kPadMN;
-        if (w >= 4096) w = w / 4096 * 4096;
-        return std::max(now, std::min(limit, w));
+        const int64_t w = entries / other / kPadMN * kPadMN;
+        return std::max(now, w >= limit ? limit : panel_side(w));
     };
     pc = widen(pr, pc, L.Np);
     pr = widen(pc, pr, L.Mp);

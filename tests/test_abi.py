@@ -177,7 +177,9 @@ def test_panel_plan_covers_c_within_the_workspace(oz, m, n, k, N):
         assert pr % 256 == 0 and pc % 256 == 0 and 256 <= pr <= Mp and 256 <= pc <= Np
         assert fixed + pr * pc * per <= ws                     # fits
         assert count == -(-Mp // pr) * -(-Np // pc) and (count > 1 or ws >= need)
-        assert pr * pc * 4 > min((ws - fixed) // per, Mp * Np) or pr * pc >= 4096 * 4096 // 4   # not wasteful
+        assert pr * pc * 8 > min((ws - fixed) // per, Mp * Np) or pr * pc >= 4096 * 4096 // 4   # not wasteful
+        for side, full in ((pr, Mp), (pc, Np)):               # full, 256 * 2^i, or a multiple of 4096
+            assert side == full or side % 4096 == 0 or (side // 256) & (side // 256 - 1) == 0
         assert pr * pc >= last or pr * pc >= 4096 * 256       # more room never shrinks small panels
         last = pr * pc
     with pytest.raises(oz.OZ2Error):

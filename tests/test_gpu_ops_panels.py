@@ -277,3 +277,41 @@ def test_prepared_operands_at_4096_with_panels(oz, oracle):
     fin = oracle.finish_rows(prep, rows)
     assert np.array_equal(C1[torch.from_numpy(rows).cuda()].cpu().numpy(), fin["C"])
     L.free(); R.free()
+
+
+def test_config_8192_transposed_and_panelled_sampled(oz, oracle):
+    """Benchmark-class size: op(A) = A^T, op(B) = B^T, the product cut into 4 panels; shifts and
+    residues compared in full, U_s of the last panel and C on sampled rows and entries."""
+    import torch
+    from paper_2508_03984_amd import binding as b
+    m = n = k = 8192
+    N = 16
+    A, B = S.gemm_inputs(m, n, k, 1.0, seed=0)
+    dAt = torch.from_numpy(A).cuda().t().contiguous()
+    dBt = torch.from_numpy(B).cuda().t().contiguous()
+    dC = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    least = oz.oz2_workspace_min_bytes(m, n, k, N)
+    try:
+        oz.oz2_set_workspace_limit(least - N * 256 * 256 + N * 4096 * 4096)
+        oz.oz2_release()
+        oz.oz2_dgemm_op(1, 1, 0, m, n, k, 1.0, dAt, m, dBt, k, 0.0, dC, n, N)
+        torch.cuda.synchronize()
+        assert oz.oz2_last_panels() == (4096, 4096, 4)
+        prep = oracle.prepare(A, B, N, True, False)
+        assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
+        assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), prep["tB"])
+        for stage, key, rows_ in ((b.OZ2_STAGE_RES_A, "Ares", m), (b.OZ2_STAGE_RES_B, "Bres", n)):
+            r = oz.unblock_slices(oz.stage_tensor(stage, copy=False))
+            for s in range(N):
+                assert torch.equal(r[s, :rows_, :k], torch.from_numpy(prep[key][s]).cuda()), (key, s)
+            del r
+    finally:
+        oz.oz2_set_workspace_limit(0)
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 4095, 4096, m - 1], rng.integers(0, m, 3)]))
+    fin = oracle.finish_rows(prep, rows)
+    assert np.array_equal(dC[torch.from_numpy(rows).cuda()].cpu().numpy(), fin["C"])
+    ii = rng.integers(0, m, 800); jj = rng.integers(0, n, 800)
+    ent = oracle.finish_entries(prep, ii, jj)
+    assert np.array_equal(dC[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy(), ent["C"])
+    oz.oz2_release()
