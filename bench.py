@@ -315,6 +315,54 @@ def sweep_general(oz, torch, args) -> int:
     return 0
 
 
+def sweep_small(oz, torch, args) -> int:
+    """Launch-bound sizes: one oz2_dgemm call is about ten kernel launches, so for small
+    matrices the call is timed eagerly and as a replayed HIP graph, next to the native GEMM."""
+    import numpy as np
+    import synth_inputs as S
+    N = args.moduli
+    path = args.out or "sweep_small.jsonl"
+    if os.path.dirname(path):
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+
+    def per_call(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    with open(path, "w") as f:
+        for size in (256, 512, 1024, 2048, 4096):
+            m = n = k = size
+            A, B = S.gemm_inputs(m, n, k, args.phi, seed=0)
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+            dC = torch.empty((m, n), dtype=torch.float64, device="cuda")
+            call = lambda: oz.oz2_dgemm(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N)
+            reps = 200 if size <= 1024 else 50
+            eager = per_call(call, reps)
+            want = dC.clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                call()
+            dC.zero_()
+            graph = per_call(g.replay, reps)
+            same = bool(torch.equal(dC, want))
+            native = per_call(lambda: torch.mm(dA, dB, out=dC), reps)
+            rec = {"m": m, "n": n, "k": k, "num_moduli": N, "eager_us": 1e6 * eager, "graph_us": 1e6 * graph,
+                   "native_us": 1e6 * native, "graph_equals_eager": same,
+                   "emulated_tflops_graph": 2.0 * m * n * k / graph / 1e12,
+                   "native_tflops": 2.0 * m * n * k / native / 1e12}
+            log(json.dumps(rec))
+            f.write(json.dumps(rec) + "\n")
+            del g
+    print(json.dumps({"sweep": "small", "file": path}), flush=True)
+    oz.oz2_release()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -335,7 +383,7 @@ def main() -> int:
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
                          "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
                          "counters); both print a reduced JSON line")
-    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general"], default=None,
+    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general", "small"], default=None,
                     help="time a whole configuration of the benchmark set over its moduli counts; "
                          "one JSON line per case goes to --out")
     ap.add_argument("--out", default=None, help="file for --sweep (default: sweep_<name>.jsonl)")
@@ -364,6 +412,8 @@ def main() -> int:
     N = args.moduli
     if args.sweep == "general":
         return sweep_general(oz, torch, args)
+    if args.sweep == "small":
+        return sweep_small(oz, torch, args)
     if args.sweep:
         return sweep(oz, torch, args.sweep, args)
     if args.stage == "int8_gemm":

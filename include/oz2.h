@@ -15,7 +15,10 @@
  *     A and B are only read; host pointers are marked "host";
  *   - calls are asynchronous on `stream`; the returned status reports argument
  *     and launch errors only.  One call may be in flight per process at a time
- *     (the workspace is shared);
+ *     (the workspace is shared).  A product call whose workspace already exists
+ *     (a caller-owned one, or the library's own after a call of at least the same
+ *     size) allocates nothing and clears its scratch with kernels, not memsets, so
+ *     it may be recorded into a HIP graph while profiling is off;
  *   - inputs must be finite.  Inf/NaN inputs give an unspecified (but memory
  *     safe) result: the paper does not define them;
  *   - no entry point throws; none synchronises the device except oz2_release,

@@ -79,9 +79,9 @@ extern "C" oz2_status oz2_mfma_probe(int random_operands, double seconds, double
     int iters = 2000;
     if (hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess) {
         for (int pass = 0; pass < 2; ++pass) {
-            hipEventRecord(e0, nullptr);
+            (void)hipEventRecord(e0, nullptr);
             hipLaunchKernelGGL(k_mfma_probe, dim3(blocks), dim3(kProbeThreads), 0, nullptr, out, iters, random_operands);
-            hipEventRecord(e1, nullptr);
+            (void)hipEventRecord(e1, nullptr);
             if (hipGetLastError() != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
                 hipEventElapsedTime(&ms, e0, e1) != hipSuccess || !(ms > 0.f)) {
                 ms = 0.f;
@@ -97,8 +97,8 @@ extern "C" oz2_status oz2_mfma_probe(int random_operands, double seconds, double
             st = OZ2_OK;
         }
     }
-    if (e0) hipEventDestroy(e0);
-    if (e1) hipEventDestroy(e1);
-    hipFree(out);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(out);
     return st;
 }

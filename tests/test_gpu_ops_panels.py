@@ -315,3 +315,35 @@ def test_config_8192_transposed_and_panelled_sampled(oz, oracle):
     ent = oracle.finish_entries(prep, ii, jj)
     assert np.array_equal(dC[torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()].cpu().numpy(), ent["C"])
     oz.oz2_release()
+
+
+# ------------------------------------------------------------------ HIP graph capture
+@pytest.mark.parametrize("accurate", [False, True])
+def test_call_can_be_captured_into_a_hip_graph(oz, oracle, accurate):
+    """A call allocates nothing once its workspace exists and clears its scratch with fill
+    kernels, so it can be recorded into a HIP graph; every replay, with new contents in the
+    same buffers and eager work in between, must equal the eager result."""
+    import torch
+    m, n, k, N = 300, 520, 700, 15
+    A, B = S.gemm_inputs(m, n, k, 1.0, seed=90)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.zeros((m, n), dtype=torch.float64, device="cuda")
+    oz.matmul(dA, dB, N, out=dC, accurate=accurate)           # allocates the workspace, eagerly
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):                                 # torch's current stream is the capture stream
+        oz.matmul(dA, dB, N, out=dC, accurate=accurate)
+    for rep in range(4):
+        A2, B2 = S.gemm_inputs(m, n, k, 0.5 + 0.5 * rep, seed=91 + 2 * rep)
+        if rep == 2:
+            A2[7, :] = 0.0; B2[:, 11] = 0.0
+        dA.copy_(torch.from_numpy(A2).cuda()); dB.copy_(torch.from_numpy(B2).cuda())
+        dC.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        got = dC.clone()
+        eager = oz.matmul(dA, dB, N, accurate=accurate)       # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager), rep
+        assert np.array_equal(got.cpu().numpy(), oracle.gemm(A2, B2, N, accurate=accurate)["C"]), rep
+    del g
