@@ -347,3 +347,28 @@ def test_call_can_be_captured_into_a_hip_graph(oz, oracle, accurate):
         assert torch.equal(got, eager), rep
         assert np.array_equal(got.cpu().numpy(), oracle.gemm(A2, B2, N, accurate=accurate)["C"]), rep
     del g
+
+
+def test_prepared_transposed_operands_with_k_beyond_2_pow_17(oz, oracle):
+    """Everything at once on a small C: A stored transposed, two K ranges folded modulo p_s,
+    prepared operands, two panels."""
+    import torch
+    m, n, k, N = 40, 300, 2 ** 17 + 700, 13
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=95)
+    dAt = torch.from_numpy(np.ascontiguousarray(A.T)).cuda()
+    dB = torch.from_numpy(B).cuda()
+    want = oracle.gemm(A, B, N)["C"]
+    L = oz.oz2_prepare_d(0, 1, m, k, dAt, m, N)
+    R = oz.oz2_prepare_d(1, 0, n, k, dB, n, N)
+    dC = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    try:
+        oz.oz2_set_workspace_limit(N * 256 * 256)
+        oz.oz2_release()
+        oz.oz2_dgemm_prepared(L, R, 1.0, 0.0, dC, n)
+        assert oz.oz2_last_panels() == (256, 256, 2)
+        assert np.array_equal(dC.cpu().numpy(), want)
+    finally:
+        oz.oz2_set_workspace_limit(0)
+        oz.oz2_release()
+    assert np.array_equal(oz.matmul(dAt.t(), dB, N).cpu().numpy(), want)
+    L.free(); R.free()
