@@ -184,3 +184,25 @@ def test_panel_plan_covers_c_within_the_workspace(oz, m, n, k, N):
         last = pr * pc
     with pytest.raises(oz.OZ2Error):
         oz.oz2_plan_panels(m, n, 2 ** 20 + 1, N, need)
+
+
+def test_binding_layout_helpers_on_the_host():
+    """Argument marshalling that involves no device: the K-blocked slice layout and the
+    detection of transposed views."""
+    import torch
+    from paper_2508_03984_amd import binding as b
+    t = torch.arange(3 * 5 * 128, dtype=torch.int32).reshape(3, 5, 128)
+    blocked = b.block_slices(t)
+    assert blocked.shape == (3, 2, 5, 64)
+    assert blocked[1, 1, 4, 7] == t[1, 4, 64 + 7]             # [s][k / 64][row][k % 64]
+    assert torch.equal(b.unblock_slices(blocked), t)
+    X = torch.zeros((6, 9))
+    assert b._ld(X) == (False, 9) and b._ld(X.t()) == (True, 9)
+    assert b._ld(X[:, :4]) == (False, 9) and b._ld(X[:, :4].t()) == (True, 9)
+    assert b._ld(X[:1]) == (False, 9) and b._ld(X[:, :1]) == (False, 9)
+    assert b._ld(X[:, :1].t()) == (True, 9)                   # 1 x 6 view of a column: stored 6 x 1, ld 9
+    assert b._ld(torch.zeros((1, 1))) == (False, 1)
+    with pytest.raises(ValueError):
+        b._ld(X[:, ::2])                                      # neither row-major nor a transposed view
+    with pytest.raises(ValueError):
+        b.matmul(X, torch.zeros((8, 3)), 14)                  # inner dimensions differ
