@@ -206,3 +206,42 @@ def test_binding_layout_helpers_on_the_host():
         b._ld(X[:, ::2])                                      # neither row-major nor a transposed view
     with pytest.raises(ValueError):
         b.matmul(X, torch.zeros((8, 3)), 14)                  # inner dimensions differ
+
+
+def test_host_constants_code_is_clean_under_sanitizers(tmp_path):
+    """The library's only non-trivial host code (the wide-integer arithmetic behind the
+    constants and the threshold tables) built with AddressSanitizer and UBSan by the host
+    compiler, every table built once; the checksums equal those of a plain optimised build."""
+    import subprocess
+    src = os.path.join(ROOT, "paper_2508_03984_amd", "csrc")
+    main = tmp_path / "main.cpp"
+    main.write_text(r'''
+#include <cstdio>
+#include "oz2_constants.hpp"
+int main() {
+    for (int d = 0; d < 2; ++d)
+        for (int n = oz2::kMinModuli; n <= oz2::kMaxModuli; ++n) {
+            const oz2::Table &t = oz2::table(n, d != 0);
+            double s = t.P1 + t.P2 + t.Pinv + t.Pfast + t.Paccu;
+            unsigned long long x = (unsigned long long)t.f_max * 131 + t.levels * 17 + t.accu_f_max * 7 + t.accu_levels;
+            for (int i = 0; i < t.n; ++i) { s += t.s1[i] * 1e-30 + t.s2[i] * 1e-20 + t.pinv[i]; x = x * 31 + t.p[i] + t.pinv_prime[i]; }
+            for (int j = 0; j < t.levels; ++j) x = x * 33 + t.theta[j];
+            for (int j = 0; j < t.accu_levels; ++j) x = x * 35 + t.accu_theta[j];
+            std::printf("%d %d %.17g %llu\n", d, n, s, x);
+        }
+    return 0;
+}
+''')
+    exe = tmp_path / "consts_san"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-I", src, str(main),
+                           os.path.join(src, "oz2_constants.cpp"), "-o", str(exe)])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1", LD_PRELOAD="")
+    out = subprocess.run([str(exe)], env=env, capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr[-2000:]
+    lines = out.stdout.strip().splitlines()
+    assert len(lines) == 2 * 19
+    plain = tmp_path / "consts_plain"
+    subprocess.check_call(["g++", "-std=c++17", "-O2", "-I", src, str(main),
+                           os.path.join(src, "oz2_constants.cpp"), "-o", str(plain)])
+    assert subprocess.run([str(plain)], capture_output=True, text=True).stdout.strip().splitlines() == lines
