@@ -372,3 +372,58 @@ def test_prepared_transposed_operands_with_k_beyond_2_pow_17(oz, oracle):
         oz.oz2_release()
     assert np.array_equal(oz.matmul(dAt.t(), dB, N).cpu().numpy(), want)
     L.free(); R.free()
+
+
+def test_random_shapes_modes_and_operand_forms_against_the_oracle(oz, oracle):
+    """Seeded sweep over small random problems: shape, number of moduli, exponent spread, FP64 /
+    FP32, fast / accurate mode, transpositions, alpha / beta, leading dimensions and an
+    occasional workspace limit; integer stages bit-exact, C within the tolerance."""
+    import torch
+    rng = np.random.default_rng(2024)
+    for case in range(120):
+        is_double = bool(rng.integers(0, 2))
+        dtype = np.float64 if is_double else np.float32
+        m, n = int(rng.integers(1, 600)), int(rng.integers(1, 600))
+        k = int(rng.choice([1, 7, 64, 129, 500, 1100, 2300]))
+        N = int(rng.integers(2, 21))
+        phi = float(rng.choice([0.5, 1.0, 2.0, 4.0]))
+        accurate = bool(rng.integers(0, 2))
+        opA, opB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        alpha, beta = (1.0, 0.0) if rng.integers(0, 2) else (float(rng.normal()), float(rng.normal()))
+        if not is_double:                                  # oz2_sgemm_op takes alpha and beta as floats
+            alpha, beta = float(np.float32(alpha)), float(np.float32(beta))
+        A, B = S.gemm_inputs(m, n, k, phi, seed=1000 + 2 * case, dtype=dtype)
+        if rng.integers(0, 4) == 0:
+            A[int(rng.integers(0, m)), :] = 0.0
+            B[:, int(rng.integers(0, n))] = 0.0
+        Cin = S.matrix(m, n, 0.5, seed=3000 + case, dtype=dtype) if beta != 0.0 else None
+        ref = oracle.gemm(A, B, N, alpha, beta, Cin, is_double=is_double, accurate=accurate)
+        limited = bool(rng.integers(0, 3) == 0) and max(m, n) > 256
+        try:
+            if limited:
+                oz.oz2_set_workspace_limit(oz.oz2_workspace_min_bytes(m, n, k, N, is_double))
+                oz.oz2_release()
+            got = run_op(oz, A, B, N, opA, opB, accurate, alpha, beta, Cin,
+                         lda_extra=int(rng.integers(0, 9)), ldb_extra=int(rng.integers(0, 9))) \
+                if not limited else None
+            if limited:
+                dt = torch.float64 if is_double else torch.float32
+                dA, lda = stored(A, opA, 1, dt)
+                dB, ldb = stored(B, opB, 2, dt)
+                dC = torch.from_numpy(Cin).cuda() if Cin is not None else torch.empty((m, n), dtype=dt, device="cuda")
+                fn = oz.oz2_dgemm_op if is_double else oz.oz2_sgemm_op
+                fn(opA, opB, accurate, m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+                assert oz.oz2_last_panels()[2] > 1
+                c, r = dC.cpu().numpy().astype(np.float64), ref["C"].astype(np.float64)
+                rel = np.max(np.abs(c - r) / np.where(r == 0, 1.0, np.abs(r)))
+                assert rel <= (TOL64 if is_double else TOL32), (case, rel)
+            else:
+                check(got, ref, is_double)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: m={m} n={n} k={k} N={N} phi={phi} {dtype.__name__} "
+                                 f"accurate={accurate} op=({opA},{opB}) alpha={alpha} beta={beta} "
+                                 f"limited={limited}: {e}")
+        finally:
+            if limited:
+                oz.oz2_set_workspace_limit(0)
+                oz.oz2_release()
