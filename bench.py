@@ -559,7 +559,9 @@ def main() -> int:
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 MFMA with int32 accumulation, f64 reconstruction",
+        "dtype": "int8",
+        "dtype_note": "INT8 MFMA products with exact INT32 accumulation; scaling, residues and CRT "
+                      "reconstruction in FP64; inputs and output " + ("FP32" if args.sgemm else "FP64"),
         "data": "synthetic",
         "config": {"workload": f"{'SGEMM' if args.sgemm else 'DGEMM'} emulation m=n=k={m}, "
                                f"{'fp32' if args.sgemm else 'fp64'} row-major, phi={args.phi}, "
