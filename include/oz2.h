@@ -159,8 +159,9 @@ oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right,
  * problem (0 if the arguments are unsupported).  oz2_set_workspace hands the
  * library a caller-owned device buffer (kept, not freed, must stay valid until
  * replaced; 256-byte aligned); with (NULL, 0) the library goes back to
- * allocating its own buffer with hipMalloc, growing it on demand and keeping
- * it until oz2_release.
+ * allocating its own buffer with hipMalloc (on the device that is current at the
+ * call; a call made with another device current allocates anew there), growing it on
+ * demand and keeping it until oz2_release.
  *
  * Bounded workspace ("block matrix multiplication" over the rows and columns of C): the
  * products U_s are the largest part (num_moduli * m * n bytes).  When the workspace may

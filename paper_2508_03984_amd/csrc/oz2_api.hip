@@ -92,6 +92,7 @@ struct State {
     char *ws = nullptr;
     size_t ws_bytes = 0;
     bool ws_owned = false;
+    int ws_device = -1;                    // device of the library's own buffer
     size_t ws_limit = 0;                   // for the library's own buffer; 0 = none
     Layout last{};
     Panels last_panels{0, 0, 0};
@@ -120,7 +121,9 @@ oz2_status ensure_workspace(size_t need_whole, size_t need_min, size_t *have) {
     size_t want = need_whole;
     if (g.ws_limit && want > g.ws_limit) want = g.ws_limit;
     if (want < need_min) return OZ2_WORKSPACE;
-    if (!g.ws || g.ws_bytes < want) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return OZ2_HIP_ERROR;
+    if (!g.ws || g.ws_bytes < want || g.ws_device != dev) {   // the buffer lives on the current device
         if (g.ws) {
             if (hipDeviceSynchronize() != hipSuccess) return OZ2_HIP_ERROR;
             (void)hipFree(g.ws);
@@ -128,7 +131,7 @@ oz2_status ensure_workspace(size_t need_whole, size_t need_min, size_t *have) {
         }
         void *p = nullptr;
         if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return OZ2_WORKSPACE; }
-        g.ws = static_cast<char *>(p); g.ws_bytes = want; g.ws_owned = true;
+        g.ws = static_cast<char *>(p); g.ws_bytes = want; g.ws_owned = true; g.ws_device = dev;
     }
     *have = g.ws_limit ? std::min(g.ws_bytes, std::max(g.ws_limit, need_min)) : g.ws_bytes;
     return OZ2_OK;
