@@ -167,6 +167,8 @@ SWEEPS = {
     # the parity-test configurations of the benchmark set, timed: (m, n, k, phi, fp64?, moduli)
     "dgemm_4096": [(4096, 4096, 4096, 0.5, True, list(range(12, 21)))],
     "dgemm_16384": [(16384, 16384, 16384, phi, True, [16, 17, 18, 19, 20]) for phi in (0.5, 1.0, 2.0)],
+    # the moduli counts at which the paper quotes its DGEMM-level results (Section 5.2)
+    "dgemm_16384_n14_15": [(16384, 16384, 16384, 0.5, True, [14, 15])],
     "sgemm": [(8192, 8192, 8192, 0.5, False, [5, 6, 7, 8, 9]),
               (16384, 16384, 16384, 0.5, False, [5, 6, 7, 8, 9])],
     "nonsquare": [(8192, 8192, 65536, 1.0, True, [18])],

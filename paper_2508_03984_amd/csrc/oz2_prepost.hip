@@ -332,29 +332,45 @@ __global__ __launch_bounds__(256) void k_epilogue(const void *__restrict__ prod_
     double C1[W], C2[W];
 #pragma unroll
     for (int c = 0; c < W; ++c) C1[c] = C2[c] = 0.0;
-#pragma unroll 8
-    for (int s = 0; s < ma.n; ++s) {
-        const double s1 = ma.s1[s], s2 = ma.s2[s];
-        int us[W];
-        if (IN_U8) {
-            const uint32_t x = *reinterpret_cast<const uint32_t *>(
-                static_cast<const uint8_t *>(prod_) + (int64_t)s * plane + at);
+    // Moduli s0 .. s0 + CNT - 1: all loads first (CNT of them in flight), then the FMAs in
+    // ascending order of s, which is the order the accumulation of C'(2) is defined in.
+    auto group = [&](int s0, auto cnt) {
+        constexpr int CNT = decltype(cnt)::value;
+        int us[CNT][W];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) us[c] = (int)((x >> (8 * c)) & 0xffu);
-        } else {
-            const int4 x = *reinterpret_cast<const int4 *>(
-                static_cast<const int32_t *>(prod_) + (int64_t)s * plane + at);
-            const int p = ma.p[s], pv = (int)ma.pinv_prime[s];
-            us[0] = mod_small(x.x, p, pv); us[1] = mod_small(x.y, p, pv);
-            us[2] = mod_small(x.z, p, pv); us[3] = mod_small(x.w, p, pv);
+        for (int g = 0; g < CNT; ++g) {
+            const int s = s0 + g;
+            if (IN_U8) {
+                const uint32_t x = *reinterpret_cast<const uint32_t *>(
+                    static_cast<const uint8_t *>(prod_) + (int64_t)s * plane + at);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) us[g][c] = (int)((x >> (8 * c)) & 0xffu);
+            } else {
+                const int4 x = *reinterpret_cast<const int4 *>(
+                    static_cast<const int32_t *>(prod_) + (int64_t)s * plane + at);
+                const int p = ma.p[s], pv = (int)ma.pinv_prime[s];
+                us[g][0] = mod_small(x.x, p, pv); us[g][1] = mod_small(x.y, p, pv);
+                us[g][2] = mod_small(x.z, p, pv); us[g][3] = mod_small(x.w, p, pv);
+            }
         }
 #pragma unroll
-        for (int c = 0; c < W; ++c) {
-            const double u = (double)us[c];
-            C1[c] = fma(s1, u, C1[c]);
-            C2[c] = fma(s2, u, C2[c]);
+        for (int g = 0; g < CNT; ++g) {
+            const double s1 = ma.s1[s0 + g], s2 = ma.s2[s0 + g];
+#pragma unroll
+            for (int c = 0; c < W; ++c) {
+                const double u = (double)us[g][c];
+                C1[c] = fma(s1, u, C1[c]);
+                C2[c] = fma(s2, u, C2[c]);
+            }
         }
-    }
+    };
+    // groups of 8, then 4, 2, 1: a count that is not a multiple of 8 costs at most three more
+    // rounds of load latency (a plain remainder loop cost 0.15 ms at 16384^2 for N = 14, 15)
+    int s = 0;
+    for (; s + 8 <= ma.n; s += 8) group(s, std::integral_constant<int, 8>{});
+    if (s + 4 <= ma.n) { group(s, std::integral_constant<int, 4>{}); s += 4; }
+    if (s + 2 <= ma.n) { group(s, std::integral_constant<int, 2>{}); s += 2; }
+    if (s < ma.n) group(s, std::integral_constant<int, 1>{});
     const int ta = tA[i];
     OutT *dst = C + i * ldc + j0;
     OutT res[W];
