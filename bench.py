@@ -472,6 +472,20 @@ def main() -> int:
     ]
     stage_gbs = [b / (t * 1e-3) / 1e9 if t > 0 else 0.0 for b, t in zip(stage_bytes, stage_ms)]
 
+    # what a plain device copy moves on this device (read + write), as the practical ceiling of
+    # the bandwidth-bound stages: dC <- dA, 2 GiB each way at the default size
+    copy_gbs = None
+    if dA.numel() == dC.numel():
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dC.copy_(dA)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            dC.copy_(dA)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 2.0 * dA.numel() * dA.element_size() / (e0.elapsed_time(e1) / 3 * 1e-3) / 1e9
+
     # native GEMM on the same buffers (rocBLAS / hipBLASLt through torch)
     torch.mm(dA, dB, out=dC)
     torch.cuda.synchronize()
@@ -580,7 +594,7 @@ def main() -> int:
                           "int8_gemm": float(stage_ms[2]), "epilogue": float(stage_ms[3])},
                    "hbm_GBps_algorithmic": {"shifts": stage_gbs[0], "residues": stage_gbs[1],
                                             "int8_gemm": stage_gbs[2], "epilogue": stage_gbs[3]},
-                   "hbm_peak_GBps": HBM_PEAK_GBS},
+                   "hbm_peak_GBps": HBM_PEAK_GBS, "device_copy_GBps_read_plus_write": copy_gbs},
         "native_gemm_tflops": native_tflops,
         "speedup_vs_native": tflops / native_tflops,
         "accuracy": accuracy,
