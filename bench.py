@@ -365,6 +365,43 @@ def sweep_small(oz, torch, args) -> int:
     return 0
 
 
+def sweep_accuracy(oz, torch, args) -> int:
+    """The setting of the paper's accuracy figure (Section 5.1): m = n = 1024, k = 1024 and 16384,
+    several phi, fast and accurate mode over the number of moduli, FP64 and FP32; the error
+    of each result and of the native GEMM against a double-double product on 16 sampled rows.
+    One JSON line per (type, k, phi) with the error per mode and N goes to --out."""
+    import numpy as np
+    import synth_inputs as S
+    from oracle import oz2_oracle as O              # reference leg only
+    path = args.out or "sweep_accuracy.jsonl"
+    if os.path.dirname(path):
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+    m = n = 1024
+    rows = np.arange(0, m, m // 16)
+    with open(path, "w") as f:
+        for is_double, moduli in ((True, list(range(8, 21))), (False, list(range(2, 13)))):
+            np_dt, t_dt = (np.float64, torch.float64) if is_double else (np.float32, torch.float32)
+            for k in (1024, 16384):
+                for phi in (0.5, 1.0, 1.5, 2.0, 4.0):
+                    A, B = S.gemm_inputs(m, n, k, phi, seed=0, dtype=np_dt)
+                    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+                    trows = torch.from_numpy(rows).cuda()
+                    hi, lo, ab = O.dd_rows(A.astype(np.float64), B.astype(np.float64), rows)
+                    err = lambda c: float(np.max(np.abs((c.astype(np.float64) - hi) - lo) / ab))
+                    rec = {"dtype": "f64" if is_double else "f32", "m": m, "n": n, "k": k, "phi": phi,
+                           "measure": "max |c - dd(AB)| / (|A||B|) on 16 rows",
+                           "native": err(torch.mm(dA, dB)[trows].cpu().numpy()), "fast": {}, "accurate": {}}
+                    for N in moduli:
+                        for accurate in (False, True):
+                            c = oz.matmul(dA, dB, N, accurate=accurate)
+                            rec["accurate" if accurate else "fast"][str(N)] = err(c[trows].cpu().numpy())
+                    log(json.dumps(rec))
+                    f.write(json.dumps(rec) + "\n")
+    print(json.dumps({"sweep": "accuracy", "file": path}), flush=True)
+    oz.oz2_release()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -385,7 +422,7 @@ def main() -> int:
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
                          "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
                          "counters); both print a reduced JSON line")
-    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general", "small"], default=None,
+    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general", "small", "accuracy"], default=None,
                     help="time a whole configuration of the benchmark set over its moduli counts; "
                          "one JSON line per case goes to --out")
     ap.add_argument("--out", default=None, help="file for --sweep (default: sweep_<name>.jsonl)")
@@ -416,6 +453,8 @@ def main() -> int:
         return sweep_general(oz, torch, args)
     if args.sweep == "small":
         return sweep_small(oz, torch, args)
+    if args.sweep == "accuracy":
+        return sweep_accuracy(oz, torch, args)
     if args.sweep:
         return sweep(oz, torch, args.sweep, args)
     if args.stage == "int8_gemm":
