@@ -327,8 +327,10 @@ template <int OUT>
 hipError_t launch_out(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp, int64_t Np,
                       int64_t Kp, int64_t k_begin, int64_t k_len, const GemmPanel &pn,
                       const GemmMods &mods, hipStream_t stream) {
-    // Small problems get the 128 x 128 tile so that more workgroups exist.
-    if (pn.rows * pn.cols * batch < (int64_t)256 * 256 * 512)
+    // Problems of fewer than 128 large tiles get the 128 x 128 tile so that more workgroups exist
+    // (measured at N = 14: 512^3, 56 large tiles, 11.4 against 17.3 us; 1024^3, 224 large tiles,
+    // 31.2 against 26.8 us, so from there on the large tile wins although it leaves units idle).
+    if (pn.rows * pn.cols * batch < (int64_t)256 * 256 * 128)
         return launch<2, 2, 2, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream);
     // 8 wavefronts (2 per SIMD), each 128 x 64: measured against 4 wavefronts of 128 x 128 on
     // the same device it is 2 % faster at 16 x 16384^3 -- a wavefront that is held up issuing
