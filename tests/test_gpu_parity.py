@@ -406,3 +406,13 @@ def test_config_sgemm_8192_sampled(oz, oracle):
 def test_config_nonsquare_k_65536_sampled(oz, oracle):
     sampled_parity(oz, oracle, 8192, 8192, 65536, 18, 1.0, np.float64, seed=0,
                    n_rows=2, n_entries=500)
+
+
+def test_large_and_skewed_shapes_sampled(oz, oracle):
+    """Shapes far from the benchmark's: 2^30 entries of C (index arithmetic beyond 32 bits),
+    a tall and a wide product, one in accurate mode, one in FP32."""
+    sampled_parity(oz, oracle, 32768, 32768, 2048, 16, 0.5, np.float64, seed=3, n_rows=2, n_entries=500)
+    sampled_parity(oz, oracle, 40000, 300, 4096, 15, 1.0, np.float64, seed=4, n_rows=2, n_entries=500,
+                   accurate=True)
+    sampled_parity(oz, oracle, 300, 50000, 1000, 8, 1.0, np.float32, seed=5, n_rows=2, n_entries=500)
+    oz.oz2_release()
