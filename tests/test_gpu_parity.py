@@ -416,3 +416,17 @@ def test_large_and_skewed_shapes_sampled(oz, oracle):
                    accurate=True)
     sampled_parity(oz, oracle, 300, 50000, 1000, 8, 1.0, np.float32, seed=5, n_rows=2, n_entries=500)
     oz.oz2_release()
+
+
+def test_short_contractions_use_the_persistent_gemm(oz, oracle):
+    """k <= 1024 with at least 128 large tiles runs the persistent form of the INT8 GEMM (every
+    workgroup walks over several tiles): full parity on a ragged shape in both product forms,
+    and the folding store phases (second K range of a k > 2^17 product, 428 deep) on samples."""
+    A, B = S.gemm_inputs(1100, 1500, 700, 1.0, seed=21)             # 5 x 6 tiles x 16 moduli
+    ref = oracle.gemm(A, B, 16)
+    assert_parity(gpu_gemm(oz, A, B, 16), ref, True)
+    assert_parity(gpu_gemm(oz, A, B, 16, int32_products=True), ref, True)
+    A32, B32 = S.gemm_inputs(3000, 2100, 1024, 0.5, seed=22, dtype=np.float32)   # 12 x 9 tiles x 8
+    assert_parity(gpu_gemm(oz, A32, B32, 8), oracle.gemm(A32, B32, 8, is_double=False), False)
+    sampled_parity(oz, oracle, 1536, 1536, 2 ** 17 + 300, 4, 0.5, np.float32, seed=23, n_rows=2, n_entries=300)
+    oz.oz2_release()
