@@ -430,3 +430,19 @@ def test_short_contractions_use_the_persistent_gemm(oz, oracle):
     assert_parity(gpu_gemm(oz, A32, B32, 8), oracle.gemm(A32, B32, 8, is_double=False), False)
     sampled_parity(oz, oracle, 1536, 1536, 2 ** 17 + 300, 4, 0.5, np.float32, seed=23, n_rows=2, n_entries=300)
     oz.oz2_release()
+
+
+def test_int8_gemm_persistent_form_direct(oz, oracle):
+    """oz2_int8_gemm on a shape that takes the persistent kernel (192 large tiles, K = 512, not a
+    multiple of 16 tiles: plain tile map), INT32 output, against the oracle on sampled rows."""
+    import torch
+    rng = np.random.default_rng(7)
+    batch, Mp, Np, Kp = 4, 1536, 2048, 512
+    A = rng.integers(-128, 128, (batch, Mp, Kp), dtype=np.int8)
+    B = rng.integers(-128, 128, (batch, Np, Kp), dtype=np.int8)
+    dC = torch.empty((batch, Mp, Np), dtype=torch.int32, device="cuda")
+    oz.oz2_int8_gemm(oz.block_slices(torch.from_numpy(A).cuda()),
+                     oz.block_slices(torch.from_numpy(B).cuda()), dC, batch, Mp, Np, Kp)
+    rows = np.array([0, 255, 256, 700, 1279, 1535])
+    ref = oracle.int8_gemm_rows(A, B, rows)
+    assert np.array_equal(dC[:, torch.from_numpy(rows).cuda(), :].cpu().numpy(), ref)
