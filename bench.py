@@ -492,15 +492,36 @@ def main() -> int:
     stage_ms /= args.steps
     ms_per_step = 1e3 * elapsed / args.steps
     tflops = 2.0 * m * n * k / (elapsed / args.steps) / 1e12
+    panel_rows, panel_cols, panels = oz.oz2_last_panels()
+    gemm_launches = panels * ((k + (1 << 17) - 1) >> 17)          # one per panel and K range of 2^17
     log(f"oz2 {'sgemm' if args.sgemm else 'dgemm'} N={N}: {ms_per_step:.2f} ms/step, "
         f"{tflops:.1f} emulated TFLOP/s; stages [shift, residues, gemm, epilogue] ms = "
-        f"{np.round(stage_ms, 3).tolist()}")
+        f"{np.round(stage_ms, 3).tolist()}; {panels} panel(s) of {panel_rows} x {panel_cols}")
+    # A call in panels overlaps the residues with the GEMMs on a second stream; its stage
+    # times are then [shifts, residues before the first GEMM, sum of the GEMM launches, rest].
+    # The time of each step on its own comes from a few calls with everything on one stream.
+    overlapped_stage_ms = None
+    if panels > 1:
+        overlapped_stage_ms = stage_ms.copy()
+        oz.oz2_set_overlap(False)
+        oz.oz2_set_profiling(True)
+        step()
+        single = np.zeros(4)
+        for _ in range(3):
+            step()
+            single += np.array(oz.oz2_last_stage_times_ms())
+        oz.oz2_set_profiling(False)
+        oz.oz2_set_overlap(True)
+        single /= 3
+        log(f"  on one stream: stages ms = {np.round(single, 3).tolist()} (sum {single.sum():.2f})")
 
     # dominant kernel: the batched INT8 GEMM on the padded slices
     pad = lambda x, to: (x + to - 1) // to * to
     Mp, Np, Kp = pad(m, 256), pad(n, 256), pad(k, 128)
     gemm_ops = 2.0 * Mp * Np * Kp * N
-    gemm_tops = gemm_ops / (stage_ms[2] * 1e-3) / 1e12
+    gemm_tops = gemm_ops / (stage_ms[2] * 1e-3) / 1e12            # stage_ms[2]: all GEMM launches of a step
+    if overlapped_stage_ms is not None:
+        stage_ms = single                                         # per-step figures below: one stream
     E = 4 if args.sgemm else 8
     PB = 4 if args.int32_products else 1                        # bytes per product entry
     stage_bytes = [
@@ -627,8 +648,17 @@ def main() -> int:
                      "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",
                      "frac": gemm_tops / INT8_PEAK_TOPS,
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(("f32" if args.sgemm else "f64", m, N)),
-                     "ops_per_launch": gemm_ops, "avg_launch_ms": float(stage_ms[2]),
+                     "ops_per_launch": gemm_ops / gemm_launches,
+                     "avg_launch_ms": float((overlapped_stage_ms if overlapped_stage_ms is not None
+                                             else stage_ms)[2] / gemm_launches),
+                     "launches_per_step": gemm_launches,
                      "note": "INT8 multiply-adds counted as 2 ops each, against the dense INT8 peak"},
+        "overlap": None if overlapped_stage_ms is None else {
+            "panels": panels, "panel": [panel_rows, panel_cols],
+            "ms": {"shifts": float(overlapped_stage_ms[0]), "residues_before_first_gemm": float(overlapped_stage_ms[1]),
+                   "int8_gemm_launches_sum": float(overlapped_stage_ms[2]), "rest": float(overlapped_stage_ms[3])},
+            "note": "the timed steps: residues of later panels run on a second stream beside the GEMMs; "
+                    "`stages` below is the same call with everything on one stream"},
         "stages": {"ms": {"shifts": float(stage_ms[0]), "residues": float(stage_ms[1]),
                           "int8_gemm": float(stage_ms[2]), "epilogue": float(stage_ms[3])},
                    "hbm_GBps_algorithmic": {"shifts": stage_gbs[0], "residues": stage_gbs[1],

@@ -269,10 +269,28 @@ oz2_status oz2_mfma_probe(int random_operands, double seconds, double *tops, int
                           int *clock_mhz);
 
 /*
+ * Overlap (on by default).  A product with a long contraction and a large C (k >= 8192, at
+ * least four panels of at most 4096 x 4096, k times the number of panels at least 9 x 8192) is
+ * computed panel by panel: the INT8 GEMMs and the accumulation
+ * of the panels run one after the other on `stream`, while a second stream owned by the
+ * library (default priority, created at the first such call, destroyed by oz2_release)
+ * computes the residues of the blocks of A and B that the coming panels need.  The second
+ * stream forks from `stream` after the shifts and has joined it again when the last panel
+ * starts, so for the caller the call is ordered on `stream` as always (it can also be captured
+ * into a graph once the second stream exists).  The result is bit-identical.  The product
+ * stages of oz2_stage_ptr are not available after such a call (shifts and residues are).
+ * oz2_set_overlap(0) computes everything on `stream`, one step after the other.
+ */
+void oz2_set_overlap(int on);
+
+/*
  * Per-stage timing.  With profiling on, each call records HIP events around its
  * stages on the call's stream; oz2_last_stage_times_ms waits for the last call
  * and writes { scale+exponent, residues, INT8 GEMM, epilogue } in milliseconds
- * to a HOST array.  Off by default (no events are recorded then).
+ * to a HOST array.  Off by default (no events are recorded then).  For an overlapped call
+ * (see oz2_set_overlap) the four numbers are: the shifts; the part of the residues that
+ * precedes the first GEMM; the sum of the GEMM launches of all panels (events on `stream`
+ * around each); the rest of the call (the accumulations, waits for residues).
  */
 void oz2_set_profiling(int on);
 oz2_status oz2_last_stage_times_ms(float *out4);

@@ -4,8 +4,10 @@
 
 #include <algorithm>
 #include <cstring>
+#include <cstdlib>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "../../include/oz2.h"
 #include "oz2_constants.hpp"
@@ -103,6 +105,12 @@ struct State {
     bool int32_products = false;           // diagnostic form: keep C'_s as int32
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     bool ev_recorded = false;
+    // overlapped form (run_overlapped): a second stream, ordering events, and with profiling
+    // one pair of timing events per panel around its INT8 GEMMs
+    bool overlap = true;
+    hipStream_t aux = nullptr;
+    std::vector<hipEvent_t> sync_ev, time_ev;
+    int64_t last_overlapped_panels = 0;    // > 0: the last call ran overlapped, with this many panels
 };
 State g;
 
@@ -164,6 +172,20 @@ hipError_t launch_any_residues(const T *X, int64_t ld, bool k_contiguous, int64_
                         : launch_residues_cols<T>(X, ld, k, rows, t, ma, out, rows_pad, Kp, stream);
 }
 
+// The same for the block of vectors [v0, v0 + block) of a factor with `rows` vectors
+// (block a multiple of 256): only that part of the slices is written.
+template <typename T>
+hipError_t launch_block_residues(const T *X, int64_t ld, bool k_contiguous, int64_t rows, int64_t k,
+                                 const int32_t *t, const ModArgs &ma, int8_t *out, int64_t rows_pad,
+                                 int64_t Kp, int64_t v0, int64_t block, hipStream_t stream) {
+    const int64_t valid = std::min(rows - v0, block);          // >= 1: v0 < rows
+    const T *Xb = X + (k_contiguous ? v0 * ld : v0);
+    return k_contiguous
+               ? launch_residues<T>(Xb, ld, valid, k, t + v0, ma, out + v0 * kBlockK, block, Kp, stream, rows_pad)
+               : launch_residues_cols<T>(Xb, ld, k, valid, t + v0, ma, out + v0 * kBlockK, block, Kp, stream,
+                                         rows_pad);
+}
+
 // Algorithm 1 lines 6-12 panel by panel: the INT8 GEMMs of one panel of C (Section 4.3: exact
 // INT32 accumulation for k <= 2^17; a longer contraction is cut into K ranges of at most 2^17
 // whose reduced results are folded together modulo p_s), then its accumulation and unscaling.
@@ -187,6 +209,90 @@ oz2_status run_products(const Layout &L, const Panels &P, const int8_t *rA, cons
                                        std::min(L.n - col0, cols), tA + row0, tB + col0, ma, alpha, beta,
                                        C + row0 * ldc + col0, ldc, stream));
         }
+    return mark(4, stream);
+}
+
+// Side of a panel of the overlapped form: the INT8 GEMM loses nothing down to 4096 x 4096.
+constexpr int64_t kOverlapPanel = 4096;
+
+oz2_status overlap_resources(size_t n_sync, size_t n_time) {
+    if (!g.aux) OZ2_TRY(hipStreamCreateWithFlags(&g.aux, hipStreamNonBlocking));   // default priority
+    while (g.sync_ev.size() < n_sync) {
+        hipEvent_t e = nullptr;
+        OZ2_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        g.sync_ev.push_back(e);
+    }
+    while (g.time_ev.size() < n_time) {
+        hipEvent_t e = nullptr;
+        OZ2_TRY(hipEventCreate(&e));
+        g.time_ev.push_back(e);
+    }
+    return OZ2_OK;
+}
+
+// Algorithm 1 lines 2-12 with the conversion to residues hidden behind the INT8 GEMMs.  The
+// shifts are known.  C is cut into panels; on the caller's stream the GEMMs and the accumulation
+// of one panel after the other; on a second stream, while they run, the residues of the row
+// block of A and the column block of B that the NEXT panel needs (each block once, the first
+// time a panel needs it).  Every dependency is an event; the second stream forks from the
+// caller's after the shifts and has nothing left to do when the last panel starts, so the call
+// as a whole is ordered on the caller's stream like any other (and can be captured into a
+// graph).  Measured at 16 x 16384^3 on one device: 61.2 ms against 62.2 ms on one stream; also
+// moving the accumulations to the second stream (two product buffers) was slower (61.7 ms: the
+// GEMMs lose more to the accumulations beside them than those take on their own), and so were
+// launches made "thin" for the registers a resident GEMM workgroup leaves free (64.6 ms).
+template <typename T>
+oz2_status run_overlapped(const Layout &L, const Panels &P, const T *A, int64_t lda, bool a_kc, const T *B,
+                          int64_t ldb, bool b_kc, const int32_t *tA, const int32_t *tB, int8_t *rA,
+                          int8_t *rB, void *prod, const ModArgs &ma, double alpha, double beta, T *C,
+                          int64_t ldc, hipStream_t stream) {
+    const int64_t nR = (L.Mp + P.pr - 1) / P.pr, nC = (L.Np + P.pc - 1) / P.pc, count = nR * nC;
+    // events: [0] fork, [1 .. nR] residues of the A blocks, then nC for the B blocks
+    const size_t eA = 1, eB = eA + (size_t)nR;
+    if (oz2_status st = overlap_resources(eB + (size_t)nC, g.profiling ? 2 * (size_t)count : 0)) return st;
+    hipEvent_t *ev = g.sync_ev.data();
+    hipStream_t aux = g.aux;
+    OZ2_TRY(hipEventRecord(ev[0], stream));
+    OZ2_TRY(hipStreamWaitEvent(aux, ev[0], 0));
+
+    auto residues_a = [&](int64_t i) -> hipError_t {
+        if (hipError_t e = launch_block_residues<T>(A, lda, a_kc, L.m, L.k, tA, ma, rA, L.Mp, L.Kp, i * P.pr,
+                                                    std::min(P.pr, L.Mp - i * P.pr), aux))
+            return e;
+        return hipEventRecord(ev[eA + i], aux);
+    };
+    auto residues_b = [&](int64_t j) -> hipError_t {
+        if (hipError_t e = launch_block_residues<T>(B, ldb, b_kc, L.n, L.k, tB, ma, rB, L.Np, L.Kp, j * P.pc,
+                                                    std::min(P.pc, L.Np - j * P.pc), aux))
+            return e;
+        return hipEventRecord(ev[eB + j], aux);
+    };
+    // The second stream's program: the blocks in the order in which the panels (row by row)
+    // first need them.  It runs ahead of the GEMMs as far as it can.
+    OZ2_TRY(residues_a(0));
+    for (int64_t j = 0; j < nC; ++j) OZ2_TRY(residues_b(j));
+    for (int64_t i = 1; i < nR; ++i) OZ2_TRY(residues_a(i));
+
+    for (int64_t p = 0; p < count; ++p) {
+        const int64_t i = p / nC, j = p % nC;
+        const int64_t row0 = i * P.pr, col0 = j * P.pc;
+        const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);
+        if (j == 0) OZ2_TRY(hipStreamWaitEvent(stream, ev[eA + i], 0));
+        if (i == 0) OZ2_TRY(hipStreamWaitEvent(stream, ev[eB + j], 0));
+        if (g.profiling) OZ2_TRY(hipEventRecord(g.time_ev[2 * p], stream));
+        const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
+        for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
+            const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
+            OZ2_TRY(launch_int8_gemm(rA, rB, prod, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0, &ma, stream,
+                                     &pn));
+        }
+        if (g.profiling) OZ2_TRY(hipEventRecord(g.time_ev[2 * p + 1], stream));
+        OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, rows, cols, std::min(L.m - row0, rows),
+                                   std::min(L.n - col0, cols), tA + row0, tB + col0, ma, alpha, beta,
+                                   C + row0 * ldc + col0, ldc, stream));
+    }
+    // The caller's stream has waited for every event of the second one: the two have joined.
+    g.last_overlapped_panels = count;
     return mark(4, stream);
 }
 
@@ -217,7 +323,18 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     Panels P{};
     if (oz2_status st = ensure_workspace(L.off_prod + L.prod_whole, L.off_prod + L.prod_min, &have)) return st;
     if (!plan_panels(L, have - L.off_prod, &P)) return OZ2_WORKSPACE;
-    g.last = L; g.last_panels = P; g.have_panels = true;
+    // Large products with a long contraction run overlapped (run_overlapped): panels of at most
+    // 4096 x 4096, at least four of them, k >= 8192 and k x panels >= 9 x 8192.  With less the
+    // conversion that precedes the first GEMM, or what the shorter GEMM launches lose, outweighs
+    // what is hidden (measured: 16 x 16384^3 -2.9 %, 8192 x 8192 x 65536 -3 %, but 8192^3 +1.5 %,
+    // 16384 x 16384 x 4096 +3 %).
+    Panels Po = P;
+    Po.pr = std::min(Po.pr, kOverlapPanel); Po.pc = std::min(Po.pc, kOverlapPanel);
+    Po.count = ((L.Mp + Po.pr - 1) / Po.pr) * ((L.Np + Po.pc - 1) / Po.pc);
+    const bool overlapped = g.overlap && Po.count >= 4 && Po.count <= 4096 && L.Kp >= 8192 &&
+                            L.Kp * Po.count >= (int64_t)9 * 8192;
+    if (overlapped) P = Po;
+    g.last = L; g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0;
     g.have_last = true; g.have_last_prod = P.count == 1; g.ev_recorded = false;
 
     void *scratch = g.ws + L.off_bt;
@@ -250,6 +367,13 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
         OZ2_TRY(launch_fast_shifts<T>(B, ldb, b_kc, n, k, sa, scratch, tB, stream));
     }
     if (oz2_status st = mark(1, stream)) return st;
+    if (overlapped) {
+        if (oz2_status st = run_overlapped<T>(L, P, A, lda, a_kc, B, ldb, b_kc, tA, tB, rA, rB, prod, ma, alpha,
+                                              beta, C, ldc, stream))
+            return st;
+        g.ev_recorded = g.profiling;
+        return OZ2_OK;
+    }
     OZ2_TRY(launch_any_residues<T>(A, lda, a_kc, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
     OZ2_TRY(launch_any_residues<T>(B, ldb, b_kc, n, k, tB, ma, rB, L.Np, L.Kp, stream));
     if (oz2_status st = mark(2, stream)) return st;
@@ -468,7 +592,11 @@ void oz2_release(void) {
     }
     g.ws = nullptr; g.ws_bytes = 0; g.ws_owned = false; g.have_last = g.have_last_prod = false;
     for (auto &e : g.ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
-    g.ev_recorded = false;
+    for (auto &e : g.sync_ev) (void)hipEventDestroy(e);
+    for (auto &e : g.time_ev) (void)hipEventDestroy(e);
+    g.sync_ev.clear(); g.time_ev.clear();
+    if (g.aux) { (void)hipStreamDestroy(g.aux); g.aux = nullptr; }
+    g.ev_recorded = false; g.last_overlapped_panels = 0;
 }
 
 oz2_status oz2_constants(int num_moduli, int is_double, int32_t *p, uint32_t *pinv_prime,
@@ -543,6 +671,11 @@ void oz2_set_int32_products(int on) {
     g.int32_products = on != 0;
 }
 
+void oz2_set_overlap(int on) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.overlap = on != 0;
+}
+
 void oz2_set_profiling(int on) {
     std::lock_guard<std::mutex> lock(g.mu);
     g.profiling = on != 0;
@@ -553,6 +686,22 @@ oz2_status oz2_last_stage_times_ms(float *out4) {
     std::lock_guard<std::mutex> lock(g.mu);
     if (!out4 || !g.ev_recorded) return OZ2_INVALID_ARG;
     OZ2_TRY(hipEventSynchronize(g.ev[4]));
+    if (g.last_overlapped_panels > 0) {
+        // overlapped call: shifts; what of the residues was exposed before the first GEMM; the
+        // sum of the panels' GEMM launches; the rest (gaps between them, the last accumulation)
+        float after_shifts = 0.f, gemm = 0.f;
+        OZ2_TRY(hipEventElapsedTime(&out4[0], g.ev[0], g.ev[1]));
+        OZ2_TRY(hipEventElapsedTime(&out4[1], g.ev[1], g.time_ev[0]));
+        OZ2_TRY(hipEventElapsedTime(&after_shifts, g.ev[1], g.ev[4]));
+        for (int64_t p = 0; p < g.last_overlapped_panels; ++p) {
+            float t = 0.f;
+            OZ2_TRY(hipEventElapsedTime(&t, g.time_ev[2 * p], g.time_ev[2 * p + 1]));
+            gemm += t;
+        }
+        out4[2] = gemm;
+        out4[3] = after_shifts - out4[1] - gemm;
+        return OZ2_OK;
+    }
     for (int i = 0; i < 4; ++i) OZ2_TRY(hipEventElapsedTime(&out4[i], g.ev[i], g.ev[i + 1]));
     return OZ2_OK;
 }

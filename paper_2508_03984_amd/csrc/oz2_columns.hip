@@ -9,6 +9,8 @@
 //       each thread reduces 8 consecutive k of one column modulo all N moduli, and the int8
 //       results go through LDS so that every modulus' 4 KiB piece of the K-blocked output
 //       [Kp/64][Np][64] is written as one contiguous run.
+#include <algorithm>
+
 #include "oz2_kernels.hpp"
 
 namespace oz2 {
@@ -100,11 +102,14 @@ __device__ inline int residue_of(double y, double p, double pinv) {
 
 // KIND as in the row kernel: 0 = residues for all moduli, 1 = the 7-bit magnitudes (slice 0).
 template <typename T, int ROUNDS, int KIND>
-__global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, int64_t ld,
-                                                       int64_t rows, int64_t cols,
-                                                       const int32_t *__restrict__ t, ModArgs ma,
-                                                       int8_t *__restrict__ out, int64_t cols_pad,
-                                                       int64_t rows_pad) {
+__device__ __forceinline__ void residues_cols_block(int64_t block_x, int64_t block_y,
+                                                    const T *__restrict__ X, int64_t ld, int64_t rows,
+                                                    int64_t cols, const int32_t *__restrict__ t,
+                                                    const ModArgs &ma, int8_t *__restrict__ out,
+                                                    int64_t cols_pad, int64_t rows_pad,
+                                                    int64_t cols_stride) {
+    // cols_pad columns are written (the grid covers them); cols_stride >= cols_pad is the number
+    // of rows of the whole transposed slice, of which this launch may fill a block.
     // LDS: per modulus 8 pieces x 64 columns x 8 bytes, piece-major so that the writes of a
     // wavefront (one piece, 64 columns) are contiguous; 8 bytes of padding per piece row.
     // Moduli are processed kGroup at a time to keep the LDS footprint (and so the number of
@@ -113,8 +118,8 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
     constexpr int kGroup = kModGroup;
     __shared__ uint2 stage[kGroup][8][65];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t c = (int64_t)blockIdx.x * kColStrip + lane;         // column of X = row of the output
-    const int64_t kb = blockIdx.y;                                    // K block
+    const int64_t c = block_x * kColStrip + lane;                     // column of X = row of the output
+    const int64_t kb = block_y;                                       // K block
     const int sh = c < cols ? t[c] : 0;
 
     double v[2][8];                                                   // pieces wave and wave + 4
@@ -130,9 +135,9 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
 
     // Write-out: per modulus the 64 columns x 64 bytes of this tile are contiguous in
     // out[s][kb][c0 .. c0+63][64]; thread -> (column, 16-byte quarter).
-    const int64_t plane = cols_pad * rows_pad;
+    const int64_t plane = cols_stride * rows_pad;
     const int col = threadIdx.x >> 2, quarter = threadIdx.x & 3;
-    int8_t *dst = out + (kb * cols_pad + (int64_t)blockIdx.x * kColStrip) * kBlockK + threadIdx.x * 16;
+    int8_t *dst = out + (kb * cols_stride + block_x * kColStrip) * kBlockK + threadIdx.x * 16;
 
     const int n_slices = KIND == 0 ? ma.n : 1;
     for (int s0 = 0; s0 < n_slices; s0 += kGroup) {
@@ -169,6 +174,16 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
     }
 }
 
+template <typename T, int ROUNDS, int KIND>
+__global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, int64_t ld,
+                                                       int64_t rows, int64_t cols,
+                                                       const int32_t *__restrict__ t, ModArgs ma,
+                                                       int8_t *__restrict__ out, int64_t cols_pad,
+                                                       int64_t rows_pad, int64_t cols_stride) {
+    residues_cols_block<T, ROUNDS, KIND>(blockIdx.x, blockIdx.y, X, ld, rows, cols, t, ma, out, cols_pad,
+                                         rows_pad, cols_stride);
+}
+
 }  // namespace
 
 size_t column_scratch_bytes(int64_t cols) { return (size_t)cols * 16; }
@@ -192,14 +207,15 @@ hipError_t launch_shifts_cols(const T *X, int64_t ld, int64_t rows, int64_t cols
 template <typename T>
 hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t cols, const int32_t *t,
                                 const ModArgs &ma, int8_t *out, int64_t cols_pad, int64_t rows_pad,
-                                hipStream_t stream) {
+                                hipStream_t stream, int64_t cols_stride) {
+    if (cols_stride == 0) cols_stride = cols_pad;
     dim3 grid((unsigned)(cols_pad / kColStrip), (unsigned)(rows_pad / kBlockK));
     if (ma.rounds == 1)
         hipLaunchKernelGGL((k_residues_cols<T, 1, 0>), grid, dim3(256), 0, stream, X, ld, rows, cols, t,
-                           ma, out, cols_pad, rows_pad);
+                           ma, out, cols_pad, rows_pad, cols_stride);
     else
         hipLaunchKernelGGL((k_residues_cols<T, 2, 0>), grid, dim3(256), 0, stream, X, ld, rows, cols, t,
-                           ma, out, cols_pad, rows_pad);
+                           ma, out, cols_pad, rows_pad, cols_stride);
     return hipGetLastError();
 }
 
@@ -210,7 +226,7 @@ hipError_t launch_magnitudes_cols(const T *X, int64_t ld, int64_t rows, int64_t 
     dim3 grid((unsigned)(cols_pad / kColStrip), (unsigned)(rows_pad / kBlockK));
     ModArgs none{};
     hipLaunchKernelGGL((k_residues_cols<T, 1, 1>), grid, dim3(256), 0, stream, X, ld, rows, cols, pre,
-                       none, out, cols_pad, rows_pad);
+                       none, out, cols_pad, rows_pad, cols_pad);
     return hipGetLastError();
 }
 
@@ -234,7 +250,7 @@ hipError_t launch_col_maxbits(const T *X, int64_t ld, int64_t rows, int64_t cols
                                               unsigned long long *, hipStream_t);                 \
     template hipError_t launch_residues_cols<T>(const T *, int64_t, int64_t, int64_t,             \
                                                 const int32_t *, const ModArgs &, int8_t *,       \
-                                                int64_t, int64_t, hipStream_t);
+                                                int64_t, int64_t, hipStream_t, int64_t);
 OZ2_INSTANTIATE_COLS(double)
 OZ2_INSTANTIATE_COLS(float)
 

@@ -67,11 +67,13 @@ hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, cons
 
 // Algorithm 1 lines 2-5: rmod(trunc(X[r][h] * 2^t[r]), p_s) as int8 for s < n,
 // r < rows_pad, h < len_pad, stored K-blocked: out[s][h / 64][r][h % 64]; entries with
-// r >= rows or h >= len are written as 0.
+// r >= rows or h >= len are written as 0.  rows_stride (0: rows_pad) is the number of rows of
+// the whole slice when the launch fills only a block of it: X, t and out then point at the
+// block's first row (out + first_row * 64), and rows / rows_pad describe the block.
 template <typename T>
 hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *t,
                            const ModArgs &ma, int8_t *out, int64_t rows_pad, int64_t len_pad,
-                           hipStream_t stream);
+                           hipStream_t stream, int64_t rows_stride = 0);
 
 // The same two stages for the COLUMNS of X (rows x cols, leading dimension ld), reading X in
 // place: one shift per column, and residue slices of X transposed, K-blocked:
@@ -84,7 +86,7 @@ hipError_t launch_shifts_cols(const T *X, int64_t ld, int64_t rows, int64_t cols
 template <typename T>
 hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t cols, const int32_t *t,
                                 const ModArgs &ma, int8_t *out, int64_t cols_pad, int64_t rows_pad,
-                                hipStream_t stream);
+                                hipStream_t stream, int64_t cols_stride = 0);   // stride: as in launch_residues
 
 // Accurate mode (Section 4.2, second half).  All vectors live in `scratch`
 // (accurate_scratch_bytes(m, n) bytes); the 7-bit matrices go to slice 0 of the residue

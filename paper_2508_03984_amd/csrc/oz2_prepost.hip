@@ -1,6 +1,7 @@
 // Bandwidth-bound kernels of the emulation for gfx950 (row side: A, and the output):
 // fast-mode shifts (Algorithm 1 line 1), residue slices (lines 2-5) and the fused
 // mod-reduce + CRT + unscale epilogue (lines 7-12).  64-wide wavefronts throughout.
+#include <algorithm>
 #include <type_traits>
 
 #include "oz2_kernels.hpp"
@@ -144,16 +145,18 @@ constexpr int kResPerThread = 8;     // consecutive elements per thread -> 8-byt
 // KIND 0: residues of trunc(x 2^t) for all moduli.  KIND 1 (accurate mode): the single
 // 7-bit magnitude matrix ceil(|x| 2^t), written as slice 0.
 template <typename T, int ROUNDS, int KIND>
-__global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64_t ld,
-                                                  int64_t rows, int64_t len,
-                                                  const int32_t *__restrict__ t, ModArgs ma,
-                                                  int8_t *__restrict__ out, int64_t rows_pad,
-                                                  int64_t len_pad) {
+__device__ __forceinline__ void residues_block(int64_t block, const T *__restrict__ X, int64_t ld,
+                                               int64_t rows, int64_t len,
+                                               const int32_t *__restrict__ t, const ModArgs &ma,
+                                               int8_t *__restrict__ out, int64_t rows_pad,
+                                               int64_t len_pad, int64_t rows_stride) {
+    // rows_pad rows are written (zeros beyond `rows`); rows_stride >= rows_pad is the number of
+    // rows of the whole slice, of which this launch may fill a block.
     // Thread -> (K block, row, 8-element piece of the 64-wide block), piece fastest: a
     // wavefront writes 8 rows x 64 B = 512 contiguous bytes of the blocked output and reads
     // 512 contiguous bytes of each of 8 input rows.
     constexpr int kPieces = kBlockK / kResPerThread;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = block * 256 + threadIdx.x;
     if (idx >= rows_pad * (len_pad / kResPerThread)) return;
     const int64_t kb = idx / (rows_pad * kPieces);
     const int64_t r = (idx / kPieces) % rows_pad;
@@ -186,8 +189,8 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
         for (int i = 0; i < kResPerThread; ++i) v[i] = 0.0;
     }
 
-    const int64_t plane = rows_pad * len_pad;
-    int8_t *o = out + (kb * rows_pad + r) * kBlockK + (h0 - kb * kBlockK);
+    const int64_t plane = rows_stride * len_pad;
+    int8_t *o = out + (kb * rows_stride + r) * kBlockK + (h0 - kb * kBlockK);
     if (KIND == 1) {
         uint32_t w[2] = {0u, 0u};
 #pragma unroll
@@ -212,6 +215,15 @@ __global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64
             *reinterpret_cast<uint2 *>(o + (int64_t)s * plane) = make_uint2(w[0], w[1]);
         }
     }
+}
+
+template <typename T, int ROUNDS, int KIND>
+__global__ __launch_bounds__(256) void k_residues(const T *__restrict__ X, int64_t ld,
+                                                  int64_t rows, int64_t len,
+                                                  const int32_t *__restrict__ t, ModArgs ma,
+                                                  int8_t *__restrict__ out, int64_t rows_pad,
+                                                  int64_t len_pad, int64_t rows_stride) {
+    residues_block<T, ROUNDS, KIND>(blockIdx.x, X, ld, rows, len, t, ma, out, rows_pad, len_pad, rows_stride);
 }
 
 // ----------------------------------------------------------------------------------------
@@ -312,18 +324,17 @@ __device__ inline OutT finish(double c, double alpha, double beta, const OutT *C
 // IN_U8: the GEMM already reduced its sums (prod holds U_s as uint8, 4 bytes per thread and
 // modulus); otherwise prod holds int32 sums (possibly folded partial sums) reduced here.
 template <typename OutT, bool IN_U8>
-__global__ __launch_bounds__(256) void k_epilogue(const void *__restrict__ prod_, int64_t Mp,
-                                                  int64_t Np, int64_t m, int64_t n,
-                                                  const int32_t *__restrict__ tA,
-                                                  const int32_t *__restrict__ tB, ModArgs ma,
-                                                  double alpha, double beta, OutT *C,
-                                                  int64_t ldc) {
+__device__ __forceinline__ void epilogue_block(int64_t block, const void *__restrict__ prod_, int64_t Mp,
+                                               int64_t Np, int64_t m, int64_t n,
+                                               const int32_t *__restrict__ tA,
+                                               const int32_t *__restrict__ tB, const ModArgs &ma,
+                                               double alpha, double beta, OutT *C, int64_t ldc) {
     // 4 consecutive columns per thread: one 4-byte (uint8 input) or 16-byte (int32 input) load
     // per modulus; 8 columns per thread measured slower (2.4 against 1.9 ms at 16384^2, N = 16).
     // Np is a multiple of 256.
     constexpr int W = 4;
     const int64_t groups = (n + W - 1) / W;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = block * 256 + threadIdx.x;
     if (idx >= m * groups) return;
     const int64_t i = idx / groups, j0 = (idx % groups) * W;
 
@@ -401,6 +412,16 @@ __global__ __launch_bounds__(256) void k_epilogue(const void *__restrict__ prod_
     }
 }
 
+template <typename OutT, bool IN_U8>
+__global__ __launch_bounds__(256) void k_epilogue(const void *__restrict__ prod_, int64_t Mp,
+                                                  int64_t Np, int64_t m, int64_t n,
+                                                  const int32_t *__restrict__ tA,
+                                                  const int32_t *__restrict__ tB, ModArgs ma,
+                                                  double alpha, double beta, OutT *C,
+                                                  int64_t ldc) {
+    epilogue_block<OutT, IN_U8>(blockIdx.x, prod_, Mp, Np, m, n, tA, tB, ma, alpha, beta, C, ldc);
+}
+
 template <typename OutT>
 __global__ __launch_bounds__(256) void k_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n,
                                                  double beta) {
@@ -437,14 +458,15 @@ hipError_t launch_shifts(const T *X, int64_t ld, int64_t rows, int64_t len, cons
 template <typename T>
 hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, const int32_t *t,
                            const ModArgs &ma, int8_t *out, int64_t rows_pad, int64_t len_pad,
-                           hipStream_t stream) {
+                           hipStream_t stream, int64_t rows_stride) {
+    if (rows_stride == 0) rows_stride = rows_pad;
     const int64_t threads = rows_pad * (len_pad / kResPerThread);
     if (ma.rounds == 1)
         hipLaunchKernelGGL((k_residues<T, 1, 0>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
-                           ld, rows, len, t, ma, out, rows_pad, len_pad);
+                           ld, rows, len, t, ma, out, rows_pad, len_pad, rows_stride);
     else
         hipLaunchKernelGGL((k_residues<T, 2, 0>), dim3(blocks_for(threads)), dim3(256), 0, stream, X,
-                           ld, rows, len, t, ma, out, rows_pad, len_pad);
+                           ld, rows, len, t, ma, out, rows_pad, len_pad, rows_stride);
     return hipGetLastError();
 }
 
@@ -454,7 +476,7 @@ hipError_t launch_magnitudes(const T *X, int64_t ld, int64_t rows, int64_t len, 
     const int64_t threads = rows_pad * (len_pad / kResPerThread);
     ModArgs none{};
     hipLaunchKernelGGL((k_residues<T, 1, 1>), dim3(blocks_for(threads)), dim3(256), 0, stream, X, ld,
-                       rows, len, pre, none, out, rows_pad, len_pad);
+                       rows, len, pre, none, out, rows_pad, len_pad, rows_pad);
     return hipGetLastError();
 }
 
@@ -488,7 +510,7 @@ hipError_t launch_scale_c(OutT *C, int64_t ldc, int64_t m, int64_t n, double bet
                                              hipStream_t);                                        \
     template hipError_t launch_residues<T>(const T *, int64_t, int64_t, int64_t, const int32_t *, \
                                            const ModArgs &, int8_t *, int64_t, int64_t,           \
-                                           hipStream_t);                                          \
+                                           hipStream_t, int64_t);                                 \
     template hipError_t launch_epilogue<T>(const void *, bool, int64_t, int64_t, int64_t,        \
                                            int64_t, const int32_t *, const int32_t *,             \
                                            const ModArgs &, double, double, T *, int64_t,         \

@@ -427,3 +427,116 @@ def test_random_shapes_modes_and_operand_forms_against_the_oracle(oz, oracle):
             if limited:
                 oz.oz2_set_workspace_limit(0)
                 oz.oz2_release()
+
+
+# ------------------------------------------------------------------ overlapped form
+@pytest.mark.parametrize("opA,opB,accurate", [(0, 0, False), (1, 1, False), (1, 0, True)])
+def test_overlapped_form_equals_the_single_stream_form(oz, oracle, opA, opB, accurate):
+    """k >= 8192 and a padded C of 8448 x 8704 (3 x 3 panels with ragged last ones): the default
+    form converts the blocks of A and B on a second stream while the GEMMs of earlier panels
+    run; it must equal the single-stream form bit for bit, call after call, and the oracle."""
+    import torch
+    from paper_2508_03984_amd import binding as b
+    m, n, k, N = 8300, 8500, 8200, 13
+    A, B = S.gemm_inputs(m, n, k, 1.0, seed=110)
+    Cin = S.matrix(m, n, 0.5, seed=111)
+    dA, lda = stored(A, opA, 1, torch.float64)
+    dB, ldb = stored(B, opB, 3, torch.float64)
+
+    def run():
+        dC = torch.from_numpy(Cin).cuda()
+        oz.oz2_dgemm_op(opA, opB, accurate, m, n, k, 0.5, dA, lda, dB, ldb, -1.25, dC, n, N)
+        return dC
+
+    oz.oz2_set_overlap(False)
+    try:
+        want = run()
+        assert oz.oz2_last_panels()[2] == 1
+    finally:
+        oz.oz2_set_overlap(True)
+    for rep in range(3):
+        got = run()
+        assert oz.oz2_last_panels() == (4096, 4096, 9)
+        assert torch.equal(got, want), rep
+    with pytest.raises(oz.OZ2Error):                       # the products of all of C are not kept
+        oz.oz2_stage_ptr(b.OZ2_STAGE_U)
+    prep = oracle.prepare(A, B, N, True, accurate)
+    assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
+    assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), prep["tB"])
+    ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A, copy=False))
+    rb = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_B, copy=False))
+    for s_ in range(N):                                    # residues written block by block, padding zero
+        assert torch.equal(ra[s_, :m, :k], torch.from_numpy(prep["Ares"][s_]).cuda())
+        assert torch.equal(rb[s_, :n, :k], torch.from_numpy(prep["Bres"][s_]).cuda())
+        assert bool((ra[s_, m:, :] == 0).all() and (ra[s_, :, k:] == 0).all())
+        assert bool((rb[s_, n:, :] == 0).all() and (rb[s_, :, k:] == 0).all())
+    del ra, rb
+    rows = np.array([0, 4095, 4096, 8191, 8192, m - 1])
+    fin = oracle.finish_rows(prep, rows, 0.5, -1.25, np.ascontiguousarray(Cin[rows]))
+    assert np.array_equal(want[torch.from_numpy(rows).cuda()].cpu().numpy(), fin["C"])
+    oz.oz2_release()
+
+
+def test_overlapped_form_with_k_ranges_fp32_and_a_workspace_limit(oz, oracle):
+    """Two K ranges per panel and FP32; a workspace limit cuts a C of 4352 x 4608 into nine
+    panels of 2048 x 2048, which makes the call an overlapped one."""
+    import torch
+    m, n, k, N = 4200, 4400, 2 ** 17 + 200, 5
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=112, dtype=np.float32)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    oz.oz2_set_overlap(False)
+    try:
+        want = oz.matmul(dA, dB, N)
+        assert oz.oz2_last_panels() == (4352, 4608, 1)
+    finally:
+        oz.oz2_set_overlap(True)
+    got = oz.matmul(dA, dB, N)                             # four panels, and k is long enough to overlap
+    assert oz.oz2_last_panels() == (4096, 4096, 4) and torch.equal(got, want)
+    least = oz.oz2_workspace_min_bytes(m, n, k, N, False)
+    try:
+        oz.oz2_set_workspace_limit(least - 5 * 256 * 256 + 5 * 2048 * 2048)
+        oz.oz2_release()
+        got = oz.matmul(dA, dB, N)
+        assert oz.oz2_last_panels() == (2048, 2048, 9) and torch.equal(got, want)
+        oz.oz2_set_overlap(False)
+        got = oz.matmul(dA, dB, N)
+        assert oz.oz2_last_panels() == (2048, 2048, 9) and torch.equal(got, want)
+    finally:
+        oz.oz2_set_overlap(True)
+        oz.oz2_set_workspace_limit(0)
+        oz.oz2_release()
+    rows = np.array([0, 4199])
+    ref = oracle.gemm(A[rows], B, N, is_double=False)["C"]
+    assert np.array_equal(want[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
+
+
+def test_overlapped_call_in_a_hip_graph(oz):
+    """The second stream forks from and joins the caller's stream, so the overlapped call can be
+    captured; replays with new inputs equal the eager results."""
+    import torch
+    m, n, k, N = 2100, 2300, 8192, 12
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=113)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.zeros((m, n), dtype=torch.float64, device="cuda")
+    least = oz.oz2_workspace_min_bytes(m, n, k, N)
+    try:
+        oz.oz2_set_workspace_limit(least - N * 256 * 256 + N * 512 * 512)
+        oz.oz2_release()
+        oz.matmul(dA, dB, N, out=dC)                       # workspace, second stream and events exist now
+        assert oz.oz2_last_panels() == (512, 512, 25)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            oz.matmul(dA, dB, N, out=dC)
+        for rep in range(3):
+            A2, B2 = S.gemm_inputs(m, n, k, 1.0, seed=114 + 2 * rep)
+            dA.copy_(torch.from_numpy(A2).cuda()); dB.copy_(torch.from_numpy(B2).cuda())
+            dC.fill_(float("nan"))
+            g.replay()
+            torch.cuda.synchronize()
+            got = dC.clone()
+            assert torch.equal(got, oz.matmul(dA, dB, N)), rep
+        del g
+    finally:
+        oz.oz2_set_workspace_limit(0)
+        oz.oz2_release()

@@ -347,12 +347,19 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
     is_double = dtype == np.float64
     A, B = S.gemm_inputs(m, n, k, phi, seed, dtype)
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    # the default (overlapped above 4096 x 4096) form first, then everything on one stream, which
+    # keeps the products of all of C for the checks below; the two must agree bit for bit
+    dC_default = oz.matmul(dA, dB, N, accurate=accurate)
     oz.oz2_set_int32_products(int32_products)
+    oz.oz2_set_overlap(False)
     try:
         dC = oz.matmul(dA, dB, N, accurate=accurate)
     finally:
         oz.oz2_set_int32_products(False)
+        oz.oz2_set_overlap(True)
     torch.cuda.synchronize()
+    assert torch.equal(dC_default, dC), "overlapped and single-stream results differ"
+    del dC_default
     prep = oracle.prepare(A, B, N, is_double, accurate)
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), prep["tB"])
