@@ -26,10 +26,11 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0          # MI355X dense INT8 MFMA, published
 HBM_PEAK_GBS = 8000.0
 
-# L2<->memory bytes per launch of k_int8_gemm from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script, scaled by what the counters read for `--stage copy` (x2.000 / x1.000); the
-# summary is profiles/oz2_dgemm_16384_N16_counters.txt.  Keyed by (dtype, m=n=k, N).
-MEASURED_GEMM_TRAFFIC_BYTES = {("f64", 16384, 16): 103.67e9 + 4.30e9}
+# L2<->memory bytes per launch of k_int8_gemm (a 4096 x 4096 panel of the 16 moduli: 16 launches
+# per call) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the
+# counters read for `--stage copy` (x2.000 / x1.000); the summary is
+# profiles/oz2_dgemm_16384_N16_counters.txt.  Keyed by (dtype, m=n=k, N).
+MEASURED_GEMM_TRAFFIC_BYTES = {("f64", 16384, 16): 6.44e9 + 0.27e9}
 
 
 def log(*a):
