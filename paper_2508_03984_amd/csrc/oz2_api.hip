@@ -445,7 +445,7 @@ oz2_status prepared_impl(const oz2_operand *l, const oz2_operand *r, double alph
     Panels P{};
     if (oz2_status st = ensure_workspace(L.prod_whole, L.prod_min, &have)) return st;
     if (!plan_panels(L, have, &P)) return OZ2_WORKSPACE;
-    g.last_panels = P; g.have_panels = true;
+    g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0;
     g.have_last = g.have_last_prod = false; g.ev_recorded = false;
     for (int i = 0; i < 3; ++i)
         if (oz2_status st = mark(i, stream)) return st;

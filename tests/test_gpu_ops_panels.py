@@ -540,3 +540,35 @@ def test_overlapped_call_in_a_hip_graph(oz):
     finally:
         oz.oz2_set_workspace_limit(0)
         oz.oz2_release()
+
+
+def test_stage_times_after_an_overlapped_and_then_a_prepared_call(oz):
+    """The stage times belong to the last call, whatever form the call before it had."""
+    import torch
+    m, n, k, N = 2100, 2300, 8192, 12
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=120)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.empty((m, n), dtype=torch.float64, device="cuda")
+    least = oz.oz2_workspace_min_bytes(m, n, k, N)
+    oz.oz2_set_profiling(True)
+    try:
+        oz.oz2_set_workspace_limit(least - N * 256 * 256 + N * 512 * 512)
+        oz.oz2_release()
+        oz.matmul(dA, dB, N, out=dC)                       # overlapped: 25 panels
+        assert oz.oz2_last_panels()[2] == 25
+        t = oz.oz2_last_stage_times_ms()
+        assert all(x >= 0.0 for x in t) and 0.0 < sum(t) < 1000.0, t
+        oz.oz2_set_workspace_limit(0)
+        L = oz.oz2_prepare_d(0, 0, m, k, dA, k, N)
+        R = oz.oz2_prepare_d(1, 0, n, k, dB, n, N)
+        oz.oz2_dgemm_prepared(L, R, 1.0, 0.0, dC, n)
+        t = oz.oz2_last_stage_times_ms()
+        assert all(x >= 0.0 for x in t) and 0.0 < sum(t) < 1000.0, t
+        oz.matmul(dA[:300], dB, N)                         # a small plain call
+        t = oz.oz2_last_stage_times_ms()
+        assert all(x >= 0.0 for x in t) and 0.0 < sum(t) < 1000.0, t
+        L.free(); R.free()
+    finally:
+        oz.oz2_set_profiling(False)
+        oz.oz2_set_workspace_limit(0)
+        oz.oz2_release()
