@@ -161,7 +161,11 @@ oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right,
  * replaced; 256-byte aligned); with (NULL, 0) the library goes back to
  * allocating its own buffer with hipMalloc (on the device that is current at the
  * call; a call made with another device current allocates anew there), growing it on
- * demand and keeping it until oz2_release.
+ * demand and keeping it until oz2_release.  The library's own buffer is sized for
+ * oz2_workspace_bytes, except for calls that take the overlapped form described under
+ * oz2_set_overlap: those work through C in panels of at most 4096 x 4096 anyway, so their
+ * buffer holds the products of one such panel beside the residues (at m = n = k = 16384 and
+ * 16 moduli 8.9 GB instead of 12.9 GB).
  *
  * Bounded workspace ("block matrix multiplication" over the rows and columns of C): the
  * products U_s are the largest part (num_moduli * m * n bytes).  When the workspace may

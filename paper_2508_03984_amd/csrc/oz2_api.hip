@@ -319,20 +319,28 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     const ModArgs ma = make_mod_args(tab);
     const ShiftArgs sa = make_shift_args(tab);
     const Layout L = make_layout(m, n, k, N, !g.int32_products);
-    size_t have = 0;
-    Panels P{};
-    if (oz2_status st = ensure_workspace(L.off_prod + L.prod_whole, L.off_prod + L.prod_min, &have)) return st;
-    if (!plan_panels(L, have - L.off_prod, &P)) return OZ2_WORKSPACE;
     // Large products with a long contraction run overlapped (run_overlapped): panels of at most
     // 4096 x 4096, at least four of them, k >= 8192 and k x panels >= 9 x 8192.  With less the
     // conversion that precedes the first GEMM, or what the shorter GEMM launches lose, outweighs
     // what is hidden (measured: 16 x 16384^3 -2.9 %, 8192 x 8192 x 65536 -3 %, but 8192^3 +1.5 %,
-    // 16384 x 16384 x 4096 +3 %).
+    // 16384 x 16384 x 4096 +3 %).  Such a call needs the products of one panel only, so the
+    // library's own workspace is sized for that.
+    const int64_t side_r = std::min(L.Mp, kOverlapPanel), side_c = std::min(L.Np, kOverlapPanel);
+    const int64_t panels_4096 = ((L.Mp + side_r - 1) / side_r) * ((L.Np + side_c - 1) / side_c);
+    auto overlap_pays = [&](int64_t panels) {
+        return g.overlap && panels >= 4 && panels <= 4096 && L.Kp >= 8192 && L.Kp * panels >= (int64_t)9 * 8192;
+    };
+    const size_t prod_want = overlap_pays(panels_4096)
+                                 ? align256((size_t)side_r * side_c * bytes_per_entry(N, L.prod_u8))
+                                 : L.prod_whole;
+    size_t have = 0;
+    Panels P{};
+    if (oz2_status st = ensure_workspace(L.off_prod + prod_want, L.off_prod + L.prod_min, &have)) return st;
+    if (!plan_panels(L, have - L.off_prod, &P)) return OZ2_WORKSPACE;
     Panels Po = P;
     Po.pr = std::min(Po.pr, kOverlapPanel); Po.pc = std::min(Po.pc, kOverlapPanel);
     Po.count = ((L.Mp + Po.pr - 1) / Po.pr) * ((L.Np + Po.pc - 1) / Po.pc);
-    const bool overlapped = g.overlap && Po.count >= 4 && Po.count <= 4096 && L.Kp >= 8192 &&
-                            L.Kp * Po.count >= (int64_t)9 * 8192;
+    const bool overlapped = overlap_pays(Po.count);        // a workspace limit may have made the panels smaller
     if (overlapped) P = Po;
     g.last = L; g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0;
     g.have_last = true; g.have_last_prod = P.count == 1; g.ev_recorded = false;
