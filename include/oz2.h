@@ -288,6 +288,16 @@ oz2_status oz2_mfma_probe(int random_operands, double seconds, double *tops, int
 void oz2_set_overlap(int on);
 
 /*
+ * Small problems (on by default).  Below about 2048^3 a call is bound by the latency of its
+ * dependent kernel launches.  For fast-mode calls with k <= 4096, m, n <= 8192 and
+ * (m + n) * k <= 2 * 2048^2 the conversion of Algorithm 1 lines 1-5 therefore runs as two
+ * launches that cover both factors (the shifts; the residues) instead of seven.  The result
+ * and every stage are bit-identical.  oz2_set_small_conversion(0) uses the general kernels
+ * at every size.
+ */
+void oz2_set_small_conversion(int on);
+
+/*
  * Per-stage timing.  With profiling on, each call records HIP events around its
  * stages on the call's stream; oz2_last_stage_times_ms waits for the last call
  * and writes { scale+exponent, residues, INT8 GEMM, epilogue } in milliseconds

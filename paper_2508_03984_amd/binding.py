@@ -23,6 +23,7 @@ EXPORTS = [
     "oz2_dgemm_op", "oz2_sgemm_op", "oz2_prepare_d", "oz2_prepare_s", "oz2_operand_free",
     "oz2_operand_bytes", "oz2_dgemm_prepared", "oz2_sgemm_prepared", "oz2_workspace_min_bytes",
     "oz2_set_workspace_limit", "oz2_last_panels", "oz2_plan_panels", "oz2_set_overlap",
+    "oz2_set_small_conversion",
 ]
 
 OZ2_OP_N, OZ2_OP_T = 0, 1
@@ -92,6 +93,8 @@ def load():
     lib.oz2_set_int32_products.restype = None
     lib.oz2_set_overlap.argtypes = [ci]
     lib.oz2_set_overlap.restype = None
+    lib.oz2_set_small_conversion.argtypes = [ci]
+    lib.oz2_set_small_conversion.restype = None
     lib.oz2_last_stage_times_ms.argtypes = [C.POINTER(flt)]
     lib.oz2_status_string.argtypes = [ci]
     lib.oz2_status_string.restype = C.c_char_p
@@ -337,6 +340,10 @@ def oz2_set_int32_products(on: bool) -> None:
 
 def oz2_set_overlap(on: bool) -> None:
     load().oz2_set_overlap(int(bool(on)))
+
+
+def oz2_set_small_conversion(on: bool) -> None:
+    load().oz2_set_small_conversion(int(bool(on)))
 
 
 def oz2_set_profiling(on: bool) -> None:

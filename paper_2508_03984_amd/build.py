@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liboz2.so")
-SOURCES = ["oz2_api.hip", "oz2_prepost.hip", "oz2_columns.hip", "oz2_accurate.hip", "oz2_int8_gemm.hip",
+SOURCES = ["oz2_api.hip", "oz2_prepost.hip", "oz2_columns.hip", "oz2_small.hip", "oz2_accurate.hip", "oz2_int8_gemm.hip",
            "oz2_probe.hip", "oz2_constants.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -108,6 +108,7 @@ struct State {
     // overlapped form (run_overlapped): a second stream, ordering events, and with profiling
     // one pair of timing events per panel around its INT8 GEMMs
     bool overlap = true;
+    bool small_conversion = true;   // fused conversion launches for small problems (oz2_small.hip)
     hipStream_t aux = nullptr;
     std::vector<hipEvent_t> sync_ev, time_ev;
     int64_t last_overlapped_panels = 0;    // > 0: the last call ran overlapped, with this many panels
@@ -352,6 +353,8 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     int8_t *rB = reinterpret_cast<int8_t *>(g.ws + L.off_rb);
     void *prod = g.ws + L.off_prod;
 
+    // Small problems in fast mode: the conversion of both factors in two launches instead of seven.
+    const bool small = g.small_conversion && !accurate && small_conversion_applies(m, n, k);
     if (oz2_status st = mark(0, stream)) return st;
     if (accurate) {
         // Section 4.2, accurate mode: 7-bit matrices into slice 0, Cbar panel by panel into the
@@ -370,6 +373,8 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
                                                n, scratch, stream));
             }
         OZ2_TRY(launch_accurate_finish(m, n, make_accu_shift_args(tab), scratch, tA, tB, stream));
+    } else if (small) {
+        OZ2_TRY(launch_small_shifts<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, sa, tA, tB, stream));
     } else {
         OZ2_TRY(launch_fast_shifts<T>(A, lda, a_kc, m, k, sa, scratch, tA, stream));
         OZ2_TRY(launch_fast_shifts<T>(B, ldb, b_kc, n, k, sa, scratch, tB, stream));
@@ -382,8 +387,13 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
         g.ev_recorded = g.profiling;
         return OZ2_OK;
     }
-    OZ2_TRY(launch_any_residues<T>(A, lda, a_kc, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
-    OZ2_TRY(launch_any_residues<T>(B, ldb, b_kc, n, k, tB, ma, rB, L.Np, L.Kp, stream));
+    if (small) {
+        OZ2_TRY(launch_small_residues<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, ma, tA, tB, rA, rB, L.Mp, L.Np,
+                                         L.Kp, stream));
+    } else {
+        OZ2_TRY(launch_any_residues<T>(A, lda, a_kc, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
+        OZ2_TRY(launch_any_residues<T>(B, ldb, b_kc, n, k, tB, ma, rB, L.Np, L.Kp, stream));
+    }
     if (oz2_status st = mark(2, stream)) return st;
     if (oz2_status st = run_products<T>(L, P, rA, rB, tA, tB, prod, ma, alpha, beta, C, ldc, stream)) return st;
     g.ev_recorded = g.profiling;
@@ -682,6 +692,11 @@ void oz2_set_int32_products(int on) {
 void oz2_set_overlap(int on) {
     std::lock_guard<std::mutex> lock(g.mu);
     g.overlap = on != 0;
+}
+
+void oz2_set_small_conversion(int on) {
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.small_conversion = on != 0;
 }
 
 void oz2_set_profiling(int on) {

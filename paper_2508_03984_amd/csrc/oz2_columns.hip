@@ -11,12 +11,14 @@
 //       [Kp/64][Np][64] is written as one contiguous run.
 #include <algorithm>
 
+#include "oz2_convert.hpp"
 #include "oz2_kernels.hpp"
 
 namespace oz2 {
 namespace {
 
-constexpr int kColStrip = 64;        // columns per workgroup (one per lane)
+using namespace dev;
+
 constexpr int kRowChunk = 512;       // rows per workgroup in the shift kernels
 
 __global__ __launch_bounds__(256) void k_fill_u64(uint64_t *p, int64_t count, uint64_t v) {
@@ -90,88 +92,6 @@ __global__ __launch_bounds__(256) void k_col_finish(const unsigned long long *__
     int j = 0;
     while (j < sa.levels - 1 && T_ > sa.theta[j]) ++j;
     t[c] = (sa.f_max - j) - floor_log2_of_bits(mx);
-}
-
-// Same reduction as in the row kernel (see oz2_prepost.hip for why it is exact).
-__device__ inline double group_reduce(double x, double M, double Minv) {
-    return fma(-rint(x * Minv), M, x);
-}
-__device__ inline int residue_of(double y, double p, double pinv) {
-    return (int)fma(-rint(y * pinv), p, y);
-}
-
-// KIND as in the row kernel: 0 = residues for all moduli, 1 = the 7-bit magnitudes (slice 0).
-template <typename T, int ROUNDS, int KIND>
-__device__ __forceinline__ void residues_cols_block(int64_t block_x, int64_t block_y,
-                                                    const T *__restrict__ X, int64_t ld, int64_t rows,
-                                                    int64_t cols, const int32_t *__restrict__ t,
-                                                    const ModArgs &ma, int8_t *__restrict__ out,
-                                                    int64_t cols_pad, int64_t rows_pad,
-                                                    int64_t cols_stride) {
-    // cols_pad columns are written (the grid covers them); cols_stride >= cols_pad is the number
-    // of rows of the whole transposed slice, of which this launch may fill a block.
-    // LDS: per modulus 8 pieces x 64 columns x 8 bytes, piece-major so that the writes of a
-    // wavefront (one piece, 64 columns) are contiguous; 8 bytes of padding per piece row.
-    // Moduli are processed kGroup at a time to keep the LDS footprint (and so the number of
-    // resident workgroups) independent of N; a group is also what shares the first reduction
-    // round when two are needed.
-    constexpr int kGroup = kModGroup;
-    __shared__ uint2 stage[kGroup][8][65];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t c = block_x * kColStrip + lane;                     // column of X = row of the output
-    const int64_t kb = block_y;                                       // K block
-    const int sh = c < cols ? t[c] : 0;
-
-    double v[2][8];                                                   // pieces wave and wave + 4
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int64_t h0 = kb * kBlockK + (wave + 4 * half) * 8;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            v[half][i] = !(c < cols && h0 + i < rows) ? 0.0
-                         : KIND == 0 ? trunc(ldexp((double)X[(h0 + i) * ld + c], sh))
-                                     : ceil(ldexp(fabs((double)X[(h0 + i) * ld + c]), sh));
-    }
-
-    // Write-out: per modulus the 64 columns x 64 bytes of this tile are contiguous in
-    // out[s][kb][c0 .. c0+63][64]; thread -> (column, 16-byte quarter).
-    const int64_t plane = cols_stride * rows_pad;
-    const int col = threadIdx.x >> 2, quarter = threadIdx.x & 3;
-    int8_t *dst = out + (kb * cols_stride + block_x * kColStrip) * kBlockK + threadIdx.x * 16;
-
-    const int n_slices = KIND == 0 ? ma.n : 1;
-    for (int s0 = 0; s0 < n_slices; s0 += kGroup) {
-        const int ns = n_slices - s0 < kGroup ? n_slices - s0 : kGroup;
-        double y[2][8];
-#pragma unroll
-        for (int half = 0; half < 2; ++half)
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                y[half][i] = (KIND == 0 && ROUNDS == 2)
-                                 ? group_reduce(v[half][i], ma.group_mod[s0 / kGroup], ma.group_inv[s0 / kGroup])
-                                 : v[half][i];
-        for (int g = 0; g < ns; ++g) {
-            const double p = (double)ma.p[s0 + g], pinv = ma.pinv[s0 + g];
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                uint32_t w[2] = {0u, 0u};
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    uint32_t b = (KIND == 0 ? (uint32_t)residue_of(y[half][i], p, pinv)
-                                            : (uint32_t)(int)y[half][i]) & 0xffu;
-                    w[i >> 2] |= b << (8 * (i & 3));
-                }
-                stage[g][wave + 4 * half][lane] = make_uint2(w[0], w[1]);
-            }
-        }
-        __syncthreads();
-        for (int g = 0; g < ns; ++g) {
-            const uint2 lo = stage[g][2 * quarter][col];
-            const uint2 hi = stage[g][2 * quarter + 1][col];
-            *reinterpret_cast<uint4 *>(dst + (int64_t)(s0 + g) * plane) = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        }
-        __syncthreads();
-    }
 }
 
 template <typename T, int ROUNDS, int KIND>

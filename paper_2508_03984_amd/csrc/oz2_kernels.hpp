@@ -88,6 +88,22 @@ hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t co
                                 const ModArgs &ma, int8_t *out, int64_t cols_pad, int64_t rows_pad,
                                 hipStream_t stream, int64_t cols_stride = 0);   // stride: as in launch_residues
 
+// Algorithm 1 lines 1-5 (fast mode) for SMALL problems, where the number of dependent launches
+// sets the time: one launch for the shifts of both factors and one for their residues, with the
+// results of the launchers above.  A is the left factor (m vectors of k elements: its rows when
+// a_k_contiguous, else its columns), B the right one (n vectors); slices as in launch_residues.
+// small_conversion_applies says for which shapes these launchers may be used.
+bool small_conversion_applies(int64_t m, int64_t n, int64_t k);
+template <typename T>
+hipError_t launch_small_shifts(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                               bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const ShiftArgs &sa,
+                               int32_t *tA, int32_t *tB, hipStream_t stream);
+template <typename T>
+hipError_t launch_small_residues(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                                 bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const ModArgs &ma,
+                                 const int32_t *tA, const int32_t *tB, int8_t *rA, int8_t *rB, int64_t Mp,
+                                 int64_t Np, int64_t Kp, hipStream_t stream);
+
 // Accurate mode (Section 4.2, second half).  All vectors live in `scratch`
 // (accurate_scratch_bytes(m, n) bytes); the 7-bit matrices go to slice 0 of the residue
 // buffers (same K-blocked layout) and Cbar to plane 0 of the product buffer:

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <type_traits>
 
+#include "oz2_convert.hpp"
 #include "oz2_kernels.hpp"
 
 namespace oz2 {
@@ -48,7 +49,7 @@ ShiftArgs make_accu_shift_args(const Table &t) {
 
 namespace {
 
-constexpr int kWave = 64;
+using namespace dev;
 
 // ----------------------------------------------------------------------------------------
 // Shifts.  One workgroup per row: pass 1 finds max|x| (as an integer compare of the FP64
@@ -57,18 +58,6 @@ constexpr int kWave = 64;
 // t = f - e.  k_shifts re-reads the row for pass 2 (rows of any length); k_shifts_cached
 // further down keeps rows of up to 16384 elements in registers between the passes.
 // ----------------------------------------------------------------------------------------
-__device__ inline uint64_t wave_max(uint64_t v) {
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        uint64_t o = __shfl_xor(v, off, kWave);
-        v = o > v ? o : v;
-    }
-    return v;
-}
-__device__ inline uint64_t wave_sum(uint64_t v) {
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void k_shifts(const T *__restrict__ X, int64_t ld, int64_t len,
                                                 ShiftArgs sa, int32_t *__restrict__ t) {
@@ -113,107 +102,6 @@ __global__ __launch_bounds__(256) void k_shifts(const T *__restrict__ X, int64_t
         int j = 0;
         while (j < sa.levels - 1 && T_ > sa.theta[j]) ++j;
         t[blockIdx.x] = (sa.f_max - j) - e;
-    }
-}
-
-// ----------------------------------------------------------------------------------------
-// Residues.  x' = trunc(x 2^t) is an integer-valued FP64 number below 2^77.  Its
-// symmetric residue modulo p comes from rounds of  y <- fma(-rint(y * (1/p)), p, y),
-// the reduction of Section 4.2 kept in FP64 throughout (FP64 and FP32 FMA run at the
-// same rate on this chip, so there is nothing to gain from dropping to FP32):
-//   round 1 is exact (the difference is an integer below 2^26 in magnitude) and leaves
-//   |y| <= p/2 + 2^-52 |x'|;  for |x'| < 2^46 the quotient estimate is within 2^-13 of
-//   x'/p, closer than any integer/p can be to a half-integer for odd p, so rint returns
-//   round(x'/p) and y is already the residue in [-(p-1)/2, (p-1)/2];
-//   otherwise two rounds.  The first one is shared by up to five moduli: it reduces
-//   modulo their product M < 2^40 (group_reduce), which is exact for the same reason (the
-//   difference is an integer, |y| <= M/2 + 2^-51 |x'| < 2^45) and y = x' (mod M) implies
-//   y = x' (mod p) for every p that divides M; the second round, on |y| < 2^46, is the
-//   one-round case above for each of these p.
-// p = 256: 1/p is exact, y lands in [-128, 128] and the int8 cast wraps 128 to -128,
-// which is the same class (Section 4.1).
-// ----------------------------------------------------------------------------------------
-__device__ inline double group_reduce(double x, double M, double Minv) {
-    return fma(-rint(x * Minv), M, x);
-}
-__device__ inline int residue_of(double y, double p, double pinv) {
-    return (int)fma(-rint(y * pinv), p, y);
-}
-
-constexpr int kResPerThread = 8;     // consecutive elements per thread -> 8-byte stores
-
-// KIND 0: residues of trunc(x 2^t) for all moduli.  KIND 1 (accurate mode): the single
-// 7-bit magnitude matrix ceil(|x| 2^t), written as slice 0.
-template <typename T, int ROUNDS, int KIND>
-__device__ __forceinline__ void residues_block(int64_t block, const T *__restrict__ X, int64_t ld,
-                                               int64_t rows, int64_t len,
-                                               const int32_t *__restrict__ t, const ModArgs &ma,
-                                               int8_t *__restrict__ out, int64_t rows_pad,
-                                               int64_t len_pad, int64_t rows_stride) {
-    // rows_pad rows are written (zeros beyond `rows`); rows_stride >= rows_pad is the number of
-    // rows of the whole slice, of which this launch may fill a block.
-    // Thread -> (K block, row, 8-element piece of the 64-wide block), piece fastest: a
-    // wavefront writes 8 rows x 64 B = 512 contiguous bytes of the blocked output and reads
-    // 512 contiguous bytes of each of 8 input rows.
-    constexpr int kPieces = kBlockK / kResPerThread;
-    const int64_t idx = block * 256 + threadIdx.x;
-    if (idx >= rows_pad * (len_pad / kResPerThread)) return;
-    const int64_t kb = idx / (rows_pad * kPieces);
-    const int64_t r = (idx / kPieces) % rows_pad;
-    const int64_t h0 = kb * kBlockK + (idx % kPieces) * kResPerThread;
-
-    double v[kResPerThread];
-    if (r < rows) {
-        const int sh = t[r];
-        const T *x = X + r * ld + h0;
-        T raw[kResPerThread];
-        if (h0 + kResPerThread <= len && (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
-            // whole piece in range and 16-byte aligned: 16-byte loads (1.9 -> 1.3 ms at 16384^2)
-            constexpr int kVec = 16 / sizeof(T);
-            typedef T vec_t __attribute__((ext_vector_type(kVec)));
-#pragma unroll
-            for (int i = 0; i < kResPerThread / kVec; ++i) {
-                const vec_t q = reinterpret_cast<const vec_t *>(x)[i];
-#pragma unroll
-                for (int c = 0; c < kVec; ++c) raw[i * kVec + c] = q[c];
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < kResPerThread; ++i) raw[i] = (h0 + i < len) ? x[i] : T(0);
-        }
-#pragma unroll
-        for (int i = 0; i < kResPerThread; ++i)
-            v[i] = KIND == 0 ? trunc(ldexp((double)raw[i], sh)) : ceil(ldexp(fabs((double)raw[i]), sh));
-    } else {
-#pragma unroll
-        for (int i = 0; i < kResPerThread; ++i) v[i] = 0.0;
-    }
-
-    const int64_t plane = rows_stride * len_pad;
-    int8_t *o = out + (kb * rows_stride + r) * kBlockK + (h0 - kb * kBlockK);
-    if (KIND == 1) {
-        uint32_t w[2] = {0u, 0u};
-#pragma unroll
-        for (int i = 0; i < kResPerThread; ++i) w[i >> 2] |= ((uint32_t)(int)v[i] & 0xffu) << (8 * (i & 3));
-        *reinterpret_cast<uint2 *>(o) = make_uint2(w[0], w[1]);
-        return;
-    }
-    for (int s0 = 0; s0 < ma.n; s0 += kModGroup) {
-        double y[kResPerThread];
-#pragma unroll
-        for (int i = 0; i < kResPerThread; ++i)
-            y[i] = ROUNDS == 2 ? group_reduce(v[i], ma.group_mod[s0 / kModGroup], ma.group_inv[s0 / kModGroup]) : v[i];
-        const int s1 = s0 + kModGroup < ma.n ? s0 + kModGroup : ma.n;
-        for (int s = s0; s < s1; ++s) {
-            const double p = (double)ma.p[s], pinv = ma.pinv[s];
-            uint32_t w[2] = {0u, 0u};
-#pragma unroll
-            for (int i = 0; i < kResPerThread; ++i) {
-                uint32_t b = (uint32_t)residue_of(y[i], p, pinv) & 0xffu;
-                w[i >> 2] |= b << (8 * (i & 3));
-            }
-            *reinterpret_cast<uint2 *>(o + (int64_t)s * plane) = make_uint2(w[0], w[1]);
-        }
     }
 }
 

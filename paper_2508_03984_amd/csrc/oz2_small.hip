@@ -1,0 +1,223 @@
+// Conversion kernels for SMALL problems (Algorithm 1 lines 1-5, fast mode of Section 4.2).
+// Below about 2048^3 a call is bound by the latency of its dependent kernel launches, not by
+// memory or arithmetic: the general path takes seven launches for the conversion (row shifts;
+// clear, column maxima, column sums, column finish; residues of A; residues of B).  Here it
+// takes two, each covering both factors:
+//   k_small_shifts    every workgroup owns whole vectors (one row, or a strip of 8 or 16
+//                     columns), so the maximum and the integer sum of squares need neither
+//                     atomics nor a buffer that has to be cleared first; the two passes read
+//                     the operand twice, which at these sizes comes from the caches;
+//   k_small_residues  the row-form and column-form workgroups of the general kernels, dealt
+//                     to the two factors by workgroup index.
+// Results are identical to the general kernels': the shifts are exact integer functions of
+// the data and the residues use the same device code.
+#include <algorithm>
+
+#include "oz2_convert.hpp"
+#include "oz2_kernels.hpp"
+
+namespace oz2 {
+namespace {
+
+using namespace dev;
+
+// One factor: `vecs` vectors of `len` elements get one shift each; element h of vector v is
+// X[v * ld + h] (k_contiguous) or X[h * ld + v].
+template <typename T>
+struct SmallSide {
+    const T *X;
+    int64_t ld, vecs, len;
+    int32_t *t;                 // [vecs] shifts: written by k_small_shifts, read by k_small_residues
+    int8_t *out;                // residue slices [N][len_pad/64][vecs_pad][64]
+    int64_t vecs_pad, len_pad;
+    int k_contiguous;
+    unsigned blocks;            // workgroups of this side in the launch at hand
+};
+
+template <typename T>
+constexpr int strip_cols() { return 64 / (int)sizeof(T); }          // 64-byte row segments
+
+__device__ inline int shift_from(uint64_t T_, int e, const ShiftArgs &sa) {
+    int j = 0;
+    while (j < sa.levels - 1 && T_ > sa.theta[j]) ++j;
+    return (sa.f_max - j) - e;
+}
+
+constexpr int kShiftThreads = 256;      // (1024 threads per workgroup were measured: slower at every size)
+constexpr int kShiftWaves = kShiftThreads / kWave;
+
+// Shift of one contiguous vector (a row), by the whole workgroup.
+template <typename T>
+__device__ void row_shift(const T *__restrict__ x, int64_t len, const ShiftArgs &sa, int32_t *t_out,
+                          uint64_t *red) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint64_t mx = 0;
+    for (int64_t h = threadIdx.x; h < len; h += kShiftThreads) {
+        const uint64_t b = (uint64_t)__double_as_longlong(fabs((double)x[h]));
+        mx = b > mx ? b : mx;
+    }
+    mx = wave_max(mx);
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = 0;
+    for (int w = 0; w < kShiftWaves; ++w) mx = red[w] > mx ? red[w] : mx;
+    if (mx == 0) {                                                    // all-zero vector
+        if (threadIdx.x == 0) *t_out = 0;
+        return;
+    }
+    const int e = floor_log2_of_bits(mx);
+    uint64_t sum = 0;
+    for (int64_t h = threadIdx.x; h < len; h += kShiftThreads) {
+        const uint64_t q = (uint64_t)ceil(ldexp(fabs((double)x[h]), 15 - e));
+        sum += q * q;
+    }
+    sum = wave_sum(sum);
+    __syncthreads();                                                  // red[] is reused
+    if (lane == 0) red[wave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t T_ = 0;
+        for (int w = 0; w < kShiftWaves; ++w) T_ += red[w];
+        *t_out = shift_from(T_, e, sa);
+    }
+}
+
+// Shifts of a strip of COLS columns: thread -> (column, row lane); a wavefront reads 64-byte
+// segments of 64 / COLS consecutive rows.  Partial results are combined across the row lanes of
+// a wavefront by shuffles, across wavefronts through LDS (red: kShiftWaves x COLS entries).
+template <typename T>
+__device__ void col_strip_shifts(int64_t strip, const T *__restrict__ X, int64_t ld, int64_t cols,
+                                 int64_t rows, const ShiftArgs &sa, int32_t *t, uint64_t *red) {
+    constexpr int COLS = strip_cols<T>(), LANES = kShiftThreads / COLS;
+    const int cl = threadIdx.x % COLS, rl = threadIdx.x / COLS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t c = strip * COLS + cl;
+    const bool live = c < cols;
+    const T *x = X + c;
+
+    uint64_t mx = 0;
+    if (live) {
+#pragma unroll 8
+        for (int64_t r = rl; r < rows; r += LANES) {
+            const uint64_t b = (uint64_t)__double_as_longlong(fabs((double)x[r * ld]));
+            mx = b > mx ? b : mx;
+        }
+    }
+    for (int off = COLS; off < kWave; off <<= 1) {                    // lanes with the same column
+        const uint64_t o = __shfl_xor(mx, off, kWave);
+        mx = o > mx ? o : mx;
+    }
+    if (lane < COLS) red[wave * COLS + cl] = mx;
+    __syncthreads();
+    mx = 0;
+    for (int w = 0; w < kShiftWaves; ++w) {                           // every thread: its column's maximum
+        const uint64_t o = red[w * COLS + cl];
+        mx = o > mx ? o : mx;
+    }
+    __syncthreads();                                                  // red[] is reused
+    const int e = mx ? floor_log2_of_bits(mx) : 0;
+    uint64_t sum = 0;
+    if (live && mx) {
+#pragma unroll 8
+        for (int64_t r = rl; r < rows; r += LANES) {
+            const uint64_t q = (uint64_t)ceil(ldexp(fabs((double)x[r * ld]), 15 - e));
+            sum += q * q;
+        }
+    }
+    for (int off = COLS; off < kWave; off <<= 1) sum += __shfl_xor(sum, off, kWave);
+    if (lane < COLS) red[wave * COLS + cl] = sum;
+    __syncthreads();
+    if (rl == 0 && live) {
+        uint64_t T_ = 0;
+        for (int w = 0; w < kShiftWaves; ++w) T_ += red[w * COLS + cl];
+        t[c] = mx ? shift_from(T_, e, sa) : 0;                        // all-zero column: shift 0
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kShiftThreads) void k_small_shifts(SmallSide<T> a, SmallSide<T> b, ShiftArgs sa) {
+    __shared__ uint64_t red[kShiftWaves * 16];
+    const bool first = blockIdx.x < a.blocks;
+    const SmallSide<T> s = first ? a : b;
+    const int64_t blk = first ? blockIdx.x : blockIdx.x - a.blocks;
+    if (s.k_contiguous) row_shift<T>(s.X + blk * s.ld, s.len, sa, s.t + blk, red);
+    else col_strip_shifts<T>(blk, s.X, s.ld, s.vecs, s.len, sa, s.t, red);
+}
+
+template <typename T, int ROUNDS>
+__global__ __launch_bounds__(256) void k_small_residues(SmallSide<T> a, SmallSide<T> b, ModArgs ma) {
+    const bool first = blockIdx.x < a.blocks;
+    const SmallSide<T> s = first ? a : b;
+    const int64_t blk = first ? blockIdx.x : blockIdx.x - a.blocks;
+    if (s.k_contiguous) {
+        residues_block<T, ROUNDS, 0>(blk, s.X, s.ld, s.vecs, s.len, s.t, ma, s.out, s.vecs_pad, s.len_pad,
+                                     s.vecs_pad);
+    } else {
+        const int64_t strips = s.vecs_pad / kColStrip;
+        residues_cols_block<T, ROUNDS, 0>(blk % strips, blk / strips, s.X, s.ld, s.len, s.vecs, s.t, ma, s.out,
+                                          s.vecs_pad, s.len_pad, s.vecs_pad);
+    }
+}
+
+template <typename T>
+SmallSide<T> side_of(const T *X, int64_t ld, bool k_contiguous, int64_t vecs, int64_t len, int32_t *t,
+                     int8_t *out, int64_t vecs_pad, int64_t len_pad) {
+    return SmallSide<T>{X, ld, vecs, len, t, out, vecs_pad, len_pad, k_contiguous ? 1 : 0, 0u};
+}
+
+}  // namespace
+
+bool small_conversion_applies(int64_t m, int64_t n, int64_t k) {
+    // Both operands within 2 x 2048^2 elements (they and their slices then sit in the caches)
+    // and columns short enough for one workgroup per strip.
+    return k <= 4096 && m <= 8192 && n <= 8192 && (m + n) * k <= (int64_t)2 * 2048 * 2048;
+}
+
+template <typename T>
+hipError_t launch_small_shifts(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                               bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const ShiftArgs &sa,
+                               int32_t *tA, int32_t *tB, hipStream_t stream) {
+    SmallSide<T> a = side_of<T>(A, lda, a_k_contiguous, m, k, tA, nullptr, 0, 0);
+    SmallSide<T> b = side_of<T>(B, ldb, b_k_contiguous, n, k, tB, nullptr, 0, 0);
+    auto blocks = [](const SmallSide<T> &s) {
+        return (unsigned)(s.k_contiguous ? s.vecs : (s.vecs + strip_cols<T>() - 1) / strip_cols<T>());
+    };
+    a.blocks = blocks(a);
+    b.blocks = blocks(b);
+    hipLaunchKernelGGL((k_small_shifts<T>), dim3(a.blocks + b.blocks), dim3(kShiftThreads), 0, stream, a, b,
+                       sa);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_small_residues(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                                 bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const ModArgs &ma,
+                                 const int32_t *tA, const int32_t *tB, int8_t *rA, int8_t *rB, int64_t Mp,
+                                 int64_t Np, int64_t Kp, hipStream_t stream) {
+    SmallSide<T> a = side_of<T>(A, lda, a_k_contiguous, m, k, const_cast<int32_t *>(tA), rA, Mp, Kp);
+    SmallSide<T> b = side_of<T>(B, ldb, b_k_contiguous, n, k, const_cast<int32_t *>(tB), rB, Np, Kp);
+    auto blocks = [](const SmallSide<T> &s) {
+        return (unsigned)(s.k_contiguous ? (s.vecs_pad * (s.len_pad / kResPerThread) + 255) / 256
+                                         : (s.vecs_pad / kColStrip) * (s.len_pad / kBlockK));
+    };
+    a.blocks = blocks(a);
+    b.blocks = blocks(b);
+    if (ma.rounds == 1)
+        hipLaunchKernelGGL((k_small_residues<T, 1>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
+    else
+        hipLaunchKernelGGL((k_small_residues<T, 2>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
+    return hipGetLastError();
+}
+
+#define OZ2_INSTANTIATE_SMALL(T)                                                                        \
+    template hipError_t launch_small_shifts<T>(const T *, int64_t, bool, const T *, int64_t, bool,      \
+                                               int64_t, int64_t, int64_t, const ShiftArgs &, int32_t *, \
+                                               int32_t *, hipStream_t);                                 \
+    template hipError_t launch_small_residues<T>(const T *, int64_t, bool, const T *, int64_t, bool,    \
+                                                 int64_t, int64_t, int64_t, const ModArgs &,            \
+                                                 const int32_t *, const int32_t *, int8_t *, int8_t *,  \
+                                                 int64_t, int64_t, int64_t, hipStream_t);
+OZ2_INSTANTIATE_SMALL(double)
+OZ2_INSTANTIATE_SMALL(float)
+
+}  // namespace oz2

@@ -33,7 +33,8 @@ def stored(X, transposed, ld_extra, dt):
     return buf, M.shape[1] + ld_extra
 
 
-def run_op(oz, A, B, N, opA, opB, accurate=False, alpha=1.0, beta=0.0, Cin=None, lda_extra=3, ldb_extra=5):
+def run_op(oz, A, B, N, opA, opB, accurate=False, alpha=1.0, beta=0.0, Cin=None, lda_extra=3, ldb_extra=5,
+           small_conversion=True):
     import torch
     from paper_2508_03984_amd import binding as b
     m, k = A.shape
@@ -46,7 +47,11 @@ def run_op(oz, A, B, N, opA, opB, accurate=False, alpha=1.0, beta=0.0, Cin=None,
     if Cin is not None:
         dC.copy_(torch.from_numpy(Cin).cuda())
     fn = oz.oz2_dgemm_op if is_double else oz.oz2_sgemm_op
-    fn(int(opA), int(opB), accurate, m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+    oz.oz2_set_small_conversion(small_conversion)
+    try:
+        fn(int(opA), int(opB), accurate, m, n, k, alpha, dA, lda, dB, ldb, beta, dC, n, N)
+    finally:
+        oz.oz2_set_small_conversion(True)
     torch.cuda.synchronize()
     ra = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_A))
     rb = oz.unblock_slices(oz.stage_tensor(b.OZ2_STAGE_RES_B))
@@ -82,7 +87,9 @@ OP_CASES = [
 def test_transposed_operands_fast_mode(oz, oracle, m, n, k, N, phi, dtype, opA, opB):
     A, B = S.gemm_inputs(m, n, k, phi, seed=50 + N, dtype=dtype)
     is_double = dtype == np.float64
-    check(run_op(oz, A, B, N, opA, opB), oracle.gemm(A, B, N, is_double=is_double), is_double)
+    ref = oracle.gemm(A, B, N, is_double=is_double)
+    check(run_op(oz, A, B, N, opA, opB), ref, is_double)
+    check(run_op(oz, A, B, N, opA, opB, small_conversion=False), ref, is_double)    # the general kernels
 
 
 @pytest.mark.parametrize("opA,opB", [(0, 1), (1, 0), (1, 1)])
@@ -404,7 +411,8 @@ def test_random_shapes_modes_and_operand_forms_against_the_oracle(oz, oracle):
                 oz.oz2_set_workspace_limit(oz.oz2_workspace_min_bytes(m, n, k, N, is_double))
                 oz.oz2_release()
             got = run_op(oz, A, B, N, opA, opB, accurate, alpha, beta, Cin,
-                         lda_extra=int(rng.integers(0, 9)), ldb_extra=int(rng.integers(0, 9))) \
+                         lda_extra=int(rng.integers(0, 9)), ldb_extra=int(rng.integers(0, 9)),
+                         small_conversion=bool(case % 2)) \
                 if not limited else None
             if limited:
                 dt = torch.float64 if is_double else torch.float32
@@ -427,6 +435,46 @@ def test_random_shapes_modes_and_operand_forms_against_the_oracle(oz, oracle):
             if limited:
                 oz.oz2_set_workspace_limit(0)
                 oz.oz2_release()
+
+
+# ------------------------------------------------------------------ small problems
+@pytest.mark.parametrize("m,n,k,N,dtype,opA,opB", [
+    (2048, 2048, 2048, 14, np.float64, 0, 0),      # the largest cube the fused launches take
+    (1500, 2500, 2000, 16, np.float64, 1, 1),      # A by columns, B by rows
+    (8192, 3, 1000, 13, np.float64, 0, 0),         # many short rows, three columns
+    (5, 8192, 1020, 20, np.float64, 1, 0),         # both factors by columns
+    (1024, 1000, 4096, 8, np.float32, 0, 0),       # the longest columns; strips of 16
+    (1000, 1024, 4095, 9, np.float32, 0, 1),       # both factors by rows
+])
+def test_small_conversion_equals_the_general_kernels(oz, m, n, k, N, dtype, opA, opB):
+    """Up to (m + n) k = 2 x 2048^2 the shifts and residues of both factors come from two fused
+    launches; every stage and C must equal what the general kernels give, bit for bit (those
+    are checked against the oracle at these sizes by the sampled tests)."""
+    import torch
+    from paper_2508_03984_amd import binding as b
+    A, B = S.gemm_inputs(m, n, k, 2.0, seed=77 + N, dtype=dtype)
+    A[m // 2, :] = 0.0
+    B[:, n // 3] = 0.0
+    is_double = dtype == np.float64
+    dt = torch.float64 if is_double else torch.float32
+    dA, lda = stored(A, opA, 2, dt)
+    dB, ldb = stored(B, opB, 6, dt)
+    fn = oz.oz2_dgemm_op if is_double else oz.oz2_sgemm_op
+    got = {}
+    try:
+        for small in (True, False):
+            oz.oz2_set_small_conversion(small)
+            dC = torch.full((m, n), float("nan"), dtype=dt, device="cuda")
+            fn(opA, opB, False, m, n, k, 1.0, dA, lda, dB, ldb, 0.0, dC, n, N)
+            torch.cuda.synchronize()
+            got[small] = [dC] + [oz.stage_tensor(st) for st in (b.OZ2_STAGE_SHIFT_A, b.OZ2_STAGE_SHIFT_B,
+                                                                 b.OZ2_STAGE_RES_A, b.OZ2_STAGE_RES_B)]
+    finally:
+        oz.oz2_set_small_conversion(True)
+    for x, y, name in zip(got[True], got[False], ("C", "tA", "tB", "residues of A", "residues of B")):
+        assert torch.equal(x, y), name
+    assert int(got[True][1][m // 2]) == 0 and int(got[True][2][n // 3]) == 0     # zero vectors: shift 0
+    assert bool(torch.isfinite(got[True][0]).all())
 
 
 # ------------------------------------------------------------------ overlapped form

@@ -27,9 +27,10 @@ def oz():
 
 
 def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, accurate=False,
-             int32_products=False, ldc=None, c_offset=0):
+             int32_products=False, ldc=None, c_offset=0, small_conversion=True):
     """Run oz2_dgemm / oz2_sgemm and fetch every stage, trimmed to the logical shapes.  By
-    default the GEMM emits U_s (uint8); with int32_products the diagnostic form C'_s."""
+    default the GEMM emits U_s (uint8); with int32_products the diagnostic form C'_s.
+    small_conversion=False: the general conversion kernels also at these small sizes."""
     import torch
     m, k = A.shape
     n = B.shape[1]
@@ -48,10 +49,12 @@ def gpu_gemm(oz, A, B, N, alpha=1.0, beta=0.0, Cin=None, lda=None, ldb=None, acc
     else:
         fn = oz.oz2_dgemm if dt == torch.float64 else oz.oz2_sgemm
     oz.oz2_set_int32_products(int32_products)
+    oz.oz2_set_small_conversion(small_conversion)
     try:
         fn(m, n, k, alpha, dA, lda, dB, ldb, beta, dC, ldc, N)
     finally:
         oz.oz2_set_int32_products(False)
+        oz.oz2_set_small_conversion(True)
     torch.cuda.synchronize()
     from paper_2508_03984_amd import binding as b
     out = dict(C=dC.cpu().numpy())
@@ -123,7 +126,7 @@ def test_stage_parity(oz, oracle, m, n, k, N, phi, dtype):
     is_double = dtype == np.float64
     ref = oracle.gemm(A, B, N, is_double=is_double)
     assert_parity(gpu_gemm(oz, A, B, N), ref, is_double)
-    assert_parity(gpu_gemm(oz, A, B, N, int32_products=True), ref, is_double)
+    assert_parity(gpu_gemm(oz, A, B, N, int32_products=True, small_conversion=False), ref, is_double)
 
 
 def test_k_beyond_2_pow_17_is_blocked(oz, oracle):
