@@ -427,7 +427,7 @@ def main() -> int:
                     help="time a whole configuration of the benchmark set over its moduli counts; "
                          "one JSON line per case goes to --out")
     ap.add_argument("--out", default=None, help="file for --sweep (default: sweep_<name>.jsonl)")
-    ap.add_argument("--cpu-block", type=int, default=1024,
+    ap.add_argument("--cpu-block", type=int, default=1536,
                     help="the oracle is timed on C[0:b, 0:b] with the full k")
     args = ap.parse_args()
     if args.gpus != 1:
