@@ -175,7 +175,12 @@ SWEEPS = {
     "nonsquare": [(8192, 8192, 65536, 1.0, True, [18])],
     # fast against accurate mode on inputs with a wide exponent range
     "modes": [(8192, 8192, 8192, phi, True, [14, 15, 16, 17, 18]) for phi in (0.5, 2.0, 4.0)],
+    # throughput against the matrix size, both modes, at the moduli counts of Section 5.2
+    # (the setting of the paper's DGEMM and SGEMM throughput and time-breakdown figures)
+    "throughput_dgemm": [(s, s, s, 0.5, True, [14, 15, 16, 17]) for s in (1024, 2048, 4096, 8192, 16384)],
+    "throughput_sgemm": [(s, s, s, 0.5, False, [6, 7, 8]) for s in (1024, 2048, 4096, 8192, 16384)],
 }
+BOTH_MODES = ("modes", "throughput_dgemm", "throughput_sgemm")
 
 
 def sweep(oz, torch, name, args) -> int:
@@ -200,13 +205,14 @@ def sweep(oz, torch, name, args) -> int:
             err = lambda c: float(np.max(np.abs((c.astype(np.float64) - hi) - lo) / ab))
             torch.mm(dA, dB, out=dC)
             torch.cuda.synchronize()
+            native_reps = max(3, min(200, int(2e11 / (2.0 * m * n * k))))
             t1 = time.perf_counter()
-            for _ in range(3):
+            for _ in range(native_reps):
                 torch.mm(dA, dB, out=dC)
             torch.cuda.synchronize()
-            native_tflops = 2.0 * m * n * k / ((time.perf_counter() - t1) / 3) / 1e12
+            native_tflops = 2.0 * m * n * k / ((time.perf_counter() - t1) / native_reps) / 1e12
             native_err = err(dC[trows].cpu().numpy())
-            modes = [False, True] if name == "modes" else [args.accurate]
+            modes = [False, True] if name in BOTH_MODES else [args.accurate]
             for N, accurate in [(N, a) for N in moduli for a in modes]:
                 if accurate:
                     fn = oz.oz2_dgemm_accurate if is_double else oz.oz2_sgemm_accurate
@@ -215,14 +221,19 @@ def sweep(oz, torch, name, args) -> int:
                 for _ in range(args.warmup):
                     fn(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N)
                 torch.cuda.synchronize()
+                # the calls back to back (small sizes: enough of them to time), then per-stage
+                # times from profiled calls, which wait for their events one by one
+                reps = max(args.steps, min(200, int(2e11 / (2.0 * m * n * k))))
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    fn(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N)
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) / reps
                 oz.oz2_set_profiling(True)
                 stage_ms = np.zeros(4)
-                t0 = time.perf_counter()
                 for _ in range(args.steps):
                     fn(m, n, k, 1.0, dA, k, dB, n, 0.0, dC, n, N)
                     stage_ms += np.array(oz.oz2_last_stage_times_ms())
-                torch.cuda.synchronize()
-                dt = (time.perf_counter() - t0) / args.steps
                 oz.oz2_set_profiling(False)
                 rec = {"m": m, "n": n, "k": k, "phi": phi, "dtype": "f64" if is_double else "f32",
                        "mode": "accurate" if accurate else "fast", "num_moduli": N, "ms": 1e3 * dt, "emulated_tflops": 2.0 * m * n * k / dt / 1e12,
