@@ -289,9 +289,10 @@ void oz2_set_overlap(int on);
 
 /*
  * Small problems (on by default).  Below about 2048^3 a call is bound by the latency of its
- * dependent kernel launches.  For fast-mode calls with k <= 4096, m, n <= 8192 and
+ * dependent kernel launches.  For calls with k <= 4096, m, n <= 8192 and
  * (m + n) * k <= 2 * 2048^2 the conversion of Algorithm 1 lines 1-5 therefore runs as two
- * launches that cover both factors (the shifts; the residues) instead of seven.  The result
+ * launches that cover both factors (the shifts; the residues) instead of seven, and in
+ * accurate mode the passes that precede Cbar (maxima; Abar and Bbar) likewise.  The result
  * and every stage are bit-identical.  oz2_set_small_conversion(0) uses the general kernels
  * at every size.
  */

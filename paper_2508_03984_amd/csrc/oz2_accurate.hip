@@ -38,47 +38,47 @@ __global__ __launch_bounds__(256) void k_row_maxbits(const T *__restrict__ X, in
     }
 }
 
-// pre[v] = 5 - floor(log2 max) (0 for an all-zero vector: its magnitudes are all 0 anyway).
+// pre[v] = 5 - floor(log2 max) (0 for an all-zero vector: its magnitudes are all 0 anyway), for
+// the rows of A and the columns of B in one go (their arrays adjoin); also clears the maxima of
+// Cbar (a kernel, not a memset: the call may be captured into a HIP graph).
 __global__ __launch_bounds__(256) void k_preshift(const unsigned long long *__restrict__ maxbits,
-                                                  int64_t count, int32_t *__restrict__ pre) {
+                                                  int64_t count, int32_t *__restrict__ pre,
+                                                  int32_t *__restrict__ cmax) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
     const uint64_t b = maxbits[i];
     pre[i] = b ? 5 - floor_log2_of_bits(b) : 0;
+    cmax[i] = 0;
 }
 
-__global__ __launch_bounds__(256) void k_fill_i32(int32_t *p, int64_t count, int32_t v) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < count) p[i] = v;
-}
-
-// rmax[i] = max(rmax[i], max_j Cbar[i][j] over j < n): one workgroup per row.  Entries are
-// >= 0 and rmax starts at 0, so the integer atomic maximum over several column panels is
-// the maximum over the whole row whatever the order.
-__global__ __launch_bounds__(256) void k_row_max_i32(const int32_t *__restrict__ Cbar, int64_t ld,
-                                                     int64_t n, int *rmax) {
-    __shared__ int part[4];
-    const int32_t *x = Cbar + (int64_t)blockIdx.x * ld;
-    int mx = 0;
-    for (int64_t j = threadIdx.x; j < n; j += 256) mx = x[j] > mx ? x[j] : mx;
-    for (int off = 32; off > 0; off >>= 1) {
-        int o = __shfl_xor(mx, off, 64);
-        mx = o > mx ? o : mx;
+// Maxima of one panel of Cbar in one launch.  Workgroups [0, m): rmax[i] = max(rmax[i],
+// max_j Cbar[i][j] over j < n), one workgroup per row.  The others: cmax[j] = max(cmax[j],
+// max_i Cbar[i][j]) over a block of 256 rows x 256 columns each.  Entries are >= 0 and the
+// maxima start at 0, so the integer atomic maximum over several panels is the maximum over the
+// whole row or column whatever the order.
+__global__ __launch_bounds__(256) void k_cbar_maxima(const int32_t *__restrict__ Cbar, int64_t ld,
+                                                     int64_t m, int64_t n, int *rmax, int *cmax) {
+    if ((int64_t)blockIdx.x < m) {
+        __shared__ int part[4];
+        const int32_t *x = Cbar + (int64_t)blockIdx.x * ld;
+        int mx = 0;
+        for (int64_t j = threadIdx.x; j < n; j += 256) mx = x[j] > mx ? x[j] : mx;
+        for (int off = 32; off > 0; off >>= 1) {
+            int o = __shfl_xor(mx, off, 64);
+            mx = o > mx ? o : mx;
+        }
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 4; ++w) mx = part[w] > mx ? part[w] : mx;
+            if (mx) atomicMax(&rmax[blockIdx.x], mx);
+        }
+        return;
     }
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; ++w) mx = part[w] > mx ? part[w] : mx;
-        if (mx) atomicMax(&rmax[blockIdx.x], mx);
-    }
-}
-
-// cmax[j] = max_i Cbar[i][j] over i < m: (256 columns x 256 rows) per workgroup, atomicMax.
-__global__ __launch_bounds__(256) void k_col_max_i32(const int32_t *__restrict__ Cbar, int64_t ld,
-                                                     int64_t m, int64_t n, int *cmax) {
-    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t blk = (int64_t)blockIdx.x - m, strips = (n + 255) / 256;
+    const int64_t j = (blk % strips) * 256 + threadIdx.x;
     if (j >= n) return;
-    const int64_t i0 = (int64_t)blockIdx.y * 256;
+    const int64_t i0 = (blk / strips) * 256;
     const int64_t i1 = i0 + 256 < m ? i0 + 256 : m;
     int mx = 0;
 #pragma unroll 8
@@ -90,17 +90,20 @@ __global__ __launch_bounds__(256) void k_col_max_i32(const int32_t *__restrict__
 }
 
 // t[v] = (5 - e_v) + floor(P'_accu - 0.51 log2 max(c_v, 1)); an all-zero vector gets 0.
+// Entries [0, m) are the rows of A, [m, count) the columns of B (the arrays adjoin).
 __global__ __launch_bounds__(256) void k_accu_finish(const unsigned long long *__restrict__ maxbits,
-                                                     const int32_t *__restrict__ cmax, int64_t count,
-                                                     ShiftArgs sa, int32_t *__restrict__ t) {
+                                                     const int32_t *__restrict__ cmax, int64_t m,
+                                                     int64_t count, ShiftArgs sa, int32_t *__restrict__ tA,
+                                                     int32_t *__restrict__ tB) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
+    int32_t *t = i < m ? tA + i : tB + (i - m);
     const uint64_t b = maxbits[i];
-    if (b == 0) { t[i] = 0; return; }
+    if (b == 0) { *t = 0; return; }
     const uint64_t c = cmax[i] > 0 ? (uint64_t)cmax[i] : 1;
     int j = 0;
     while (j < sa.levels - 1 && c > sa.theta[j]) ++j;
-    t[i] = (5 - floor_log2_of_bits(b)) + (sa.f_max - j);
+    *t = (5 - floor_log2_of_bits(b)) + (sa.f_max - j);
 }
 
 struct Scratch {
@@ -130,8 +133,17 @@ template <typename T>
 hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous, const T *B,
                                     int64_t ldb, bool b_k_contiguous, int64_t m, int64_t n,
                                     int64_t k, void *scratch, int8_t *Abar, int8_t *Bbar,
-                                    int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream) {
+                                    int64_t Mp, int64_t Np, int64_t Kp, bool small, hipStream_t stream) {
     const Scratch s = carve(scratch, m, n);
+    if (small) {                                          // both factors per launch
+        if (hipError_t e = launch_small_maxbits<T>(A, lda, a_k_contiguous, B, ldb, b_k_contiguous, m, n, k,
+                                                   s.amax, s.bmax, stream))
+            return e;
+        hipLaunchKernelGGL(k_preshift, dim3(blocks_for(m + n)), dim3(256), 0, stream, s.amax, m + n, s.preA,
+                           s.crow);
+        return launch_small_magnitudes<T>(A, lda, a_k_contiguous, B, ldb, b_k_contiguous, m, n, k, s.preA,
+                                          s.preB, Abar, Bbar, Mp, Np, Kp, stream);
+    }
     // A vector of the product (a row of op(A), a column of op(B)) is either contiguous in
     // memory (one workgroup per vector) or strided by the leading dimension (column kernels).
     if (a_k_contiguous)
@@ -140,8 +152,8 @@ hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous
     if (b_k_contiguous)
         hipLaunchKernelGGL((k_row_maxbits<T>), dim3((unsigned)n), dim3(256), 0, stream, B, ldb, k, s.bmax);
     else if (hipError_t e = launch_col_maxbits<T>(B, ldb, k, n, s.bmax, stream)) return e;
-    hipLaunchKernelGGL(k_preshift, dim3(blocks_for(m)), dim3(256), 0, stream, s.amax, m, s.preA);
-    hipLaunchKernelGGL(k_preshift, dim3(blocks_for(n)), dim3(256), 0, stream, s.bmax, n, s.preB);
+    // amax | bmax, preA | preB and crow | ccol adjoin: one launch for both factors
+    hipLaunchKernelGGL(k_preshift, dim3(blocks_for(m + n)), dim3(256), 0, stream, s.amax, m + n, s.preA, s.crow);
     if (hipError_t e = a_k_contiguous ? launch_magnitudes<T>(A, lda, m, k, s.preA, Abar, Mp, Kp, stream)
                                       : launch_magnitudes_cols<T>(A, lda, k, m, s.preA, Abar, Mp, Kp, stream))
         return e;
@@ -149,37 +161,30 @@ hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous
                           : launch_magnitudes_cols<T>(B, ldb, k, n, s.preB, Bbar, Np, Kp, stream);
 }
 
-hipError_t launch_accurate_maxima_clear(int64_t m, int64_t n, void *scratch, hipStream_t stream) {
-    const Scratch s = carve(scratch, m, n);
-    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(m + n)), dim3(256), 0, stream, s.crow, m + n, 0);   // crow, ccol adjoin
-    return hipGetLastError();
-}
-
 hipError_t launch_accurate_maxima(const int32_t *Cbar, int64_t ld, int64_t row0, int64_t rows,
                                   int64_t col0, int64_t cols, int64_t m, int64_t n, void *scratch,
                                   hipStream_t stream) {
     const Scratch s = carve(scratch, m, n);
     if (rows <= 0 || cols <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_row_max_i32, dim3((unsigned)rows), dim3(256), 0, stream, Cbar, ld, cols,
-                       s.crow + row0);
-    hipLaunchKernelGGL(k_col_max_i32, dim3(blocks_for(cols), (unsigned)((rows + 255) / 256)), dim3(256), 0,
-                       stream, Cbar, ld, rows, cols, s.ccol + col0);
+    const int64_t blocks = rows + ((cols + 255) / 256) * ((rows + 255) / 256);
+    hipLaunchKernelGGL(k_cbar_maxima, dim3((unsigned)blocks), dim3(256), 0, stream, Cbar, ld, rows, cols,
+                       s.crow + row0, s.ccol + col0);
     return hipGetLastError();
 }
 
 hipError_t launch_accurate_finish(int64_t m, int64_t n, const ShiftArgs &sa, void *scratch,
                                   int32_t *tA, int32_t *tB, hipStream_t stream) {
     const Scratch s = carve(scratch, m, n);
-    hipLaunchKernelGGL(k_accu_finish, dim3(blocks_for(m)), dim3(256), 0, stream, s.amax, s.crow, m, sa, tA);
-    hipLaunchKernelGGL(k_accu_finish, dim3(blocks_for(n)), dim3(256), 0, stream, s.bmax, s.ccol, n, sa, tB);
+    hipLaunchKernelGGL(k_accu_finish, dim3(blocks_for(m + n)), dim3(256), 0, stream, s.amax, s.crow, m, m + n,
+                       sa, tA, tB);
     return hipGetLastError();
 }
 
 template hipError_t launch_accurate_prescale<double>(const double *, int64_t, bool, const double *, int64_t,
                                                      bool, int64_t, int64_t, int64_t, void *, int8_t *,
-                                                     int8_t *, int64_t, int64_t, int64_t, hipStream_t);
+                                                     int8_t *, int64_t, int64_t, int64_t, bool, hipStream_t);
 template hipError_t launch_accurate_prescale<float>(const float *, int64_t, bool, const float *, int64_t,
                                                     bool, int64_t, int64_t, int64_t, void *, int8_t *,
-                                                    int8_t *, int64_t, int64_t, int64_t, hipStream_t);
+                                                    int8_t *, int64_t, int64_t, int64_t, bool, hipStream_t);
 
 }  // namespace oz2

@@ -353,15 +353,15 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     int8_t *rB = reinterpret_cast<int8_t *>(g.ws + L.off_rb);
     void *prod = g.ws + L.off_prod;
 
-    // Small problems in fast mode: the conversion of both factors in two launches instead of seven.
-    const bool small = g.small_conversion && !accurate && small_conversion_applies(m, n, k);
+    // Small problems: the conversion of both factors in two launches instead of seven (and
+    // likewise the passes of accurate mode that precede Cbar).
+    const bool small = g.small_conversion && small_conversion_applies(m, n, k);
     if (oz2_status st = mark(0, stream)) return st;
     if (accurate) {
         // Section 4.2, accurate mode: 7-bit matrices into slice 0, Cbar panel by panel into the
         // product part, of which only the row and column maxima are kept.
         OZ2_TRY(launch_accurate_prescale<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, scratch, rA, rB, L.Mp,
-                                            L.Np, L.Kp, stream));
-        OZ2_TRY(launch_accurate_maxima_clear(m, n, scratch, stream));
+                                            L.Np, L.Kp, small, stream));
         for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
             for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
                 const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);

@@ -104,24 +104,36 @@ hipError_t launch_small_residues(const T *A, int64_t lda, bool a_k_contiguous, c
                                  const int32_t *tA, const int32_t *tB, int8_t *rA, int8_t *rB, int64_t Mp,
                                  int64_t Np, int64_t Kp, hipStream_t stream);
 
+// The same for accurate mode: the bits of max |.| per vector of both factors in one launch, and
+// the 7-bit magnitude matrices ceil(|x| 2^pre) of both (slice 0 of the residue buffers) in one.
+template <typename T>
+hipError_t launch_small_maxbits(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                                bool b_k_contiguous, int64_t m, int64_t n, int64_t k,
+                                unsigned long long *amax, unsigned long long *bmax, hipStream_t stream);
+template <typename T>
+hipError_t launch_small_magnitudes(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                                   bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const int32_t *preA,
+                                   const int32_t *preB, int8_t *Abar, int8_t *Bbar, int64_t Mp, int64_t Np,
+                                   int64_t Kp, hipStream_t stream);
+
 // Accurate mode (Section 4.2, second half).  All vectors live in `scratch`
 // (accurate_scratch_bytes(m, n) bytes); the 7-bit matrices go to slice 0 of the residue
 // buffers (same K-blocked layout) and Cbar to plane 0 of the product buffer:
 //   launch_accurate_prescale   max|.| per row of A / column of B, mu' = 2^(5-e), nu', and
-//                              Abar = ceil(mu' |A|), Bbar = ceil(|B| nu') as int8
+//                              Abar = ceil(mu' |A|), Bbar = ceil(|B| nu') as int8; clears the
+//                              maxima of Cbar.  small: with the fused launches for small problems
 //   (the caller then runs launch_int8_gemm with batch 1 to get Cbar = Abar * Bbar)
-//   launch_accurate_maxima*    row / column maxima of Cbar over its m x n part
+//   launch_accurate_maxima     row / column maxima of Cbar over its m x n part
 //   launch_accurate_finish     t = (5 - e) + floor(P'_accu - 0.51 log2 max), zero vectors -> 0
 size_t accurate_scratch_bytes(int64_t m, int64_t n);
 template <typename T>
 hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous, const T *B,
                                     int64_t ldb, bool b_k_contiguous, int64_t m, int64_t n,
                                     int64_t k, void *scratch, int8_t *Abar, int8_t *Bbar,
-                                    int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream);
-// Maxima of Cbar, panel by panel: _clear zeroes them; _maxima folds in the (rows x cols) valid
-// part of one panel of Cbar (leading dimension ld) whose top-left entry is (row0, col0) of the
-// whole product; _finish turns them into the shifts.
-hipError_t launch_accurate_maxima_clear(int64_t m, int64_t n, void *scratch, hipStream_t stream);
+                                    int64_t Mp, int64_t Np, int64_t Kp, bool small, hipStream_t stream);
+// Maxima of Cbar, panel by panel: _maxima folds in the (rows x cols) valid part of one panel of
+// Cbar (leading dimension ld) whose top-left entry is (row0, col0) of the whole product; _finish
+// turns them into the shifts.
 hipError_t launch_accurate_maxima(const int32_t *Cbar, int64_t ld, int64_t row0, int64_t rows,
                                   int64_t col0, int64_t cols, int64_t m, int64_t n, void *scratch,
                                   hipStream_t stream);

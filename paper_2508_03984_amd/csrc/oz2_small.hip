@@ -28,6 +28,7 @@ struct SmallSide {
     const T *X;
     int64_t ld, vecs, len;
     int32_t *t;                 // [vecs] shifts: written by k_small_shifts, read by k_small_residues
+    unsigned long long *maxbits;   // [vecs] accurate mode: bits of max |x|, written by k_small_maxbits
     int8_t *out;                // residue slices [N][len_pad/64][vecs_pad][64]
     int64_t vecs_pad, len_pad;
     int k_contiguous;
@@ -46,10 +47,10 @@ __device__ inline int shift_from(uint64_t T_, int e, const ShiftArgs &sa) {
 constexpr int kShiftThreads = 256;      // (1024 threads per workgroup were measured: slower at every size)
 constexpr int kShiftWaves = kShiftThreads / kWave;
 
-// Shift of one contiguous vector (a row), by the whole workgroup.
+// Bits of max |x| over one contiguous vector (a row), by the whole workgroup; every thread
+// receives the result.
 template <typename T>
-__device__ void row_shift(const T *__restrict__ x, int64_t len, const ShiftArgs &sa, int32_t *t_out,
-                          uint64_t *red) {
+__device__ uint64_t row_max(const T *__restrict__ x, int64_t len, uint64_t *red) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint64_t mx = 0;
     for (int64_t h = threadIdx.x; h < len; h += kShiftThreads) {
@@ -61,6 +62,16 @@ __device__ void row_shift(const T *__restrict__ x, int64_t len, const ShiftArgs 
     __syncthreads();
     mx = 0;
     for (int w = 0; w < kShiftWaves; ++w) mx = red[w] > mx ? red[w] : mx;
+    __syncthreads();                                                  // red[] may be reused
+    return mx;
+}
+
+// Shift of one row.
+template <typename T>
+__device__ void row_shift(const T *__restrict__ x, int64_t len, const ShiftArgs &sa, int32_t *t_out,
+                          uint64_t *red) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t mx = row_max<T>(x, len, red);
     if (mx == 0) {                                                    // all-zero vector
         if (threadIdx.x == 0) *t_out = 0;
         return;
@@ -72,7 +83,6 @@ __device__ void row_shift(const T *__restrict__ x, int64_t len, const ShiftArgs 
         sum += q * q;
     }
     sum = wave_sum(sum);
-    __syncthreads();                                                  // red[] is reused
     if (lane == 0) red[wave] = sum;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -82,21 +92,20 @@ __device__ void row_shift(const T *__restrict__ x, int64_t len, const ShiftArgs 
     }
 }
 
-// Shifts of a strip of COLS columns: thread -> (column, row lane); a wavefront reads 64-byte
-// segments of 64 / COLS consecutive rows.  Partial results are combined across the row lanes of
-// a wavefront by shuffles, across wavefronts through LDS (red: kShiftWaves x COLS entries).
+// A strip of COLS columns: thread -> (column, row lane); a wavefront reads 64-byte segments of
+// 64 / COLS consecutive rows.  Partial results are combined across the row lanes of a wavefront
+// by shuffles, across wavefronts through LDS (red: kShiftWaves x COLS entries).
+// col_strip_max: every thread receives the bits of max |x| over its column (0 beyond `cols`).
 template <typename T>
-__device__ void col_strip_shifts(int64_t strip, const T *__restrict__ X, int64_t ld, int64_t cols,
-                                 int64_t rows, const ShiftArgs &sa, int32_t *t, uint64_t *red) {
+__device__ uint64_t col_strip_max(int64_t strip, const T *__restrict__ X, int64_t ld, int64_t cols,
+                                  int64_t rows, uint64_t *red) {
     constexpr int COLS = strip_cols<T>(), LANES = kShiftThreads / COLS;
     const int cl = threadIdx.x % COLS, rl = threadIdx.x / COLS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t c = strip * COLS + cl;
-    const bool live = c < cols;
     const T *x = X + c;
-
     uint64_t mx = 0;
-    if (live) {
+    if (c < cols) {
 #pragma unroll 8
         for (int64_t r = rl; r < rows; r += LANES) {
             const uint64_t b = (uint64_t)__double_as_longlong(fabs((double)x[r * ld]));
@@ -110,11 +119,24 @@ __device__ void col_strip_shifts(int64_t strip, const T *__restrict__ X, int64_t
     if (lane < COLS) red[wave * COLS + cl] = mx;
     __syncthreads();
     mx = 0;
-    for (int w = 0; w < kShiftWaves; ++w) {                           // every thread: its column's maximum
+    for (int w = 0; w < kShiftWaves; ++w) {
         const uint64_t o = red[w * COLS + cl];
         mx = o > mx ? o : mx;
     }
-    __syncthreads();                                                  // red[] is reused
+    __syncthreads();                                                  // red[] may be reused
+    return mx;
+}
+
+template <typename T>
+__device__ void col_strip_shifts(int64_t strip, const T *__restrict__ X, int64_t ld, int64_t cols,
+                                 int64_t rows, const ShiftArgs &sa, int32_t *t, uint64_t *red) {
+    constexpr int COLS = strip_cols<T>(), LANES = kShiftThreads / COLS;
+    const int cl = threadIdx.x % COLS, rl = threadIdx.x / COLS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t c = strip * COLS + cl;
+    const bool live = c < cols;
+    const T *x = X + c;
+    const uint64_t mx = col_strip_max<T>(strip, X, ld, cols, rows, red);
     const int e = mx ? floor_log2_of_bits(mx) : 0;
     uint64_t sum = 0;
     if (live && mx) {
@@ -144,17 +166,36 @@ __global__ __launch_bounds__(kShiftThreads) void k_small_shifts(SmallSide<T> a, 
     else col_strip_shifts<T>(blk, s.X, s.ld, s.vecs, s.len, sa, s.t, red);
 }
 
-template <typename T, int ROUNDS>
+// Accurate mode: only the bits of max |x| per vector (its pre-shift 5 - e follows from them).
+template <typename T>
+__global__ __launch_bounds__(kShiftThreads) void k_small_maxbits(SmallSide<T> a, SmallSide<T> b) {
+    __shared__ uint64_t red[kShiftWaves * 16];
+    const bool first = blockIdx.x < a.blocks;
+    const SmallSide<T> s = first ? a : b;
+    const int64_t blk = first ? blockIdx.x : blockIdx.x - a.blocks;
+    if (s.k_contiguous) {
+        const uint64_t mx = row_max<T>(s.X + blk * s.ld, s.len, red);
+        if (threadIdx.x == 0) s.maxbits[blk] = mx;
+    } else {
+        constexpr int COLS = strip_cols<T>();
+        const uint64_t mx = col_strip_max<T>(blk, s.X, s.ld, s.vecs, s.len, red);
+        const int64_t c = blk * COLS + threadIdx.x;
+        if (threadIdx.x < COLS && c < s.vecs) s.maxbits[c] = mx;
+    }
+}
+
+// KIND 0: residues for all moduli; KIND 1 (accurate mode): the 7-bit magnitudes ceil(|x| 2^t).
+template <typename T, int ROUNDS, int KIND>
 __global__ __launch_bounds__(256) void k_small_residues(SmallSide<T> a, SmallSide<T> b, ModArgs ma) {
     const bool first = blockIdx.x < a.blocks;
     const SmallSide<T> s = first ? a : b;
     const int64_t blk = first ? blockIdx.x : blockIdx.x - a.blocks;
     if (s.k_contiguous) {
-        residues_block<T, ROUNDS, 0>(blk, s.X, s.ld, s.vecs, s.len, s.t, ma, s.out, s.vecs_pad, s.len_pad,
+        residues_block<T, ROUNDS, KIND>(blk, s.X, s.ld, s.vecs, s.len, s.t, ma, s.out, s.vecs_pad, s.len_pad,
                                      s.vecs_pad);
     } else {
         const int64_t strips = s.vecs_pad / kColStrip;
-        residues_cols_block<T, ROUNDS, 0>(blk % strips, blk / strips, s.X, s.ld, s.len, s.vecs, s.t, ma, s.out,
+        residues_cols_block<T, ROUNDS, KIND>(blk % strips, blk / strips, s.X, s.ld, s.len, s.vecs, s.t, ma, s.out,
                                           s.vecs_pad, s.len_pad, s.vecs_pad);
     }
 }
@@ -162,7 +203,18 @@ __global__ __launch_bounds__(256) void k_small_residues(SmallSide<T> a, SmallSid
 template <typename T>
 SmallSide<T> side_of(const T *X, int64_t ld, bool k_contiguous, int64_t vecs, int64_t len, int32_t *t,
                      int8_t *out, int64_t vecs_pad, int64_t len_pad) {
-    return SmallSide<T>{X, ld, vecs, len, t, out, vecs_pad, len_pad, k_contiguous ? 1 : 0, 0u};
+    return SmallSide<T>{X, ld, vecs, len, t, nullptr, out, vecs_pad, len_pad, k_contiguous ? 1 : 0, 0u};
+}
+
+// Workgroups one side contributes to the shift / maximum launch and to the residue launch.
+template <typename T>
+unsigned shift_blocks(const SmallSide<T> &s) {
+    return (unsigned)(s.k_contiguous ? s.vecs : (s.vecs + strip_cols<T>() - 1) / strip_cols<T>());
+}
+template <typename T>
+unsigned residue_blocks(const SmallSide<T> &s) {
+    return (unsigned)(s.k_contiguous ? (s.vecs_pad * (s.len_pad / kResPerThread) + 255) / 256
+                                     : (s.vecs_pad / kColStrip) * (s.len_pad / kBlockK));
 }
 
 }  // namespace
@@ -179,11 +231,8 @@ hipError_t launch_small_shifts(const T *A, int64_t lda, bool a_k_contiguous, con
                                int32_t *tA, int32_t *tB, hipStream_t stream) {
     SmallSide<T> a = side_of<T>(A, lda, a_k_contiguous, m, k, tA, nullptr, 0, 0);
     SmallSide<T> b = side_of<T>(B, ldb, b_k_contiguous, n, k, tB, nullptr, 0, 0);
-    auto blocks = [](const SmallSide<T> &s) {
-        return (unsigned)(s.k_contiguous ? s.vecs : (s.vecs + strip_cols<T>() - 1) / strip_cols<T>());
-    };
-    a.blocks = blocks(a);
-    b.blocks = blocks(b);
+    a.blocks = shift_blocks(a);
+    b.blocks = shift_blocks(b);
     hipLaunchKernelGGL((k_small_shifts<T>), dim3(a.blocks + b.blocks), dim3(kShiftThreads), 0, stream, a, b,
                        sa);
     return hipGetLastError();
@@ -196,16 +245,40 @@ hipError_t launch_small_residues(const T *A, int64_t lda, bool a_k_contiguous, c
                                  int64_t Np, int64_t Kp, hipStream_t stream) {
     SmallSide<T> a = side_of<T>(A, lda, a_k_contiguous, m, k, const_cast<int32_t *>(tA), rA, Mp, Kp);
     SmallSide<T> b = side_of<T>(B, ldb, b_k_contiguous, n, k, const_cast<int32_t *>(tB), rB, Np, Kp);
-    auto blocks = [](const SmallSide<T> &s) {
-        return (unsigned)(s.k_contiguous ? (s.vecs_pad * (s.len_pad / kResPerThread) + 255) / 256
-                                         : (s.vecs_pad / kColStrip) * (s.len_pad / kBlockK));
-    };
-    a.blocks = blocks(a);
-    b.blocks = blocks(b);
+    a.blocks = residue_blocks(a);
+    b.blocks = residue_blocks(b);
     if (ma.rounds == 1)
-        hipLaunchKernelGGL((k_small_residues<T, 1>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
+        hipLaunchKernelGGL((k_small_residues<T, 1, 0>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
     else
-        hipLaunchKernelGGL((k_small_residues<T, 2>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
+        hipLaunchKernelGGL((k_small_residues<T, 2, 0>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_small_maxbits(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                                bool b_k_contiguous, int64_t m, int64_t n, int64_t k,
+                                unsigned long long *amax, unsigned long long *bmax, hipStream_t stream) {
+    SmallSide<T> a = side_of<T>(A, lda, a_k_contiguous, m, k, nullptr, nullptr, 0, 0);
+    SmallSide<T> b = side_of<T>(B, ldb, b_k_contiguous, n, k, nullptr, nullptr, 0, 0);
+    a.maxbits = amax;
+    b.maxbits = bmax;
+    a.blocks = shift_blocks(a);
+    b.blocks = shift_blocks(b);
+    hipLaunchKernelGGL((k_small_maxbits<T>), dim3(a.blocks + b.blocks), dim3(kShiftThreads), 0, stream, a, b);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_small_magnitudes(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
+                                   bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const int32_t *preA,
+                                   const int32_t *preB, int8_t *Abar, int8_t *Bbar, int64_t Mp, int64_t Np,
+                                   int64_t Kp, hipStream_t stream) {
+    SmallSide<T> a = side_of<T>(A, lda, a_k_contiguous, m, k, const_cast<int32_t *>(preA), Abar, Mp, Kp);
+    SmallSide<T> b = side_of<T>(B, ldb, b_k_contiguous, n, k, const_cast<int32_t *>(preB), Bbar, Np, Kp);
+    a.blocks = residue_blocks(a);
+    b.blocks = residue_blocks(b);
+    ModArgs none{};
+    hipLaunchKernelGGL((k_small_residues<T, 1, 1>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, none);
     return hipGetLastError();
 }
 
@@ -216,7 +289,14 @@ hipError_t launch_small_residues(const T *A, int64_t lda, bool a_k_contiguous, c
     template hipError_t launch_small_residues<T>(const T *, int64_t, bool, const T *, int64_t, bool,    \
                                                  int64_t, int64_t, int64_t, const ModArgs &,            \
                                                  const int32_t *, const int32_t *, int8_t *, int8_t *,  \
-                                                 int64_t, int64_t, int64_t, hipStream_t);
+                                                 int64_t, int64_t, int64_t, hipStream_t);              \
+    template hipError_t launch_small_maxbits<T>(const T *, int64_t, bool, const T *, int64_t, bool,     \
+                                                int64_t, int64_t, int64_t, unsigned long long *,        \
+                                                unsigned long long *, hipStream_t);                     \
+    template hipError_t launch_small_magnitudes<T>(const T *, int64_t, bool, const T *, int64_t, bool,  \
+                                                   int64_t, int64_t, int64_t, const int32_t *,          \
+                                                   const int32_t *, int8_t *, int8_t *, int64_t,        \
+                                                   int64_t, int64_t, hipStream_t);
 OZ2_INSTANTIATE_SMALL(double)
 OZ2_INSTANTIATE_SMALL(float)
 

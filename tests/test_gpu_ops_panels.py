@@ -99,6 +99,7 @@ def test_transposed_operands_accurate_mode_alpha_beta(oz, oracle, opA, opB):
     Cin = S.matrix(150, 260, 0.5, seed=62)
     ref = oracle.gemm(A, B, 15, -0.75, 1.5, Cin, accurate=True)
     check(run_op(oz, A, B, 15, opA, opB, True, -0.75, 1.5, Cin), ref, True)
+    check(run_op(oz, A, B, 15, opA, opB, True, -0.75, 1.5, Cin, small_conversion=False), ref, True)
     A32, B32 = A.astype(np.float32), B.astype(np.float32)
     ref = oracle.gemm(A32, B32, 7, is_double=False, accurate=True)
     check(run_op(oz, A32, B32, 7, opA, opB, True), ref, False)
@@ -438,6 +439,7 @@ def test_random_shapes_modes_and_operand_forms_against_the_oracle(oz, oracle):
 
 
 # ------------------------------------------------------------------ small problems
+@pytest.mark.parametrize("accurate", [False, True])
 @pytest.mark.parametrize("m,n,k,N,dtype,opA,opB", [
     (2048, 2048, 2048, 14, np.float64, 0, 0),      # the largest cube the fused launches take
     (1500, 2500, 2000, 16, np.float64, 1, 1),      # A by columns, B by rows
@@ -446,7 +448,7 @@ def test_random_shapes_modes_and_operand_forms_against_the_oracle(oz, oracle):
     (1024, 1000, 4096, 8, np.float32, 0, 0),       # the longest columns; strips of 16
     (1000, 1024, 4095, 9, np.float32, 0, 1),       # both factors by rows
 ])
-def test_small_conversion_equals_the_general_kernels(oz, m, n, k, N, dtype, opA, opB):
+def test_small_conversion_equals_the_general_kernels(oz, m, n, k, N, dtype, opA, opB, accurate):
     """Up to (m + n) k = 2 x 2048^2 the shifts and residues of both factors come from two fused
     launches; every stage and C must equal what the general kernels give, bit for bit (those
     are checked against the oracle at these sizes by the sampled tests)."""
@@ -465,7 +467,7 @@ def test_small_conversion_equals_the_general_kernels(oz, m, n, k, N, dtype, opA,
         for small in (True, False):
             oz.oz2_set_small_conversion(small)
             dC = torch.full((m, n), float("nan"), dtype=dt, device="cuda")
-            fn(opA, opB, False, m, n, k, 1.0, dA, lda, dB, ldb, 0.0, dC, n, N)
+            fn(opA, opB, accurate, m, n, k, 1.0, dA, lda, dB, ldb, 0.0, dC, n, N)
             torch.cuda.synchronize()
             got[small] = [dC] + [oz.stage_tensor(st) for st in (b.OZ2_STAGE_SHIFT_A, b.OZ2_STAGE_SHIFT_B,
                                                                  b.OZ2_STAGE_RES_A, b.OZ2_STAGE_RES_B)]

@@ -166,8 +166,8 @@ def test_stage_parity_accurate_mode(oz, oracle, m, n, k, N, phi, dtype):
     A, B = S.gemm_inputs(m, n, k, phi, seed=30 + N, dtype=dtype)
     is_double = dtype == np.float64
     ref = oracle.gemm(A, B, N, is_double=is_double, accurate=True)
-    got = gpu_gemm(oz, A, B, N, accurate=True)
-    assert_parity(got, ref, is_double)
+    assert_parity(gpu_gemm(oz, A, B, N, accurate=True), ref, is_double)
+    assert_parity(gpu_gemm(oz, A, B, N, accurate=True, small_conversion=False), ref, is_double)
 
 
 def test_accurate_mode_degenerate_inputs(oz, oracle):
@@ -178,8 +178,13 @@ def test_accurate_mode_degenerate_inputs(oz, oracle):
     Cin = S.matrix(40, 50, 0.5, seed=2)
     assert_parity(gpu_gemm(oz, A, B, 16, 0.5, 2.0, Cin.copy(), lda=77, ldb=64, accurate=True),
                   oracle.gemm(A, B, 16, 0.5, 2.0, Cin, accurate=True), True)
+    assert_parity(gpu_gemm(oz, A, B, 16, 0.5, 2.0, Cin.copy(), lda=77, ldb=64, accurate=True,
+                           small_conversion=False),
+                  oracle.gemm(A, B, 16, 0.5, 2.0, Cin, accurate=True), True)
     Zb = np.zeros((60, 50))                      # B = 0: every maximum of Cbar is 0
     assert_parity(gpu_gemm(oz, A, Zb, 14, accurate=True), oracle.gemm(A, Zb, 14, accurate=True), True)
+    assert_parity(gpu_gemm(oz, A, Zb, 14, accurate=True, small_conversion=False),
+                  oracle.gemm(A, Zb, 14, accurate=True), True)
 
 
 def test_alpha_beta_and_leading_dimensions(oz, oracle):
