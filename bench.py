@@ -400,13 +400,21 @@ def sweep_accuracy(oz, torch, args) -> int:
                     trows = torch.from_numpy(rows).cuda()
                     hi, lo, ab = O.dd_rows(A.astype(np.float64), B.astype(np.float64), rows)
                     err = lambda c: float(np.max(np.abs((c.astype(np.float64) - hi) - lo) / ab))
+                    # second measure: the error relative to the entry itself, |c - AB| / |AB|
+                    ref_abs = np.abs(hi + lo)
+                    rel = lambda c: float(np.max(np.abs((c.astype(np.float64) - hi) - lo)
+                                                 / np.where(ref_abs == 0, 1.0, ref_abs)))
+                    native = torch.mm(dA, dB)[trows].cpu().numpy()
                     rec = {"dtype": "f64" if is_double else "f32", "m": m, "n": n, "k": k, "phi": phi,
                            "measure": "max |c - dd(AB)| / (|A||B|) on 16 rows",
-                           "native": err(torch.mm(dA, dB)[trows].cpu().numpy()), "fast": {}, "accurate": {}}
+                           "measure_rel": "max |c - dd(AB)| / |dd(AB)| on the same rows",
+                           "native": err(native), "fast": {}, "accurate": {},
+                           "native_rel": rel(native), "fast_rel": {}, "accurate_rel": {}}
                     for N in moduli:
                         for accurate in (False, True):
-                            c = oz.matmul(dA, dB, N, accurate=accurate)
-                            rec["accurate" if accurate else "fast"][str(N)] = err(c[trows].cpu().numpy())
+                            c = oz.matmul(dA, dB, N, accurate=accurate)[trows].cpu().numpy()
+                            rec["accurate" if accurate else "fast"][str(N)] = err(c)
+                            rec["accurate_rel" if accurate else "fast_rel"][str(N)] = rel(c)
                     log(json.dumps(rec))
                     f.write(json.dumps(rec) + "\n")
     print(json.dumps({"sweep": "accuracy", "file": path}), flush=True)
