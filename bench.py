@@ -316,7 +316,7 @@ def sweep_general(oz, torch, args) -> int:
         for frac in (4, 16):
             if m // 256 < frac:
                 continue
-            limit = least - max(N, 4) * 256 * 256 + max(N, 4) * (m * n // frac)
+            limit = least - N * 256 * 256 + N * (m * n // frac)
             oz.oz2_set_workspace_limit(limit)
             oz.oz2_release()
             dC.zero_()

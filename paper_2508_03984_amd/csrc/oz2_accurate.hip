@@ -51,44 +51,6 @@ __global__ __launch_bounds__(256) void k_preshift(const unsigned long long *__re
     cmax[i] = 0;
 }
 
-// Maxima of one panel of Cbar in one launch.  Workgroups [0, m): rmax[i] = max(rmax[i],
-// max_j Cbar[i][j] over j < n), one workgroup per row.  The others: cmax[j] = max(cmax[j],
-// max_i Cbar[i][j]) over a block of 256 rows x 256 columns each.  Entries are >= 0 and the
-// maxima start at 0, so the integer atomic maximum over several panels is the maximum over the
-// whole row or column whatever the order.
-__global__ __launch_bounds__(256) void k_cbar_maxima(const int32_t *__restrict__ Cbar, int64_t ld,
-                                                     int64_t m, int64_t n, int *rmax, int *cmax) {
-    if ((int64_t)blockIdx.x < m) {
-        __shared__ int part[4];
-        const int32_t *x = Cbar + (int64_t)blockIdx.x * ld;
-        int mx = 0;
-        for (int64_t j = threadIdx.x; j < n; j += 256) mx = x[j] > mx ? x[j] : mx;
-        for (int off = 32; off > 0; off >>= 1) {
-            int o = __shfl_xor(mx, off, 64);
-            mx = o > mx ? o : mx;
-        }
-        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mx;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            for (int w = 1; w < 4; ++w) mx = part[w] > mx ? part[w] : mx;
-            if (mx) atomicMax(&rmax[blockIdx.x], mx);
-        }
-        return;
-    }
-    const int64_t blk = (int64_t)blockIdx.x - m, strips = (n + 255) / 256;
-    const int64_t j = (blk % strips) * 256 + threadIdx.x;
-    if (j >= n) return;
-    const int64_t i0 = (blk / strips) * 256;
-    const int64_t i1 = i0 + 256 < m ? i0 + 256 : m;
-    int mx = 0;
-#pragma unroll 8
-    for (int64_t i = i0; i < i1; ++i) {
-        int v = Cbar[i * ld + j];
-        mx = v > mx ? v : mx;
-    }
-    if (mx) atomicMax(&cmax[j], mx);
-}
-
 // t[v] = (5 - e_v) + floor(P'_accu - 0.51 log2 max(c_v, 1)); an all-zero vector gets 0.
 // Entries [0, m) are the rows of A, [m, count) the columns of B (the arrays adjoin).
 __global__ __launch_bounds__(256) void k_accu_finish(const unsigned long long *__restrict__ maxbits,
@@ -161,15 +123,10 @@ hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous
                           : launch_magnitudes_cols<T>(B, ldb, k, n, s.preB, Bbar, Np, Kp, stream);
 }
 
-hipError_t launch_accurate_maxima(const int32_t *Cbar, int64_t ld, int64_t row0, int64_t rows,
-                                  int64_t col0, int64_t cols, int64_t m, int64_t n, void *scratch,
-                                  hipStream_t stream) {
+void accurate_maxima(void *scratch, int64_t m, int64_t n, int **row_max, int **col_max) {
     const Scratch s = carve(scratch, m, n);
-    if (rows <= 0 || cols <= 0) return hipSuccess;
-    const int64_t blocks = rows + ((cols + 255) / 256) * ((rows + 255) / 256);
-    hipLaunchKernelGGL(k_cbar_maxima, dim3((unsigned)blocks), dim3(256), 0, stream, Cbar, ld, rows, cols,
-                       s.crow + row0, s.ccol + col0);
-    return hipGetLastError();
+    *row_max = s.crow;
+    *col_max = s.ccol;
 }
 
 hipError_t launch_accurate_finish(int64_t m, int64_t n, const ShiftArgs &sa, void *scratch,

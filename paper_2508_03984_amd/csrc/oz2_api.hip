@@ -30,9 +30,8 @@ struct Layout {
     size_t prod_whole, prod_min;           // product part: all of C at once / one 256 x 256 panel
 };
 
-// Bytes of product workspace per entry of C: N planes of uint8, or of int32 (diagnostic form);
-// accurate mode keeps its int32 Cbar in the same place, hence at least one int32 plane.
-inline size_t bytes_per_entry(int N, bool prod_u8) { return std::max<size_t>((size_t)N * (prod_u8 ? 1 : 4), 4); }
+// Bytes of product workspace per entry of C: N planes of uint8, or of int32 (diagnostic form).
+inline size_t bytes_per_entry(int N, bool prod_u8) { return (size_t)N * (prod_u8 ? 1 : 4); }
 
 Layout make_layout(int64_t m, int64_t n, int64_t k, int N, bool prod_u8, bool with_operands = true) {
     Layout L{};
@@ -358,19 +357,19 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     const bool small = g.small_conversion && small_conversion_applies(m, n, k);
     if (oz2_status st = mark(0, stream)) return st;
     if (accurate) {
-        // Section 4.2, accurate mode: 7-bit matrices into slice 0, Cbar panel by panel into the
-        // product part, of which only the row and column maxima are kept.
+        // Section 4.2, accurate mode: 7-bit matrices into slice 0; of Cbar, computed panel by
+        // panel, only the row and column maxima are kept (it is never stored).
         OZ2_TRY(launch_accurate_prescale<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, scratch, rA, rB, L.Mp,
                                             L.Np, L.Kp, small, stream));
+        int *row_max = nullptr, *col_max = nullptr;
+        accurate_maxima(scratch, m, n, &row_max, &col_max);
         for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
             for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
                 const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);
                 const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
-                OZ2_TRY(launch_int8_gemm(rA, rB, prod, 1, L.Mp, L.Np, L.Kp, 0, L.Kp, false, false, nullptr,
-                                         stream, &pn));
-                OZ2_TRY(launch_accurate_maxima(static_cast<const int32_t *>(prod), cols, row0,
-                                               std::min(m - row0, rows), col0, std::min(n - col0, cols), m,
-                                               n, scratch, stream));
+                OZ2_TRY(launch_int8_gemm_maxima(rA, rB, L.Mp, L.Np, L.Kp, pn, std::min(m - row0, rows),
+                                                std::min(n - col0, cols), row_max + row0, col_max + col0,
+                                                stream));
             }
         OZ2_TRY(launch_accurate_finish(m, n, make_accu_shift_args(tab), scratch, tA, tB, stream));
     } else if (small) {

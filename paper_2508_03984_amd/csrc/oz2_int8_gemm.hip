@@ -31,6 +31,8 @@
 namespace oz2 {
 namespace {
 
+constexpr int64_t kMaxExactK = (int64_t)1 << 17;   // Section 4.3: no INT32 overflow up to here
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
@@ -82,7 +84,14 @@ __device__ inline void map_tile(const TileMap &tm, int id, int &s, int &tr, int 
 //   kOutI32Fold  int32: mod(old, p_s) + mod(C'_s, p_s)   (a further K range of a k > 2^17 product)
 //   kOutU8       U_s = mod(C'_s, p_s) as uint8 -- the form the accumulation kernel wants
 //   kOutU8Fold   uint8: (old + mod(C'_s, p_s)) mod p_s
-enum { kOutI32 = 0, kOutI32Fold = 1, kOutU8 = 2, kOutU8Fold = 3 };
+//   kOutMax      nothing of the product itself: only its row and column maxima, folded into
+//                two int arrays with atomic maxima (accurate mode of Section 4.2, where the
+//                product Cbar = Abar * Bbar of the 7-bit matrices is needed for nothing else).
+//                The kernel arguments then mean: C = the row maxima of the panel's rows,
+//                C + c_plane (in ints) = the column maxima of its columns, c_ld = the number of
+//                valid rows of the panel in its low and of valid columns in its high 32 bits.
+//                (k_int8_gemm only.)
+enum { kOutI32 = 0, kOutI32Fold = 1, kOutU8 = 2, kOutU8Fold = 3, kOutMax = 4 };
 
 struct GemmMods {                       // moduli of the slices and their mulhi multipliers
     int32_t p[kMaxModuli];
@@ -231,6 +240,44 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
     // the L2 fetch the lines it merges them into.)
     // (the mulhi form: an FP64 floor/fma version of this reduction measured 1.1 ms slower
     // per launch at 16 x 16384^3)
+    if (OUT == kOutMax) {
+        // Entries are sums of products of non-negative 7-bit numbers (k <= 2^17: below 2^29), the
+        // maxima start at 0 and zero entries (all the padding) are skipped, so integer atomic
+        // maxima give the exact result whatever the order.  A lane holds, per 32 x 32 tile, 16
+        // columns of one row: the row maximum is completed by the lane 32 further on, a column
+        // maximum by the 32 lanes of the same half-wavefront.
+        int *rmax = static_cast<int *>(C);
+        int *cmax = rmax + c_plane;
+        const int valid_rows = (int)(c_ld & 0xffffffff), valid_cols = (int)(c_ld >> 32);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int v = 0;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v = acc[i][j][r] > v ? acc[i][j][r] : v;
+            const int o = __shfl_xor(v, 32, 64);
+            v = o > v ? o : v;
+            const int row = (int)bm + wm * 32 * TM + i * 32 + lrow;
+            if (lhalf == 0 && v > 0 && row < valid_rows) atomicMax(&rmax[row], v);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int v = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) v = acc[i][j][r] > v ? acc[i][j][r] : v;
+#pragma unroll
+                for (int off = 1; off < 32; off <<= 1) {
+                    const int o = __shfl_xor(v, off, 64);
+                    v = o > v ? o : v;
+                }
+                const int col = (int)bn + wn * 32 * TN + j * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                if (lrow == 0 && v > 0 && col < valid_cols) atomicMax(&cmax[col], v);
+            }
+        return;
+    }
     const int p = mods.p[s], pv = mods.pinv_prime[s];
     const int64_t c_off = (int64_t)s * c_plane + bm * c_ld + bn;   // C: [slice][row][column]
     if (OUT == kOutU8) {
@@ -634,6 +681,24 @@ hipError_t launch_out(const int8_t *A, const int8_t *B, void *C, int batch, int6
 }
 
 }  // namespace
+
+hipError_t launch_int8_gemm_maxima(const int8_t *A, const int8_t *B, int64_t Mp, int64_t Np, int64_t Kp,
+                                   const GemmPanel &pn, int64_t valid_rows, int64_t valid_cols,
+                                   int *row_max, int *col_max, hipStream_t stream) {
+    if (pn.row0 < 0 || pn.col0 < 0 || pn.rows < kPadMN || pn.cols < kPadMN || pn.row0 % kPadMN ||
+        pn.col0 % kPadMN || pn.rows % kPadMN || pn.cols % kPadMN || pn.row0 + pn.rows > Mp ||
+        pn.col0 + pn.cols > Np || valid_rows < 0 || valid_cols < 0 || valid_rows > pn.rows ||
+        valid_cols > pn.cols || Kp > kMaxExactK || !row_max || !col_max)
+        return hipErrorInvalidValue;
+    // the kernel's view of these arguments: see kOutMax
+    GemmPanel q = pn;
+    q.c_ld = valid_rows | (valid_cols << 32);
+    q.c_plane = col_max - row_max;
+    const GemmMods none{};
+    if (pn.rows * pn.cols < (int64_t)256 * 256 * 128)        // as in launch_out
+        return launch<2, 2, 2, 2, 64, 4, kOutMax>(A, B, row_max, 1, Mp, Np, Kp, 0, Kp, q, none, stream);
+    return launch<2, 4, 4, 2, 64, 4, kOutMax>(A, B, row_max, 1, Mp, Np, Kp, 0, Kp, q, none, stream);
+}
 
 hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp,
                             int64_t Np, int64_t Kp, int64_t k_begin, int64_t k_len, bool as_u8,

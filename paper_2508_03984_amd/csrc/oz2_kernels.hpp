@@ -122,8 +122,7 @@ hipError_t launch_small_magnitudes(const T *A, int64_t lda, bool a_k_contiguous,
 //   launch_accurate_prescale   max|.| per row of A / column of B, mu' = 2^(5-e), nu', and
 //                              Abar = ceil(mu' |A|), Bbar = ceil(|B| nu') as int8; clears the
 //                              maxima of Cbar.  small: with the fused launches for small problems
-//   (the caller then runs launch_int8_gemm with batch 1 to get Cbar = Abar * Bbar)
-//   launch_accurate_maxima     row / column maxima of Cbar over its m x n part
+//   (the caller then runs launch_int8_gemm_maxima over the panels of Cbar = Abar * Bbar)
 //   launch_accurate_finish     t = (5 - e) + floor(P'_accu - 0.51 log2 max), zero vectors -> 0
 size_t accurate_scratch_bytes(int64_t m, int64_t n);
 template <typename T>
@@ -131,12 +130,10 @@ hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous
                                     int64_t ldb, bool b_k_contiguous, int64_t m, int64_t n,
                                     int64_t k, void *scratch, int8_t *Abar, int8_t *Bbar,
                                     int64_t Mp, int64_t Np, int64_t Kp, bool small, hipStream_t stream);
-// Maxima of Cbar, panel by panel: _maxima folds in the (rows x cols) valid part of one panel of
-// Cbar (leading dimension ld) whose top-left entry is (row0, col0) of the whole product; _finish
-// turns them into the shifts.
-hipError_t launch_accurate_maxima(const int32_t *Cbar, int64_t ld, int64_t row0, int64_t rows,
-                                  int64_t col0, int64_t cols, int64_t m, int64_t n, void *scratch,
-                                  hipStream_t stream);
+// Where the maxima of Cbar live in `scratch` (m row maxima, then n column maxima; the caller
+// folds every panel of Cbar into them with launch_int8_gemm_maxima); _finish turns them into the
+// shifts.
+void accurate_maxima(void *scratch, int64_t m, int64_t n, int **row_max, int **col_max);
 hipError_t launch_accurate_finish(int64_t m, int64_t n, const ShiftArgs &sa, void *scratch,
                                   int32_t *tA, int32_t *tB, hipStream_t stream);
 
@@ -177,6 +174,15 @@ hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch
                             int64_t Np, int64_t Kp, int64_t k_begin, int64_t k_len, bool as_u8,
                             bool fold, const ModArgs *ma, hipStream_t stream,
                             const GemmPanel *panel = nullptr);
+
+// Accurate mode (Section 4.2): the contraction of slice 0 of A and B over all of K for one panel
+// (as above), of which only the maxima are kept: row_max[i] = max(row_max[i], max_j c_ij) for
+// the panel's rows i < valid_rows, col_max[j] likewise for its columns j < valid_cols (entries
+// are sums of products of non-negative numbers; Kp <= 2^17).  Both arrays are indexed from the
+// panel's first row / column and are updated with integer atomic maxima.
+hipError_t launch_int8_gemm_maxima(const int8_t *A, const int8_t *B, int64_t Mp, int64_t Np, int64_t Kp,
+                                   const GemmPanel &panel, int64_t valid_rows, int64_t valid_cols,
+                                   int *row_max, int *col_max, hipStream_t stream);
 
 // Algorithm 1 lines 7-12 and the alpha/beta update, fused:
 // C[i][j] = alpha * ldexp(C''(i,j), -(tA[i]+tB[j])) + beta * C[i][j]   (OutT = double or float)

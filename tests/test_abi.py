@@ -161,7 +161,7 @@ def test_panel_plan_covers_c_within_the_workspace(oz, m, n, k, N):
     need = oz.oz2_workspace_bytes(m, n, k, N)
     least = oz.oz2_workspace_min_bytes(m, n, k, N)
     Mp, Np = -(-m // 256) * 256, -(-n // 256) * 256
-    per = max(N, 4)
+    per = N
     fixed = need - Mp * Np * per
     assert fixed == least - 256 * 256 * per and fixed >= N * (Mp + Np) * k
     assert oz.oz2_plan_panels(m, n, k, N, need) == (Mp, Np, 1)

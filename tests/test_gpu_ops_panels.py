@@ -145,7 +145,7 @@ def test_panelled_product_is_bit_identical(oz, oracle, dtype, N, accurate):
     assert oz.oz2_last_panels() == (768, 1280, 1)
     need = oz.oz2_workspace_bytes(m, n, k, N, is_double)
     least = oz.oz2_workspace_min_bytes(m, n, k, N, is_double)
-    per_entry = max(N, 4)
+    per_entry = N
     seen = set()
     try:
         for entries in (256 * 256, 2 * 256 * 256, 512 * 512 + 7, 768 * 512, 768 * 1024 + 100):
