@@ -175,8 +175,8 @@ oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right,
  * for each (row panel, column panel) the INT8 GEMMs and the accumulation of that panel
  * only.  The result is bit-identical.  oz2_workspace_min_bytes is the smallest workspace
  * such a call can run in (one 256 x 256 panel); below it the call returns OZ2_WORKSPACE.
- * Accurate mode computes its Cbar with the same panels and never stores it (only its row and
- * column maxima are kept).  oz2_plan_panels says, without touching the GPU, how a product of this
+ * Accurate mode never stores its Cbar (only the row and column maxima are kept), so it needs
+ * no workspace of its own.  oz2_plan_panels says, without touching the GPU, how a product of this
  * shape is cut in a workspace of `workspace_bytes` (host pointers, may be NULL: rows and
  * columns of a panel, multiples of 256, the last panels of a row or column may be smaller;
  * and the number of panels); oz2_last_panels reports the same for the most recent product

@@ -357,20 +357,14 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     const bool small = g.small_conversion && small_conversion_applies(m, n, k);
     if (oz2_status st = mark(0, stream)) return st;
     if (accurate) {
-        // Section 4.2, accurate mode: 7-bit matrices into slice 0; of Cbar, computed panel by
-        // panel, only the row and column maxima are kept (it is never stored).
+        // Section 4.2, accurate mode: 7-bit matrices into slice 0; of Cbar only the row and
+        // column maxima are kept (it is never stored).
         OZ2_TRY(launch_accurate_prescale<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, scratch, rA, rB, L.Mp,
                                             L.Np, L.Kp, small, stream));
         int *row_max = nullptr, *col_max = nullptr;
         accurate_maxima(scratch, m, n, &row_max, &col_max);
-        for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
-            for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
-                const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);
-                const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
-                OZ2_TRY(launch_int8_gemm_maxima(rA, rB, L.Mp, L.Np, L.Kp, pn, std::min(m - row0, rows),
-                                                std::min(n - col0, cols), row_max + row0, col_max + col0,
-                                                stream));
-            }
+        const GemmPanel all{0, L.Mp, 0, L.Np, L.Np, L.Mp * L.Np};      // nothing is stored: no panels needed
+        OZ2_TRY(launch_int8_gemm_maxima(rA, rB, L.Mp, L.Np, L.Kp, all, m, n, row_max, col_max, stream));
         OZ2_TRY(launch_accurate_finish(m, n, make_accu_shift_args(tab), scratch, tA, tB, stream));
     } else if (small) {
         OZ2_TRY(launch_small_shifts<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, sa, tA, tB, stream));

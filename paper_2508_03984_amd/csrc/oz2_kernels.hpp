@@ -122,7 +122,7 @@ hipError_t launch_small_magnitudes(const T *A, int64_t lda, bool a_k_contiguous,
 //   launch_accurate_prescale   max|.| per row of A / column of B, mu' = 2^(5-e), nu', and
 //                              Abar = ceil(mu' |A|), Bbar = ceil(|B| nu') as int8; clears the
 //                              maxima of Cbar.  small: with the fused launches for small problems
-//   (the caller then runs launch_int8_gemm_maxima over the panels of Cbar = Abar * Bbar)
+//   (the caller then runs launch_int8_gemm_maxima on Cbar = Abar * Bbar)
 //   launch_accurate_finish     t = (5 - e) + floor(P'_accu - 0.51 log2 max), zero vectors -> 0
 size_t accurate_scratch_bytes(int64_t m, int64_t n);
 template <typename T>
@@ -131,8 +131,7 @@ hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous
                                     int64_t k, void *scratch, int8_t *Abar, int8_t *Bbar,
                                     int64_t Mp, int64_t Np, int64_t Kp, bool small, hipStream_t stream);
 // Where the maxima of Cbar live in `scratch` (m row maxima, then n column maxima; the caller
-// folds every panel of Cbar into them with launch_int8_gemm_maxima); _finish turns them into the
-// shifts.
+// fills them with launch_int8_gemm_maxima); _finish turns them into the shifts.
 void accurate_maxima(void *scratch, int64_t m, int64_t n, int **row_max, int **col_max);
 hipError_t launch_accurate_finish(int64_t m, int64_t n, const ShiftArgs &sa, void *scratch,
                                   int32_t *tA, int32_t *tB, hipStream_t stream);
