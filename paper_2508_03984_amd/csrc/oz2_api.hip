@@ -111,6 +111,7 @@ struct State {
     hipStream_t aux = nullptr;
     std::vector<hipEvent_t> sync_ev, time_ev;
     int64_t last_overlapped_panels = 0;    // > 0: the last call ran overlapped, with this many panels
+    int res_device = -1;                   // device the events and the second stream belong to
 };
 State g;
 
@@ -132,10 +133,14 @@ oz2_status ensure_workspace(size_t need_whole, size_t need_min, size_t *have) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return OZ2_HIP_ERROR;
     if (!g.ws || g.ws_bytes < want || g.ws_device != dev) {   // the buffer lives on the current device
-        if (g.ws) {
-            if (hipDeviceSynchronize() != hipSuccess) return OZ2_HIP_ERROR;
+        if (g.ws) {                                           // wait on the device that may still use it
+            const bool elsewhere = g.ws_device != dev;
+            if (elsewhere && hipSetDevice(g.ws_device) != hipSuccess) return OZ2_HIP_ERROR;
+            const hipError_t e = hipDeviceSynchronize();
             (void)hipFree(g.ws);
             g.ws = nullptr; g.ws_bytes = 0;
+            if (elsewhere && hipSetDevice(dev) != hipSuccess) return OZ2_HIP_ERROR;
+            if (e != hipSuccess) return OZ2_HIP_ERROR;
         }
         void *p = nullptr;
         if (hipMalloc(&p, want) != hipSuccess) { (void)hipGetLastError(); return OZ2_WORKSPACE; }
@@ -146,6 +151,27 @@ oz2_status ensure_workspace(size_t need_whole, size_t need_min, size_t *have) {
 }
 
 #define OZ2_TRY(expr) do { if ((expr) != hipSuccess) return OZ2_HIP_ERROR; } while (0)
+
+// Events and the second stream belong to one device: a call made with another device current
+// drops them (they are created again when needed).
+void drop_device_resources() {
+    for (auto &e : g.ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
+    for (auto &e : g.sync_ev) (void)hipEventDestroy(e);
+    for (auto &e : g.time_ev) (void)hipEventDestroy(e);
+    g.sync_ev.clear(); g.time_ev.clear();
+    if (g.aux) { (void)hipStreamDestroy(g.aux); g.aux = nullptr; }
+    g.ev_recorded = false; g.last_overlapped_panels = 0;
+}
+
+oz2_status bind_device_resources() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return OZ2_HIP_ERROR;
+    if (g.res_device != dev) {
+        drop_device_resources();
+        g.res_device = dev;
+    }
+    return OZ2_OK;
+}
 
 oz2_status mark(int i, hipStream_t stream) {
     if (!g.profiling) return OZ2_OK;
@@ -314,6 +340,7 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     if (!A || !B || lda < (a_kc ? k : m) || ldb < (b_kc ? k : n)) return OZ2_INVALID_ARG;
 
     std::lock_guard<std::mutex> lock(g.mu);
+    if (oz2_status st = bind_device_resources()) return st;
     const bool is_double = sizeof(T) == 8;
     const Table &tab = table(N, is_double);
     const ModArgs ma = make_mod_args(tab);
@@ -450,6 +477,7 @@ oz2_status prepared_impl(const oz2_operand *l, const oz2_operand *r, double alph
         l->is_double != is_double || r->is_double != is_double || !C || ldc < r->rows)
         return OZ2_INVALID_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
+    if (oz2_status st = bind_device_resources()) return st;
     const ModArgs ma = make_mod_args(table(l->N, is_double));
     const Layout L = make_layout(l->rows, r->rows, l->k, l->N, !g.int32_products, false);
     size_t have = 0;
@@ -602,12 +630,8 @@ void oz2_release(void) {
         (void)hipFree(g.ws);
     }
     g.ws = nullptr; g.ws_bytes = 0; g.ws_owned = false; g.have_last = g.have_last_prod = false;
-    for (auto &e : g.ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
-    for (auto &e : g.sync_ev) (void)hipEventDestroy(e);
-    for (auto &e : g.time_ev) (void)hipEventDestroy(e);
-    g.sync_ev.clear(); g.time_ev.clear();
-    if (g.aux) { (void)hipStreamDestroy(g.aux); g.aux = nullptr; }
-    g.ev_recorded = false; g.last_overlapped_panels = 0;
+    drop_device_resources();
+    g.res_device = -1;
 }
 
 oz2_status oz2_constants(int num_moduli, int is_double, int32_t *p, uint32_t *pinv_prime,

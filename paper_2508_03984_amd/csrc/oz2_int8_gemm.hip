@@ -612,13 +612,15 @@ hipError_t launch_persistent(const int8_t *A, const int8_t *B, void *C, int batc
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
     static_assert(lds_bytes > 80 * 1024, "one workgroup per compute unit is assumed");
-    static bool attr_set = false;
-    if (!attr_set) {
+    static int attr_device = -1;                             // the attribute is per device
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    if (attr_device != dev) {
         hipError_t e = hipFuncSetAttribute(
             reinterpret_cast<const void *>(&k_int8_gemm_persistent<WM, WN, TM, TN, BK, STAGES, OUT>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_device = dev;
     }
     TileMap tm;
     tm.tiles_m = (int)(pn.rows / BM);
@@ -642,13 +644,15 @@ hipError_t launch(const int8_t *A, const int8_t *B, void *C, int batch, int64_t 
                   const GemmMods &mods, hipStream_t stream) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static int attr_device = -1;                             // the attribute is per device
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev)) return e;
+    if (attr_device != dev) {
         hipError_t e = hipFuncSetAttribute(
             reinterpret_cast<const void *>(&k_int8_gemm<WM, WN, TM, TN, BK, STAGES, OUT>),
             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_device = dev;
     }
     TileMap tm;
     tm.tiles_m = (int)(pn.rows / BM);
