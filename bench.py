@@ -422,6 +422,101 @@ def sweep_accuracy(oz, torch, args) -> int:
     return 0
 
 
+def sweep_rank_k(oz, torch, args) -> int:
+    """Short contractions, the shape of a blocked factorisation's trailing update (the use the
+    paper names for N = 14, 15): C <- C - A B with m = n large and k = 512 ... 4096, against the
+    native GEMM doing the same update.  One JSON line per shape goes to --out."""
+    import numpy as np
+    import synth_inputs as S
+    N = args.moduli if args.moduli != 16 else 15
+    path = args.out or "sweep_rank_k.jsonl"
+    if os.path.dirname(path):
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        for (m, n, k) in ((16384, 16384, 512), (16384, 16384, 1024), (16384, 16384, 2048),
+                          (16384, 16384, 4096), (32768, 32768, 1024)):
+            A, B = S.gemm_inputs(m, n, k, args.phi, seed=0)
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+            dC = torch.zeros((m, n), dtype=torch.float64, device="cuda")
+            call = lambda: oz.oz2_dgemm(m, n, k, -1.0, dA, k, dB, n, 1.0, dC, n, N)
+            for _ in range(args.warmup):
+                call()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                call()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / args.steps
+            oz.oz2_set_profiling(True)
+            stage_ms = np.zeros(4)
+            for _ in range(args.steps):
+                call()
+                stage_ms += np.array(oz.oz2_last_stage_times_ms())
+            oz.oz2_set_profiling(False)
+            dC.addmm_(dA, dB, beta=1.0, alpha=-1.0)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(3):
+                dC.addmm_(dA, dB, beta=1.0, alpha=-1.0)
+            torch.cuda.synchronize()
+            nat = (time.perf_counter() - t1) / 3
+            rec = {"m": m, "n": n, "k": k, "num_moduli": N, "alpha": -1.0, "beta": 1.0, "ms": 1e3 * dt,
+                   "emulated_tflops": 2.0 * m * n * k / dt / 1e12,
+                   "stage_ms": (stage_ms / args.steps).round(3).tolist(), "native_ms": 1e3 * nat,
+                   "native_tflops": 2.0 * m * n * k / nat / 1e12}
+            log(json.dumps(rec))
+            f.write(json.dumps(rec) + "\n")
+            del dA, dB, dC
+    print(json.dumps({"sweep": "rank_k", "file": path}), flush=True)
+    oz.oz2_release()
+    return 0
+
+
+def sweep_overlap(oz, torch, args) -> int:
+    """The default form of a call (conversion of later panels on a second stream where the
+    rule allows it) against the single-stream form, on the same device and buffers, in turns.
+    One JSON line per workload goes to --out."""
+    import numpy as np
+    import synth_inputs as S
+    path = args.out or "sweep_overlap.jsonl"
+    if os.path.dirname(path):
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+    cases = [(16384, 16384, 16384, 16, True, False), (16384, 16384, 16384, 16, True, True),
+             (16384, 16384, 16384, 8, False, False), (8192, 8192, 65536, 18, True, False),
+             (8192, 8192, 8192, 16, True, False), (16384, 16384, 4096, 15, True, False)]
+    with open(path, "w") as f:
+        for (m, n, k, N, is_double, accurate) in cases:
+            A, B = S.gemm_inputs(m, n, k, args.phi, seed=0, dtype=np.float64 if is_double else np.float32)
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+            dC = torch.empty((m, n), dtype=dA.dtype, device="cuda")
+            call = lambda: oz.matmul(dA, dB, N, out=dC, accurate=accurate)
+            ms = {False: [], True: []}
+            try:
+                for _ in range(2):                         # in turns, so that drift hits both alike
+                    for on in (False, True):
+                        oz.oz2_set_overlap(on)
+                        for _ in range(args.warmup):
+                            call()
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        for _ in range(args.steps):
+                            call()
+                        torch.cuda.synchronize()
+                        ms[on].append(1e3 * (time.perf_counter() - t0) / args.steps)
+            finally:
+                oz.oz2_set_overlap(True)
+            call()
+            rec = {"m": m, "n": n, "k": k, "num_moduli": N, "dtype": "f64" if is_double else "f32",
+                   "mode": "accurate" if accurate else "fast", "single_stream_ms": min(ms[False]),
+                   "default_ms": min(ms[True]), "panels_of_the_default_form": list(oz.oz2_last_panels())}
+            log(json.dumps(rec))
+            f.write(json.dumps(rec) + "\n")
+            del dA, dB, dC
+    print(json.dumps({"sweep": "overlap", "file": path}), flush=True)
+    oz.oz2_release()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -442,7 +537,7 @@ def main() -> int:
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
                          "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
                          "counters); both print a reduced JSON line")
-    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general", "small", "accuracy"], default=None,
+    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general", "small", "accuracy", "rank_k", "overlap"], default=None,
                     help="time a whole configuration of the benchmark set over its moduli counts; "
                          "one JSON line per case goes to --out")
     ap.add_argument("--out", default=None, help="file for --sweep (default: sweep_<name>.jsonl)")
@@ -475,6 +570,10 @@ def main() -> int:
         return sweep_small(oz, torch, args)
     if args.sweep == "accuracy":
         return sweep_accuracy(oz, torch, args)
+    if args.sweep == "rank_k":
+        return sweep_rank_k(oz, torch, args)
+    if args.sweep == "overlap":
+        return sweep_overlap(oz, torch, args)
     if args.sweep:
         return sweep(oz, torch, args.sweep, args)
     if args.stage == "int8_gemm":
