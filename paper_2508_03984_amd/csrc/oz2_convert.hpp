@@ -28,7 +28,7 @@ __device__ inline uint64_t wave_sum(uint64_t v) {
 // symmetric residue modulo p comes from rounds of  y <- fma(-rint(y * (1/p)), p, y),
 // the reduction of Section 4.2 kept in FP64 throughout (FP64 and FP32 FMA run at the
 // same rate on this chip, so there is nothing to gain from dropping to FP32):
-//   round 1 is exact (the difference is an integer below 2^26 in magnitude) and leaves
+//   the first round is exact (the difference is an integer below 2^26 in magnitude) and leaves
 //   |y| <= p/2 + 2^-52 |x'|;  for |x'| < 2^46 the quotient estimate is within 2^-13 of
 //   x'/p, closer than any integer/p can be to a half-integer for odd p, so rint returns
 //   round(x'/p) and y is already the residue in [-(p-1)/2, (p-1)/2];
