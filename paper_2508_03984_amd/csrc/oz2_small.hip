@@ -1,4 +1,4 @@
-// Conversion kernels for SMALL problems (Algorithm 1 lines 1-5, fast mode of Section 4.2).
+// Conversion kernels for SMALL problems (Algorithm 1 lines 1-5; the scale vectors of Section 4.2).
 // Below about 2048^3 a call is bound by the latency of its dependent kernel launches, not by
 // memory or arithmetic: the general path takes seven launches for the conversion (row shifts;
 // clear, column maxima, column sums, column finish; residues of A; residues of B).  Here it
@@ -9,6 +9,8 @@
 //                     the operand twice, which at these sizes comes from the caches;
 //   k_small_residues  the row-form and column-form workgroups of the general kernels, dealt
 //                     to the two factors by workgroup index.
+// Accurate mode uses the same two shapes for what precedes its product Cbar: k_small_maxbits
+// (the first half of k_small_shifts) and k_small_residues in its "magnitude" form (Abar, Bbar).
 // Results are identical to the general kernels': the shifts are exact integer functions of
 // the data and the residues use the same device code.
 #include <algorithm>
