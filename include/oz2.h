@@ -119,6 +119,24 @@ oz2_status oz2_sgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t
                         float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream);
 
 /*
+ * The same product for COLUMN-MAJOR callers (the BLAS convention): C <- alpha * op(A) * op(B)
+ * + beta * C with every matrix stored column-major, op(A) m x k and op(B) k x n; the stored A is
+ * m x k (lda >= m) or, transposed, k x m (lda >= k); the stored B is k x n (ldb >= k) or n x k
+ * (ldb >= n); C is m x n (ldc >= m).  A column-major matrix is the row-major storage of its
+ * transpose and C^T = op(B)^T op(A)^T, so this is oz2_*gemm_op with the operands exchanged:
+ * (opA, opB, m, n, A, lda, B, ldb) -> (opB, opA, n, m, B, ldb, A, lda); nothing is copied, and the
+ * result is the one that call gives, bit for bit.
+ */
+oz2_status oz2_dgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                              double alpha, const double *A, int64_t lda, const double *B,
+                              int64_t ldb, double beta, double *C, int64_t ldc, int num_moduli,
+                              hipStream_t stream);
+
+oz2_status oz2_sgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                              float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                              float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream);
+
+/*
  * Prepared operands: Algorithm 1 lines 1-5 (fast mode) for ONE matrix, kept for reuse.
  * In fast mode the scale vector and the residues of A do not depend on B and vice versa,
  * so a matrix that enters many products (the panel of a blocked factorisation, a fixed

@@ -14,4 +14,5 @@ from .binding import (  # noqa: F401
     OZ2_OP_N, OZ2_OP_T, Operand, oz2_dgemm_op, oz2_sgemm_op, oz2_prepare_d, oz2_prepare_s, oz2_operand_free,
     oz2_operand_bytes, oz2_dgemm_prepared, oz2_sgemm_prepared, oz2_workspace_min_bytes,
     oz2_set_workspace_limit, oz2_last_panels, oz2_plan_panels, oz2_set_overlap, oz2_set_small_conversion,
+    oz2_dgemm_colmajor, oz2_sgemm_colmajor,
 )

@@ -23,7 +23,7 @@ EXPORTS = [
     "oz2_dgemm_op", "oz2_sgemm_op", "oz2_prepare_d", "oz2_prepare_s", "oz2_operand_free",
     "oz2_operand_bytes", "oz2_dgemm_prepared", "oz2_sgemm_prepared", "oz2_workspace_min_bytes",
     "oz2_set_workspace_limit", "oz2_last_panels", "oz2_plan_panels", "oz2_set_overlap",
-    "oz2_set_small_conversion",
+    "oz2_set_small_conversion", "oz2_dgemm_colmajor", "oz2_sgemm_colmajor",
 ]
 
 OZ2_OP_N, OZ2_OP_T = 0, 1
@@ -63,6 +63,8 @@ def load():
     lib.oz2_shift_table_accurate.argtypes = [ci, vp, vp, vp, vp]
     lib.oz2_dgemm_op.argtypes = [ci, ci, ci] + lib.oz2_dgemm.argtypes
     lib.oz2_sgemm_op.argtypes = [ci, ci, ci] + lib.oz2_sgemm.argtypes
+    lib.oz2_dgemm_colmajor.argtypes = lib.oz2_dgemm_op.argtypes
+    lib.oz2_sgemm_colmajor.argtypes = lib.oz2_sgemm_op.argtypes
     lib.oz2_prepare_d.argtypes = [ci, ci, i64, i64, vp, i64, ci, vp, C.POINTER(vp)]
     lib.oz2_prepare_s.argtypes = lib.oz2_prepare_d.argtypes
     lib.oz2_operand_free.argtypes = [vp]
@@ -102,7 +104,8 @@ def load():
                  "oz2_shift_table_accurate", "oz2_set_workspace", "oz2_constants", "oz2_shift_table",
                  "oz2_stage_ptr", "oz2_int8_gemm", "oz2_last_stage_times_ms", "oz2_mfma_probe",
                  "oz2_dgemm_op", "oz2_sgemm_op", "oz2_prepare_d", "oz2_prepare_s", "oz2_dgemm_prepared",
-                 "oz2_sgemm_prepared", "oz2_last_panels", "oz2_plan_panels"):
+                 "oz2_sgemm_prepared", "oz2_last_panels", "oz2_plan_panels", "oz2_dgemm_colmajor",
+                 "oz2_sgemm_colmajor"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -182,6 +185,24 @@ def oz2_sgemm_op(opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C_, l
                                _dev(A, torch.float32), lda, _dev(B, torch.float32), ldb, float(beta),
                                _dev(C_, torch.float32), ldc, int(num_moduli), _stream(stream)),
            "oz2_sgemm_op")
+
+
+def oz2_dgemm_colmajor(opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli,
+                       stream=None) -> None:
+    import torch
+    _check(load().oz2_dgemm_colmajor(int(opA), int(opB), int(bool(accurate)), m, n, k, float(alpha),
+                                     _dev(A, torch.float64), lda, _dev(B, torch.float64), ldb, float(beta),
+                                     _dev(C_, torch.float64), ldc, int(num_moduli), _stream(stream)),
+           "oz2_dgemm_colmajor")
+
+
+def oz2_sgemm_colmajor(opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli,
+                       stream=None) -> None:
+    import torch
+    _check(load().oz2_sgemm_colmajor(int(opA), int(opB), int(bool(accurate)), m, n, k, float(alpha),
+                                     _dev(A, torch.float32), lda, _dev(B, torch.float32), ldb, float(beta),
+                                     _dev(C_, torch.float32), ldc, int(num_moduli), _stream(stream)),
+           "oz2_sgemm_colmajor")
 
 
 class Operand:

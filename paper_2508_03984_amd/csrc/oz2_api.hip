@@ -540,6 +540,22 @@ oz2_status oz2_sgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t
                             num_moduli, stream, accurate != 0);
 }
 
+// Column-major callers: C^T = op(B)^T op(A)^T in row-major terms (see include/oz2.h).
+oz2_status oz2_dgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                              double alpha, const double *A, int64_t lda, const double *B,
+                              int64_t ldb, double beta, double *C, int64_t ldc, int num_moduli,
+                              hipStream_t stream) {
+    return gemm_impl<double>(opB, opA, n, m, k, alpha, B, ldb, A, lda, beta, C, ldc, num_moduli, stream,
+                             accurate != 0);
+}
+
+oz2_status oz2_sgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                              float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                              float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream) {
+    return gemm_impl<float>(opB, opA, n, m, k, (double)alpha, B, ldb, A, lda, (double)beta, C, ldc,
+                            num_moduli, stream, accurate != 0);
+}
+
 oz2_status oz2_prepare_d(int side, oz2_op op, int64_t rows, int64_t k, const double *X, int64_t ld,
                          int num_moduli, hipStream_t stream, oz2_operand **out) {
     return prepare_impl<double>(side, op, rows, k, X, ld, num_moduli, stream, out);

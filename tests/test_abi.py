@@ -139,6 +139,13 @@ def test_general_entry_points_check_their_arguments_without_a_gpu(oz):
     assert op(0, 1, 4, 6, 5, 5, 4, 6) == 1                    # B^T is stored 6 x 5: ldb >= 5
     assert op(1, 1, 0, 6, 5, 1, 5, 6) == 0                    # empty: no-op
     assert op(1, 1, 4, 6, 2 ** 17 + 1, 4, 2 ** 17 + 1, 6, acc=1) == 2   # accurate mode: k <= 2^17
+    # column-major form: A (m x k) needs lda >= m, A^T (k x m) lda >= k, C ldc >= m
+    cm = lambda opA, opB, m, n, k, lda, ldb, ldc: lib.oz2_dgemm_colmajor(
+        opA, opB, 0, m, n, k, 1.0, one, lda, one, ldb, 0.0, one, ldc, 14, null)
+    assert cm(0, 0, 4, 6, 5, 3, 5, 4) == 1 and cm(1, 0, 4, 6, 5, 4, 5, 4) == 1      # lda
+    assert cm(0, 0, 4, 6, 5, 4, 4, 4) == 1 and cm(0, 1, 4, 6, 5, 4, 5, 4) == 1      # ldb
+    assert cm(0, 0, 4, 6, 5, 4, 5, 3) == 1 and cm(2, 0, 4, 6, 5, 4, 5, 4) == 1      # ldc, op
+    assert cm(0, 0, 0, 6, 5, 1, 5, 1) == 0                                          # empty: no-op
     out = C.c_void_p(0)
     prep = lambda side, o, rows, k, ld, N=14, X=one: lib.oz2_prepare_d(side, o, rows, k, X, ld, N, null,
                                                                       C.byref(out))

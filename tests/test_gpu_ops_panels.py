@@ -130,6 +130,39 @@ def test_op_argument_checks(oz):
         assert e.value.status == 1
 
 
+@pytest.mark.parametrize("dtype,N,accurate", [(np.float64, 15, False), (np.float64, 14, True), (np.float32, 7, False)])
+def test_column_major_entry_points(oz, oracle, dtype, N, accurate):
+    """oz2_*gemm_colmajor: every matrix column-major, as a BLAS caller holds them.  A column-major
+    array is built here as the row-major storage of the transpose; the result must equal the
+    oracle's for the matrices the arrays stand for, in all four transposition cases."""
+    import torch
+    m, n, k = 150, 210, 333
+    A, B = S.gemm_inputs(m, n, k, 1.0, seed=90 + N, dtype=dtype)
+    Cin = S.matrix(m, n, 0.5, seed=91, dtype=dtype)
+    is_double = dtype == np.float64
+    ref = oracle.gemm(A, B, N, 0.5, -1.5, Cin, is_double=is_double, accurate=accurate)["C"]
+    dt = torch.float64 if is_double else torch.float32
+    fn = oz.oz2_dgemm_colmajor if is_double else oz.oz2_sgemm_colmajor
+
+    def colmajor(X, extra):           # column-major X with leading dimension rows + extra
+        buf = torch.full((X.shape[1], X.shape[0] + extra), 3.0, dtype=dt, device="cuda")
+        buf[:, :X.shape[0]] = torch.from_numpy(np.ascontiguousarray(X.T)).cuda()
+        return buf, X.shape[0] + extra
+
+    for opA in (0, 1):
+        for opB in (0, 1):
+            dA, lda = colmajor(A.T if opA else A, 3)          # op = T: the stored matrix is the transpose
+            dB, ldb = colmajor(B.T if opB else B, 1)
+            dC, ldc = colmajor(Cin, 2)
+            fn(opA, opB, accurate, m, n, k, 0.5, dA, lda, dB, ldb, -1.5, dC, ldc, N)
+            torch.cuda.synchronize()
+            got = dC[:, :m].t().cpu().numpy().astype(np.float64)
+            r = ref.astype(np.float64)
+            rel = np.max(np.abs(got - r) / np.where(r == 0, 1.0, np.abs(r)))
+            assert rel <= (TOL64 if is_double else TOL32), (opA, opB, rel)
+            assert bool((dC[:, m:] == 3.0).all())             # the gap between columns is untouched
+
+
 # ------------------------------------------------------------------ bounded workspace
 @pytest.mark.parametrize("accurate", [False, True])
 @pytest.mark.parametrize("dtype,N", [(np.float64, 15), (np.float32, 6)])
