@@ -330,8 +330,9 @@ def sweep_general(oz, torch, args) -> int:
 
 
 def sweep_small(oz, torch, args) -> int:
-    """Launch-bound sizes: one oz2_dgemm call is about ten kernel launches, so for small
-    matrices the call is timed eagerly and as a replayed HIP graph, next to the native GEMM."""
+    """Launch-bound sizes: one oz2_dgemm call is four dependent kernel launches at these sizes
+    (nine from 4096^3 on), so the call is timed eagerly and as a replayed HIP graph, next to the
+    native GEMM."""
     import numpy as np
     import synth_inputs as S
     N = args.moduli
