@@ -625,6 +625,31 @@ def test_overlapped_call_in_a_hip_graph(oz):
         oz.oz2_release()
 
 
+def test_overlapped_form_with_int32_products(oz):
+    """The diagnostic pipeline (INT32 sums kept, reduced in the accumulation) in the overlapped
+    form: same result as the default uint8 pipeline, bit for bit."""
+    import torch
+    m, n, k, N = 2100, 2300, 8192, 12
+    A, B = S.gemm_inputs(m, n, k, 2.0, seed=117)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    try:
+        for int32 in (False, True):
+            oz.oz2_set_int32_products(int32)
+            least = oz.oz2_workspace_min_bytes(m, n, k, N)
+            per = 4 * N if int32 else N
+            oz.oz2_set_workspace_limit(least - per * 256 * 256 + per * 512 * 512)
+            oz.oz2_release()
+            got = oz.matmul(dA, dB, N)
+            assert oz.oz2_last_panels() == (512, 512, 25)
+            if int32:
+                assert torch.equal(got, want)
+            want = got
+    finally:
+        oz.oz2_set_int32_products(False)
+        oz.oz2_set_workspace_limit(0)
+        oz.oz2_release()
+
+
 def test_stage_times_after_an_overlapped_and_then_a_prepared_call(oz):
     """The stage times belong to the last call, whatever form the call before it had."""
     import torch
