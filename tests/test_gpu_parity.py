@@ -150,6 +150,24 @@ def test_k_beyond_2_pow_17_is_blocked(oz, oracle):
     assert e.value.status == 2
 
 
+def test_longest_contraction_k_2_pow_20(oz, oracle):
+    """The largest k the fast mode takes (the exact integer sum of squares needs k 2^32 < 2^53):
+    eight K ranges of 2^17, rows of A a million elements long, N = 20; one element more is
+    refused."""
+    import torch
+    m, n, k = 20, 24, 2 ** 20
+    A, B = S.gemm_inputs(m, n, k, 1.0, seed=8)
+    A[3, :] = np.ldexp(np.sign(A[3, :]) + (A[3, :] == 0), 17)     # a row of +-2^17: the largest sum of squares
+    assert_parity(gpu_gemm(oz, A, B, 20), oracle.gemm(A, B, 20), True)
+    A32, B32 = A.astype(np.float32), B.astype(np.float32)
+    assert_parity(gpu_gemm(oz, A32, B32, 9), oracle.gemm(A32, B32, 9, is_double=False), False)
+    dA = torch.zeros((2, k + 1), dtype=torch.float64, device="cuda")
+    dB = torch.zeros((k + 1, 2), dtype=torch.float64, device="cuda")
+    with pytest.raises(oz.OZ2Error) as e:
+        oz.matmul(dA, dB, 14)
+    assert e.value.status == 2
+
+
 ACCURATE_CASES = [
     (256, 256, 256, 14, 0.5, np.float64),
     (1, 1, 1, 2, 0.5, np.float64),
