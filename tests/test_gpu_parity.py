@@ -261,9 +261,12 @@ def test_degenerate_inputs(oz, oracle):
     A[6, :] = 0.0; A[6, 11] = -1.0      # single entry
     A[7, :] = 1.0                       # constant rows and columns: worst case of the bound
     B[:, 11] = -1.0
-    assert_parity(gpu_gemm(oz, A, B, 16), oracle.gemm(A, B, 16), True)
+    ref = oracle.gemm(A, B, 16)
+    assert_parity(gpu_gemm(oz, A, B, 16), ref, True)
+    assert_parity(gpu_gemm(oz, A, B, 16, small_conversion=False), ref, True)        # the general kernels
     Z = np.zeros((20, 30)); Zb = np.zeros((30, 10))
     assert_parity(gpu_gemm(oz, Z, Zb, 14), oracle.gemm(Z, Zb, 14), True)
+    assert_parity(gpu_gemm(oz, Z, Zb, 14, small_conversion=False), oracle.gemm(Z, Zb, 14), True)
 
 
 def test_nonfinite_inputs_stay_local_and_memory_safe(oz, oracle):
@@ -272,12 +275,12 @@ def test_nonfinite_inputs_stay_local_and_memory_safe(oz, oracle):
     A, B = S.gemm_inputs(48, 40, 70, 0.5, seed=14)
     A_bad, B_bad = A.copy(), B.copy()
     A_bad[5, 3] = np.nan; A_bad[9, 0] = np.inf; B_bad[7, 11] = -np.inf; B_bad[0, 2] = np.nan
-    for accurate in (False,):                    # accurate mode couples rows through Cbar's maxima
-        got = gpu_gemm(oz, A_bad, B_bad, 15, accurate=accurate)["C"]
-        ref = oracle.gemm(A, B, 15, accurate=accurate)["C"]
-        rows = np.setdiff1d(np.arange(48), [5, 9]); cols = np.setdiff1d(np.arange(40), [11, 2])
+    ref = oracle.gemm(A, B, 15)["C"]
+    rows = np.setdiff1d(np.arange(48), [5, 9]); cols = np.setdiff1d(np.arange(40), [11, 2])
+    for small in (True, False):                  # fast mode only: accurate mode couples rows through Cbar's maxima
+        got = gpu_gemm(oz, A_bad, B_bad, 15, small_conversion=small)["C"]
         assert np.array_equal(got[np.ix_(rows, cols)], ref[np.ix_(rows, cols)])
-    gpu_gemm(oz, A_bad, B_bad, 15, accurate=True)    # must simply return
+        gpu_gemm(oz, A_bad, B_bad, 15, accurate=True, small_conversion=small)    # must simply return
 
 
 def test_empty_and_k_zero(oz):
