@@ -650,6 +650,35 @@ def test_overlapped_form_with_int32_products(oz):
         oz.oz2_release()
 
 
+def test_overlapped_form_in_a_caller_owned_workspace(oz):
+    """A caller-owned buffer sized for panels of 512 x 512: the overlapped form runs in it,
+    allocates no workspace of its own, and gives the result of the library-owned workspace."""
+    import torch
+    m, n, k, N = 2100, 2300, 8192, 12
+    A, B = S.gemm_inputs(m, n, k, 0.5, seed=118)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    want = oz.matmul(dA, dB, N)
+    oz.oz2_release()
+    least = oz.oz2_workspace_min_bytes(m, n, k, N)
+    buf = torch.empty(least - N * 256 * 256 + N * 512 * 512, dtype=torch.uint8, device="cuda")
+    oz.oz2_set_workspace(buf)
+    try:
+        got = torch.empty_like(want)
+        oz.matmul(dA, dB, N, out=got)                          # creates the second stream and its events
+        torch.cuda.synchronize()
+        free_before = torch.cuda.mem_get_info()[0]
+        got.zero_()
+        oz.matmul(dA, dB, N, out=got)
+        torch.cuda.synchronize()
+        assert oz.oz2_last_panels() == (512, 512, 25)
+        # no workspace of the library's own (it would be some 250 MB; the runtime's own pools may grow a little)
+        assert free_before - torch.cuda.mem_get_info()[0] < 32 * 2 ** 20
+        assert torch.equal(got, want)
+    finally:
+        oz.oz2_set_workspace(None)
+        oz.oz2_release()
+
+
 def test_stage_times_after_an_overlapped_and_then_a_prepared_call(oz):
     """The stage times belong to the last call, whatever form the call before it had."""
     import torch
