@@ -10,6 +10,15 @@ GEMM, timed with HIP events on the call's stream inside the timed steps),
 native FP64 GEMM on the same buffers, the accuracy of both against a
 double-double product on sampled rows, the matrix cores' own rate and the board
 power of both GEMMs, and the CPU oracle timed on a sub-block of the same problem.  Everything else goes to stderr.
+
+    python bench.py --sweep NAME [--out FILE]
+
+times other workloads, one JSON line per case into FILE: dgemm_4096, dgemm_16384, dgemm_16384_n14_15,
+sgemm, nonsquare, modes (the benchmark configurations over their moduli counts), throughput_dgemm,
+throughput_sgemm (m = n = k from 1024 to 16384, both modes), accuracy (error against N in the setting
+of the paper's accuracy figure), general (transposed and prepared operands, bounded workspace), small
+(launch-bound sizes, eager and as a graph), rank_k (short contractions), overlap (the default form of a
+call against the single-stream form).
 """
 from __future__ import annotations
 
