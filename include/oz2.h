@@ -39,7 +39,7 @@ typedef struct ihipStream_t *hipStream_t;   /* same declaration as the HIP runti
 typedef enum {
     OZ2_OK = 0,
     OZ2_INVALID_ARG = 1,   /* null pointer, negative size, leading dimension too small  */
-    OZ2_UNSUPPORTED = 2,   /* num_moduli outside 2..20, or k > 2^17                      */
+    OZ2_UNSUPPORTED = 2,   /* num_moduli outside 2..20, k > 2^20 (accurate mode: 2^17)  */
     OZ2_WORKSPACE = 3,     /* caller-provided workspace too small / allocation failed    */
     OZ2_HIP_ERROR = 4      /* a HIP runtime call or a kernel launch failed               */
 } oz2_status;
@@ -239,6 +239,16 @@ oz2_status oz2_shift_table(int num_moduli, int32_t *f_max, int32_t *levels, uint
  */
 oz2_status oz2_shift_table_accurate(int num_moduli, float *Paccu, int32_t *f_max, int32_t *levels,
                                     uint64_t *theta);
+
+/*
+ * How many rounds of the floating-point reduction y <- fma(-round(y / p), p, y) of Section 4.2
+ * the residue kernels run for this number of moduli (1 or 2; 0 if num_moduli is out of range).
+ * One round gives the symmetric residue only while the scaled integers stay below 2^46; fast
+ * mode keeps them below 2^(f_max + 1) and accurate mode below 2^(f_max + 6) with f_max from
+ * oz2_shift_table / oz2_shift_table_accurate, so accurate mode needs the second round earlier
+ * (from 11 moduli on instead of 13, the threshold N_1 = 13 of Section 4.2 being fast mode's).
+ */
+int oz2_residue_rounds(int num_moduli, int accurate);
 
 /*
  * Diagnostics: where the stages of the most recent oz2_dgemm / oz2_sgemm call

@@ -23,7 +23,7 @@ EXPORTS = [
     "oz2_dgemm_op", "oz2_sgemm_op", "oz2_prepare_d", "oz2_prepare_s", "oz2_operand_free",
     "oz2_operand_bytes", "oz2_dgemm_prepared", "oz2_sgemm_prepared", "oz2_workspace_min_bytes",
     "oz2_set_workspace_limit", "oz2_last_panels", "oz2_plan_panels", "oz2_set_overlap",
-    "oz2_set_small_conversion", "oz2_dgemm_colmajor", "oz2_sgemm_colmajor",
+    "oz2_set_small_conversion", "oz2_dgemm_colmajor", "oz2_sgemm_colmajor", "oz2_residue_rounds",
 ]
 
 OZ2_OP_N, OZ2_OP_T = 0, 1
@@ -98,6 +98,8 @@ def load():
     lib.oz2_set_small_conversion.argtypes = [ci]
     lib.oz2_set_small_conversion.restype = None
     lib.oz2_last_stage_times_ms.argtypes = [C.POINTER(flt)]
+    lib.oz2_residue_rounds.argtypes = [ci, ci]
+    lib.oz2_residue_rounds.restype = ci
     lib.oz2_status_string.argtypes = [ci]
     lib.oz2_status_string.restype = C.c_char_p
     for name in ("oz2_dgemm", "oz2_sgemm", "oz2_dgemm_accurate", "oz2_sgemm_accurate",
@@ -332,6 +334,10 @@ def oz2_shift_table(num_moduli: int) -> dict:
     _check(load().oz2_shift_table(int(num_moduli), f.ctypes.data, lv.ctypes.data, th.ctypes.data),
            "oz2_shift_table")
     return dict(f_max=int(f[0]), levels=int(lv[0]), theta=th[:int(lv[0])].copy())
+
+
+def oz2_residue_rounds(num_moduli: int, accurate: bool = False) -> int:
+    return int(load().oz2_residue_rounds(int(num_moduli), int(bool(accurate))))
 
 
 def oz2_stage_ptr(stage: int) -> Tuple[int, Tuple[int, int, int, int]]:

@@ -343,7 +343,7 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     if (oz2_status st = bind_device_resources()) return st;
     const bool is_double = sizeof(T) == 8;
     const Table &tab = table(N, is_double);
-    const ModArgs ma = make_mod_args(tab);
+    const ModArgs ma = make_mod_args(tab, accurate);
     const ShiftArgs sa = make_shift_args(tab);
     const Layout L = make_layout(m, n, k, N, !g.int32_products);
     // Large products with a long contraction run overlapped (run_overlapped): panels of at most
@@ -462,7 +462,7 @@ oz2_status prepare_impl(int side, oz2_op op, int64_t rows, int64_t k, const T *X
     hipError_t e = launch_fast_shifts<T>(X, ld, k_contiguous, rows, k, make_shift_args(tab),
                                          o->mem + off_scratch, o->t, stream);
     if (e == hipSuccess)
-        e = launch_any_residues<T>(X, ld, k_contiguous, rows, k, o->t, make_mod_args(tab), o->res,
+        e = launch_any_residues<T>(X, ld, k_contiguous, rows, k, o->t, make_mod_args(tab, false), o->res,
                                    o->rows_pad, o->Kp, stream);
     if (e != hipSuccess) { (void)hipFree(o->mem); delete o; return OZ2_HIP_ERROR; }
     *out = o;
@@ -478,7 +478,7 @@ oz2_status prepared_impl(const oz2_operand *l, const oz2_operand *r, double alph
         return OZ2_INVALID_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
     if (oz2_status st = bind_device_resources()) return st;
-    const ModArgs ma = make_mod_args(table(l->N, is_double));
+    const ModArgs ma = make_mod_args(table(l->N, is_double), false);
     const Layout L = make_layout(l->rows, r->rows, l->k, l->N, !g.int32_products, false);
     size_t have = 0;
     Panels P{};
@@ -687,6 +687,11 @@ oz2_status oz2_shift_table_accurate(int num_moduli, float *Paccu, int32_t *f_max
     return OZ2_OK;
 }
 
+int oz2_residue_rounds(int num_moduli, int accurate) {
+    if (num_moduli < OZ2_MIN_MODULI || num_moduli > OZ2_MAX_MODULI) return 0;
+    return residue_rounds(table(num_moduli, true), accurate != 0);
+}
+
 oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims) {
     std::lock_guard<std::mutex> lock(g.mu);
     if (!g.have_last || !dev_ptr || !dims) return OZ2_INVALID_ARG;
@@ -766,7 +771,7 @@ const char *oz2_status_string(oz2_status s) {
     switch (s) {
     case OZ2_OK: return "ok";
     case OZ2_INVALID_ARG: return "invalid argument";
-    case OZ2_UNSUPPORTED: return "unsupported number of moduli or k > 2^17";
+    case OZ2_UNSUPPORTED: return "unsupported number of moduli, or k > 2^20 (accurate mode: k > 2^17)";
     case OZ2_WORKSPACE: return "workspace too small or allocation failed";
     case OZ2_HIP_ERROR: return "HIP runtime error";
     }

@@ -38,7 +38,10 @@ struct ShiftArgs {
     uint64_t theta[kMaxLevels];
 };
 
-ModArgs make_mod_args(const Table &t);
+// accurate: the scale vectors come from accurate mode, whose scaled integers can be larger than
+// fast mode's for the same number of moduli (it decides the number of reduction rounds).
+int residue_rounds(const Table &t, bool accurate);
+ModArgs make_mod_args(const Table &t, bool accurate);
 ShiftArgs make_shift_args(const Table &t);
 ShiftArgs make_accu_shift_args(const Table &t);
 

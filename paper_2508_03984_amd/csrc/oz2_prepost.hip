@@ -9,11 +9,19 @@
 
 namespace oz2 {
 
-ModArgs make_mod_args(const Table &t) {
+int residue_rounds(const Table &t, bool accurate) {
+    // One reduction round gives the canonical residue while |x'| < 2^46 (see residue_of).
+    // Fast mode: |x| < 2^(e+1) and t = f - e with f <= f_max, so |x'| < 2^(f_max+1).
+    // Accurate mode: mu' brings |x| below 2^6 and the second factor is at most 2^accu_f_max
+    // (reached when the maximum of Cbar is 0 or 1), so |x'| < 2^(accu_f_max+6).
+    const int bits = accurate ? t.accu_f_max + 6 : t.f_max + 1;
+    return bits <= 46 ? 1 : 2;
+}
+
+ModArgs make_mod_args(const Table &t, bool accurate) {
     ModArgs a{};
     a.n = t.n;
-    // One reduction round is exact while |x'| < 2^46 (see residue_of); |x'| < 2^(f_max+1).
-    a.rounds = (t.f_max + 1 <= 46) ? 1 : 2;
+    a.rounds = residue_rounds(t, accurate);
     for (int i = 0; i < t.n; ++i) {
         a.p[i] = t.p[i];
         a.pinv_prime[i] = t.pinv_prime[i];

@@ -252,3 +252,58 @@ int main() {
     subprocess.check_call(["g++", "-std=c++17", "-O2", "-I", src, str(main),
                            os.path.join(src, "oz2_constants.cpp"), "-o", str(plain)])
     assert subprocess.run([str(plain)], capture_output=True, text=True).stdout.strip().splitlines() == lines
+
+
+def _one_round(x: int, p: int) -> int:
+    """y = fma(-rint(x * double(1/p)), p, x) as the residue kernels evaluate it: the product is
+    rounded to FP64, rint is to nearest-even, the FMA is exact here (Python integers)."""
+    q = int(np.rint(np.float64(x) * (np.float64(1.0) / np.float64(p))))
+    return x - q * p
+
+
+def _adversarial(p: int, bits: int, rng):
+    """Integers below 2^bits next to half-integer multiples of p, where a quotient estimate
+    that is slightly off rounds to the wrong side."""
+    top = (1 << bits) - 1
+    if top // p < 4000:                                       # few enough to try every multiple
+        return [c * s for j in range(top // p + 1) for c in ((2 * j + 1) * p // 2 + d for d in (-1, 0, 1, 2))
+                for s in (1, -1) if c <= top]
+    out = []
+    for _ in range(400):
+        j = int(rng.integers(top // p // 2, top // p))
+        centre = (2 * j + 1) * p // 2
+        out += [centre - 1, centre, centre + 1, centre + 2, -centre, -centre - 1]
+    return [x for x in out if abs(x) <= top and float(x) == x]       # representable in FP64
+
+
+@pytest.mark.parametrize("n", range(2, 21))
+def test_residue_rounds_are_enough_for_the_largest_scaled_integer(oz, n):
+    """Where the library takes ONE reduction round, that round must give the symmetric residue for
+    every integer the mode can produce: |x'| < 2^(f_max+1) in fast mode, < 2^(f_max+6) in accurate
+    mode (Section 4.2: mu' brings a row maximum into [32, 64), the second factor is at most
+    2^floor(P'_accu)).  Checked at adversarial integers of that size for the moduli of this N."""
+    rng = np.random.default_rng(n)
+    fast_bits = oz.oz2_shift_table(n)["f_max"] + 1
+    accu_bits = oz.oz2_shift_table_accurate(n)["f_max"] + 6
+    assert accu_bits > fast_bits
+    for accurate, bits in ((False, fast_bits), (True, accu_bits)):
+        rounds = oz.oz2_residue_rounds(n, accurate)
+        assert rounds in (1, 2)
+        if rounds == 2 or bits > 52:
+            continue
+        for p in K.moduli(n):
+            for x in _adversarial(p, bits, rng):
+                y = _one_round(x, p)
+                assert (y - x) % p == 0
+                assert 2 * abs(y) < p or (p == 256 and abs(y) == 128), (n, accurate, p, x, y)
+
+
+def test_one_round_is_not_enough_at_the_accurate_mode_bound_of_12_moduli():
+    """Why accurate mode with 11 and 12 moduli takes two rounds although fast mode takes one:
+    its scaled integers reach 2^52, and there a single round misses the symmetric residue."""
+    rng = np.random.default_rng(0)
+    misses = 0
+    for p in K.moduli(12)[1:]:
+        for x in _adversarial(p, 52, rng):
+            misses += 2 * abs(_one_round(x, p)) > p
+    assert misses > 0

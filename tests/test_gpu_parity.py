@@ -205,6 +205,25 @@ def test_accurate_mode_degenerate_inputs(oz, oracle):
                   oracle.gemm(A, Zb, 14, accurate=True), True)
 
 
+@pytest.mark.parametrize("N", [10, 11, 12, 13])
+def test_accurate_mode_largest_scaled_integers(oz, oracle, N):
+    """Accurate mode's scaled integers are largest when the maxima of Cbar are smallest: B = 0
+    (maxima 0, taken as 1) and B with a single tiny entry per column.  Around 11-12 moduli they
+    exceed what one round of the floating-point reduction handles (fast mode's never do there), so
+    the residues of A must still be the symmetric ones."""
+    A, B = S.gemm_inputs(70, 40, 200, 1.0, seed=40 + N)
+    A = np.trunc(A * 2.0 ** 20) + 0.5 * np.sign(A)       # many low bits set after scaling
+    Zb = np.zeros_like(B)
+    for small in (True, False):
+        assert_parity(gpu_gemm(oz, A, Zb, N, accurate=True, small_conversion=small),
+                      oracle.gemm(A, Zb, N, accurate=True), True)
+    B1 = np.zeros_like(B)
+    B1[np.arange(40) % 200, np.arange(40)] = 2.0 ** -30 * (1 + np.arange(40))
+    for small in (True, False):
+        assert_parity(gpu_gemm(oz, A, B1, N, accurate=True, small_conversion=small),
+                      oracle.gemm(A, B1, N, accurate=True), True)
+
+
 def test_alpha_beta_and_leading_dimensions(oz, oracle):
     A, B = S.gemm_inputs(70, 90, 150, 0.5, seed=3)
     Cin = S.matrix(70, 90, 0.5, seed=5)
@@ -368,14 +387,29 @@ def test_caller_owned_workspace(oz, oracle):
 
 
 # ------------------------------------------------------------------ benchmark-size configurations
+def band_rows(m, rng, band=256):
+    """One row out of every `band` consecutive rows (every row of tiles of the INT8 GEMM is hit),
+    plus the first and the last row."""
+    starts = np.arange(0, m, band)
+    picks = starts + rng.integers(0, np.minimum(band, m - starts))
+    return np.unique(np.concatenate([[0, m - 1], picks]))
+
+
 def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries=1500,
-                   accurate=False, int32_products=False):
-    """Full comparison of shifts and residues, sampled comparison of products and C."""
+                   accurate=False, int32_products=False, inputs=None, bands=None):
+    """Full comparison of shifts and residues, sampled comparison of products and C.
+    inputs: (A, B, dA, dB) generated before (several N on one pair of matrices);
+    bands: compare one full row per `bands` rows instead of n_rows random ones."""
     import torch
     from paper_2508_03984_amd import binding as b
     is_double = dtype == np.float64
-    A, B = S.gemm_inputs(m, n, k, phi, seed, dtype)
-    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    print(f"sampled parity: {m} x {n} x {k}, N = {N}, phi = {phi}, {np.dtype(dtype).name}, "
+          f"accurate = {accurate}", flush=True)
+    if inputs is None:
+        A, B = S.gemm_inputs(m, n, k, phi, seed, dtype)
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    else:
+        A, B, dA, dB = inputs
     # the default (overlapped above 4096 x 4096) form first, then everything on one stream, which
     # keeps the products of all of C for the checks below; the two must agree bit for bit
     dC_default = oz.matmul(dA, dB, N, accurate=accurate)
@@ -401,7 +435,10 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
         assert torch.equal(rb[s, :n, :k], torch.from_numpy(prep["Bres"][s]).cuda()), f"B slice {s}"
     del rb
     rng = np.random.default_rng(seed)
-    rows = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, n_rows)]))
+    if bands:
+        rows = band_rows(m, rng, bands)
+    else:
+        rows = np.unique(np.concatenate([[0, m - 1], rng.integers(0, m, n_rows)]))
     fin = oracle.finish_rows(prep, rows)
     stage, key = (b.OZ2_STAGE_PROD, "prod") if int32_products else (b.OZ2_STAGE_U, "U")
     prod = oz.stage_tensor(stage, copy=False)
@@ -420,6 +457,12 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
     return dC
 
 
+def device_inputs(m, n, k, phi, seed, dtype):
+    import torch
+    A, B = S.gemm_inputs(m, n, k, phi, seed, dtype)
+    return A, B, torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+
+
 def test_config_4096_sampled(oz, oracle):
     for N in (12, 16, 20):
         sampled_parity(oz, oracle, 4096, 4096, 4096, N, 0.5, np.float64, seed=0)
@@ -431,12 +474,35 @@ def test_config_4096_accurate_sampled(oz, oracle):
 
 
 def test_config_16384_dgemm_sampled(oz, oracle):
+    """The headline configuration: shifts and residues in full; products and C on one full row out
+    of every 256 (66 rows: every row of output tiles, and with all columns every tile of every
+    modulus) and on 10^5 scattered entries."""
     sampled_parity(oz, oracle, 16384, 16384, 16384, 16, 0.5, np.float64, seed=0,
-                   n_rows=2, n_entries=1000)
+                   bands=256, n_entries=100000)
+
+
+@pytest.mark.parametrize("phi,N", [(1.0, 18), (2.0, 20)])
+def test_config_16384_dgemm_wider_exponent_range_sampled(oz, oracle, phi, N):
+    """The other corners of the 16384^3 configuration (phi up to 2, up to 20 moduli, the widest
+    scaled integers): one row per 1024 rows and 20000 entries."""
+    sampled_parity(oz, oracle, 16384, 16384, 16384, N, phi, np.float64, seed=0,
+                   bands=1024, n_entries=20000)
+    oz.oz2_release()
 
 
 def test_config_sgemm_8192_sampled(oz, oracle):
-    sampled_parity(oz, oracle, 8192, 8192, 8192, 8, 0.5, np.float32, seed=0, n_rows=3)
+    inputs = device_inputs(8192, 8192, 8192, 0.5, 0, np.float32)
+    for N in (5, 8, 9):                           # the moduli counts of Section 5.2's SGEMM figures
+        sampled_parity(oz, oracle, 8192, 8192, 8192, N, 0.5, np.float32, seed=0, bands=1024,
+                       n_entries=5000, inputs=inputs)
+
+
+def test_config_sgemm_16384_sampled(oz, oracle):
+    inputs = device_inputs(16384, 16384, 16384, 0.5, 0, np.float32)
+    for N in (5, 8, 9):
+        sampled_parity(oz, oracle, 16384, 16384, 16384, N, 0.5, np.float32, seed=0, bands=1024,
+                       n_entries=20000, inputs=inputs)
+    oz.oz2_release()
 
 
 def test_config_nonsquare_k_65536_sampled(oz, oracle):
