@@ -540,6 +540,9 @@ def main() -> int:
                     help="accurate mode of Section 4.2 (oz2_dgemm_accurate / oz2_sgemm_accurate)")
     ap.add_argument("--int32-products", action="store_true",
                     help="diagnostic pipeline: the GEMM stores int32 sums, the epilogue reduces them")
+    ap.add_argument("--inputs", choices=["synthetic", "ones"], default="synthetic",
+                    help="ones: A = B = 1 everywhere, so every residue slice is one constant (diagnostic: "
+                         "the matrix cores then draw little power and the chip does not lower its clock)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the MFMA-only probe, the library INT8 GEMM and the power legs")
@@ -593,7 +596,10 @@ def main() -> int:
     np_dt, t_dt = (np.float32, torch.float32) if args.sgemm else (np.float64, torch.float64)
     log(f"generating inputs {m}x{k}, {k}x{n} phi={args.phi} ...")
     t0 = time.time()
-    A, B = S.gemm_inputs(m, n, k, args.phi, seed=0, dtype=np_dt)
+    if args.inputs == "ones":
+        A, B = np.ones((m, k), np_dt), np.ones((k, n), np_dt)
+    else:
+        A, B = S.gemm_inputs(m, n, k, args.phi, seed=0, dtype=np_dt)
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     dC = torch.empty((m, n), dtype=t_dt, device="cuda")
     log(f"  done in {time.time() - t0:.1f}s")
@@ -767,7 +773,7 @@ def main() -> int:
         "dtype": "int8",
         "dtype_note": "INT8 MFMA products with exact INT32 accumulation; scaling, residues and CRT "
                       "reconstruction in FP64; inputs and output " + ("FP32" if args.sgemm else "FP64"),
-        "data": "synthetic",
+        "data": "synthetic" if args.inputs == "synthetic" else "all ones (diagnostic run, not the benchmark)",
         "config": {"workload": f"{'SGEMM' if args.sgemm else 'DGEMM'} emulation m=n=k={m}, "
                                f"{'fp32' if args.sgemm else 'fp64'} row-major, phi={args.phi}, "
                                f"seed 0/1, {'accurate' if args.accurate else 'fast'} mode, N={N} moduli, "

@@ -250,15 +250,28 @@ def accu_shift_from_max(e, cmax, Paccu: float, is_zero=None) -> np.ndarray:
     return t
 
 
-def accu_shifts(A64: np.ndarray, B64: np.ndarray, Paccu: float) -> Dict:
+def accu_shifts(A64: np.ndarray, B64: np.ndarray, Paccu: float, kblock: int = MAX_K) -> Dict:
     """Accurate-mode scale vectors of Section 4.2: Cbar = Abar Bbar, then the shifts from its
     row and column maxima.  The product is a library matmul in FP64, which is exact here
-    (entries are integers below 2^29)."""
+    (entries are integers below 2^29).
+
+    k > kblock (the longest contraction one INT32 product holds, Section 4.3): Cbar is the sum of
+    the products Cbar_r over K ranges of kblock ("block matrix multiplication", last sentence of
+    Section 4.3).  The bound chain of Section 4.2 needs an upper bound of max_j sum_h |a_ih||b_hj|
+    only, and  max_j sum_r (Cbar_r)_ij <= sum_r max_j (Cbar_r)_ij,  so the row maximum of Cbar is
+    replaced by the sum over the ranges of the row maxima of Cbar_r (columns alike): no matrix
+    larger than one INT32 product is ever reduced.  For k <= kblock this is the paper's formula."""
     eA, Abar = accu_prescale(A64, 0)
     eB, Bbar = accu_prescale(B64, 1)
-    Cbar = np.matmul(Abar.astype(np.float64), Bbar.astype(np.float64).T)
-    rmax = Cbar.max(axis=1).astype(np.int64) if Cbar.size else np.zeros(A64.shape[0], np.int64)
-    cmax = Cbar.max(axis=0).astype(np.int64) if Cbar.size else np.zeros(B64.shape[1], np.int64)
+    m, k = A64.shape
+    n = B64.shape[1]
+    rmax = np.zeros(m, np.int64)
+    cmax = np.zeros(n, np.int64)
+    for k0 in range(0, k, kblock):
+        Cbar = np.matmul(Abar[:, k0:k0 + kblock].astype(np.float64), Bbar[:, k0:k0 + kblock].astype(np.float64).T)
+        if Cbar.size:
+            rmax += Cbar.max(axis=1).astype(np.int64)
+            cmax += Cbar.max(axis=0).astype(np.int64)
     zA = np.ascontiguousarray(~A64.any(axis=1), dtype=np.uint8)
     zB = np.ascontiguousarray(~B64.any(axis=0), dtype=np.uint8)
     tA = accu_shift_from_max(eA, rmax, Paccu, zA)
@@ -267,13 +280,13 @@ def accu_shifts(A64: np.ndarray, B64: np.ndarray, Paccu: float) -> Dict:
 
 
 def prepare(A: np.ndarray, B: np.ndarray, num_moduli: int, is_double: bool = True,
-            accurate: bool = False) -> Dict:
+            accurate: bool = False, kblock: int = MAX_K) -> Dict:
     """Algorithm 1 lines 1-5 on the whole of A and B (fast or accurate scale vectors)."""
     c = K.constants(num_moduli, is_double)
     A64 = np.ascontiguousarray(A, dtype=np.float64)
     B64 = np.ascontiguousarray(B, dtype=np.float64)
     if accurate:
-        out = accu_shifts(A64, B64, c.Paccu)
+        out = accu_shifts(A64, B64, c.Paccu, kblock)
         tA, tB = out["tA"], out["tB"]
     else:
         tA, eA, TA = shifts(A64, 0, c.Pfast)

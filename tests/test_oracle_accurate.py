@@ -84,6 +84,61 @@ def test_uniqueness_condition_eq3_accurate(oracle, n_mod):
                 assert 2 * sum(abs(Ap[i][h]) * abs(Bp[h][j]) for h in range(64)) < c.P
 
 
+def test_blocked_bound_for_long_contractions(oracle):
+    """k beyond one INT32 product (Section 4.3, last sentence; here with a block of 16 instead of
+    2^17 so that exact integers stay cheap): the row bound is sum_r max_j (Cbar_r)_ij, computed
+    here from the definition with Python integers; it is at least the true row maximum of the
+    whole Cbar, equals the paper's formula when one block holds all of k, and the bound chain of
+    Section 4.2 still holds entry by entry."""
+    A, B = S.gemm_inputs(6, 5, 70, 1.5, seed=12)
+    r = oracle.accu_shifts(A, B, 40.0, kblock=16)
+    Ab = [[int(v) for v in row] for row in r["Abar"]]
+    Bb = [[int(v) for v in row] for row in r["Bbar"]]          # vector-major: Bb[j][h]
+    blocks = [(k0, min(k0 + 16, 70)) for k0 in range(0, 70, 16)]
+    cb = lambda i, j, k0, k1: sum(Ab[i][h] * Bb[j][h] for h in range(k0, k1))
+    rmax = [sum(max(cb(i, j, *b) for j in range(5)) for b in blocks) for i in range(6)]
+    cmax = [sum(max(cb(i, j, *b) for i in range(6)) for b in blocks) for j in range(5)]
+    assert r["rmax"].tolist() == rmax and r["cmax"].tolist() == cmax
+    whole = oracle.accu_shifts(A, B, 40.0, kblock=70)
+    assert whole["rmax"].tolist() == [max(cb(i, j, 0, 70) for j in range(5)) for i in range(6)]
+    assert np.all(r["rmax"] >= whole["rmax"]) and np.all(r["cmax"] >= whole["cmax"])
+    assert np.any(r["rmax"] > whole["rmax"])                      # the bound is really coarser here
+    assert np.all(r["tA"] <= whole["tA"]) and np.all(r["tB"] <= whole["tB"])
+    for i in range(6):
+        for j in range(5):
+            lhs = sum(abs(Fraction(float(A[i, h])) * Fraction(float(B[h, j]))) for h in range(70))
+            scale = Fraction(2) ** int(5 - r["eA"][i]) * Fraction(2) ** int(5 - r["eB"][j])
+            assert lhs <= Fraction(rmax[i]) / scale and lhs <= Fraction(cmax[j]) / scale
+
+
+@pytest.mark.parametrize("n_mod", [2, 9, 14, 20])
+def test_uniqueness_condition_eq3_accurate_blocked(oracle, n_mod):
+    """Eq. 3 with exact integers when the contraction spans several blocks, including the case in
+    which every bound of the chain is attained (constant parallel vectors)."""
+    c = K.constants(n_mod)
+    for phi, seed in ((0.5, 1), (4.0, 3)):
+        A, B = S.gemm_inputs(6, 5, 100, phi, seed)
+        A[0, :] = np.abs(A[0, :]).max()
+        B[:, 0] = np.abs(B[:, 0]).max()
+        prep = oracle.prepare(A, B, n_mod, accurate=True, kblock=32)
+        Ap, Bp = exact_scaled_matrices(A, B, prep["tA"], prep["tB"])
+        for i in range(6):
+            for j in range(5):
+                assert 2 * sum(abs(Ap[i][h]) * abs(Bp[h][j]) for h in range(100)) < c.P
+
+
+def test_blocked_accurate_mode_end_to_end(oracle):
+    """The whole of Algorithm 1 with the blocked bound: the result is as accurate as with the
+    unblocked bound up to the (at most 0.51 log2(blocks)-bit) smaller shifts."""
+    A, B = S.gemm_inputs(24, 20, 512, 1.0, seed=5)
+    rows = np.arange(24)
+    err = {}
+    for kb in (512, 64):
+        prep = oracle.prepare(A, B, 13, accurate=True, kblock=kb)
+        err[kb] = dd_error(oracle, oracle.finish_rows(prep, rows)["C"], A, B)
+    assert err[512] <= 2 * err[64] and err[64] < 64 * err[512]
+
+
 def test_accurate_special_cases(oracle):
     A, B = S.gemm_inputs(6, 7, 30, 0.5, seed=9)
     A[2, :] = 0.0
