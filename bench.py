@@ -17,8 +17,8 @@ times other workloads, one JSON line per case into FILE: dgemm_4096, dgemm_16384
 sgemm, nonsquare, modes (the benchmark configurations over their moduli counts), throughput_dgemm,
 throughput_sgemm (m = n = k from 1024 to 16384, both modes), accuracy (error against N in the setting
 of the paper's accuracy figure), general (transposed and prepared operands, bounded workspace), small
-(launch-bound sizes, eager and as a graph), rank_k (short contractions), overlap (the default form of a
-call against the single-stream form).
+(launch-bound sizes, eager and as a graph), rank_k (short contractions), overlap (the overlapped form of a
+call, an option, against the default single-stream form).
 """
 from __future__ import annotations
 
@@ -483,9 +483,9 @@ def sweep_rank_k(oz, torch, args) -> int:
 
 
 def sweep_overlap(oz, torch, args) -> int:
-    """The default form of a call (conversion of later panels on a second stream where the
-    rule allows it) against the single-stream form, on the same device and buffers, in turns.
-    One JSON line per workload goes to --out."""
+    """The overlapped form of a call (an option: conversion of later panels on a second stream
+    where the rule allows it) against the default single-stream form, on the same device and
+    buffers, in turns.  One JSON line per workload goes to --out."""
     import numpy as np
     import synth_inputs as S
     path = args.out or "sweep_overlap.jsonl"
@@ -513,12 +513,12 @@ def sweep_overlap(oz, torch, args) -> int:
                             call()
                         torch.cuda.synchronize()
                         ms[on].append(1e3 * (time.perf_counter() - t0) / args.steps)
+                panels = list(oz.oz2_last_panels())            # of the overlapped form
             finally:
-                oz.oz2_set_overlap(True)
-            call()
+                oz.oz2_set_overlap(False)
             rec = {"m": m, "n": n, "k": k, "num_moduli": N, "dtype": "f64" if is_double else "f32",
                    "mode": "accurate" if accurate else "fast", "single_stream_ms": min(ms[False]),
-                   "default_ms": min(ms[True]), "panels_of_the_default_form": list(oz.oz2_last_panels())}
+                   "overlapped_ms": min(ms[True]), "panels_of_the_overlapped_form": panels}
             log(json.dumps(rec))
             f.write(json.dumps(rec) + "\n")
             del dA, dB, dC
@@ -632,31 +632,11 @@ def main() -> int:
     log(f"oz2 {'sgemm' if args.sgemm else 'dgemm'} N={N}: {ms_per_step:.2f} ms/step, "
         f"{tflops:.1f} emulated TFLOP/s; stages [shift, residues, gemm, epilogue] ms = "
         f"{np.round(stage_ms, 3).tolist()}; {panels} panel(s) of {panel_rows} x {panel_cols}")
-    # A call in panels overlaps the residues with the GEMMs on a second stream; its stage
-    # times are then [shifts, residues before the first GEMM, sum of the GEMM launches, rest].
-    # The time of each step on its own comes from a few calls with everything on one stream.
-    overlapped_stage_ms = None
-    if panels > 1:
-        overlapped_stage_ms = stage_ms.copy()
-        oz.oz2_set_overlap(False)
-        oz.oz2_set_profiling(True)
-        step()
-        single = np.zeros(4)
-        for _ in range(3):
-            step()
-            single += np.array(oz.oz2_last_stage_times_ms())
-        oz.oz2_set_profiling(False)
-        oz.oz2_set_overlap(True)
-        single /= 3
-        log(f"  on one stream: stages ms = {np.round(single, 3).tolist()} (sum {single.sum():.2f})")
-
     # dominant kernel: the batched INT8 GEMM on the padded slices
     pad = lambda x, to: (x + to - 1) // to * to
     Mp, Np, Kp = pad(m, 256), pad(n, 256), pad(k, 128)
     gemm_ops = 2.0 * Mp * Np * Kp * N
     gemm_tops = gemm_ops / (stage_ms[2] * 1e-3) / 1e12            # stage_ms[2]: all GEMM launches of a step
-    if overlapped_stage_ms is not None:
-        stage_ms = single                                         # per-step figures below: one stream
     E = 4 if args.sgemm else 8
     PB = 4 if args.int32_products else 1                        # bytes per product entry
     stage_bytes = [
@@ -784,16 +764,9 @@ def main() -> int:
                      "frac": gemm_tops / INT8_PEAK_TOPS,
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(("f32" if args.sgemm else "f64", m, N)),
                      "ops_per_launch": gemm_ops / gemm_launches,
-                     "avg_launch_ms": float((overlapped_stage_ms if overlapped_stage_ms is not None
-                                             else stage_ms)[2] / gemm_launches),
+                     "avg_launch_ms": float(stage_ms[2] / gemm_launches),
                      "launches_per_step": gemm_launches,
                      "note": "INT8 multiply-adds counted as 2 ops each, against the dense INT8 peak"},
-        "overlap": None if overlapped_stage_ms is None else {
-            "panels": panels, "panel": [panel_rows, panel_cols],
-            "ms": {"shifts": float(overlapped_stage_ms[0]), "residues_before_first_gemm": float(overlapped_stage_ms[1]),
-                   "int8_gemm_launches_sum": float(overlapped_stage_ms[2]), "rest": float(overlapped_stage_ms[3])},
-            "note": "the timed steps: residues of later panels run on a second stream beside the GEMMs; "
-                    "`stages` below is the same call with everything on one stream"},
         "stages": {"ms": {"shifts": float(stage_ms[0]), "residues": float(stage_ms[1]),
                           "int8_gemm": float(stage_ms[2]), "epilogue": float(stage_ms[3])},
                    "hbm_GBps_algorithmic": {"shifts": stage_gbs[0], "residues": stage_gbs[1],

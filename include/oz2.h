@@ -14,15 +14,27 @@
  *   - pointers named A, B, C, dev_* are DEVICE pointers owned by the caller;
  *     A and B are only read; host pointers are marked "host";
  *   - calls are asynchronous on `stream`; the returned status reports argument
- *     and launch errors only.  One call may be in flight per process at a time
- *     (the workspace is shared).  A product call whose workspace already exists
- *     (a caller-owned one, or the library's own after a call of at least the same
- *     size) allocates nothing and clears its scratch with kernels, not memsets, so
- *     it may be recorded into a HIP graph while profiling is off;
+ *     and launch errors only;
+ *   - state (the workspace, the options, the diagnostics of the last call) lives in a
+ *     CONTEXT (oz2_create / oz2_destroy; the oz2_ctx_* entry points).  The product calls
+ *     of one context share its workspace: the caller orders them (one stream, or events
+ *     between streams).  Calls on different contexts are independent and may run
+ *     concurrently, from several host threads and on several streams.  Every entry
+ *     point without a context argument (oz2_dgemm, oz2_set_workspace, ...) is the
+ *     oz2_ctx_* one applied to the process's DEFAULT context, which a NULL context
+ *     argument also denotes;
+ *   - a product call whose workspace already exists (a caller-owned one, or the
+ *     library's own after a call of at least the same size on the same device)
+ *     allocates nothing and clears its scratch with kernels, not memsets, so it may be
+ *     recorded into a HIP graph while profiling is off.  A call that has to grow the
+ *     library's own workspace (or move it to another device) waits for the device,
+ *     frees the old buffer and allocates the new one with hipMalloc before it
+ *     launches anything;
  *   - inputs must be finite.  Inf/NaN inputs give an unspecified (but memory
  *     safe) result: the paper does not define them;
- *   - no entry point throws; none synchronises the device except oz2_release,
- *     oz2_set_workspace and oz2_last_stage_times_ms.
+ *   - no entry point throws; besides the workspace growth above only oz2_destroy,
+ *     oz2_release, oz2_set_workspace and oz2_last_stage_times_ms (and their oz2_ctx_
+ *     forms) synchronise the device.
  */
 #ifndef OZ2_H
 #define OZ2_H
@@ -86,8 +98,12 @@ oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha,
  * sum_h |a_ih||b_hj| directly instead of through the Cauchy-Schwarz inequality.  This costs
  * one more INT8 GEMM and gives larger scale factors, i.e. a smaller truncation error for
  * the same number of moduli (it matters for inputs with a wide exponent range).
- * Arguments, conventions and errors are those of oz2_dgemm / oz2_sgemm, except that
- * k > OZ2_MAX_K returns OZ2_UNSUPPORTED (Cbar is a single INT32 product).
+ * Arguments, conventions and errors are those of oz2_dgemm / oz2_sgemm.  For
+ * OZ2_MAX_K < k <= OZ2_MAX_K_BLOCKED Cbar is cut into the same K ranges as the products
+ * (Section 4.3, last sentence), each an exact INT32 product of which the row and column
+ * maxima are kept; the maxima of the whole Cbar are then replaced by the sums of the ranges'
+ * maxima, an upper bound of them, which is all the inequalities of Section 4.2 need (the
+ * scale factors can come out one binary step smaller than with the exact maxima).
  */
 oz2_status oz2_dgemm_accurate(int64_t m, int64_t n, int64_t k, double alpha,
                               const double *A, int64_t lda, const double *B, int64_t ldb,
@@ -137,6 +153,41 @@ oz2_status oz2_sgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, i
                               float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream);
 
 /*
+ * Contexts, for callers that run several products at once (host threads, streams) or want
+ * options and workspaces of their own (the callers that cannot share the process-wide state).
+ * oz2_create makes an empty context (no device memory yet; *out is written on success only);
+ * oz2_destroy waits for the device, frees what the context owns (its workspace, events, second
+ * stream) and the context itself; the caller makes sure none of its calls is still being issued.
+ * A context may be used on any device: its own workspace lives on the device that is current
+ * when a product call needs it (see oz2_set_workspace).  NULL stands for the default context.
+ *
+ * oz2_ctx_dgemm / oz2_ctx_sgemm are oz2_dgemm_op / oz2_sgemm_op on a context, i.e. the general
+ * form C <- alpha * op(A) * op(B) + beta * C of Algorithm 1 in fast (accurate = 0) or accurate
+ * mode (Section 4.2); arguments, conventions and errors as described there.  The other oz2_ctx_*
+ * functions are the context forms of the functions of the same name without "ctx_", described
+ * further down.  Options (oz2_ctx_set_option; value 0 = off, otherwise on):
+ *   OZ2_OPT_INT32_PRODUCTS    see oz2_set_int32_products     (default off)
+ *   OZ2_OPT_OVERLAP           see oz2_set_overlap            (default off)
+ *   OZ2_OPT_SMALL_CONVERSION  see oz2_set_small_conversion   (default on)
+ *   OZ2_OPT_PROFILING         see oz2_set_profiling          (default off)
+ */
+typedef struct oz2_context oz2_context;
+typedef enum { OZ2_OPT_INT32_PRODUCTS = 0, OZ2_OPT_OVERLAP = 1, OZ2_OPT_SMALL_CONVERSION = 2,
+               OZ2_OPT_PROFILING = 3 } oz2_option;
+
+oz2_status oz2_create(oz2_context **out);
+oz2_status oz2_destroy(oz2_context *ctx);
+oz2_status oz2_ctx_set_option(oz2_context *ctx, oz2_option option, int value);
+oz2_status oz2_ctx_dgemm(oz2_context *ctx, oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n,
+                         int64_t k, double alpha, const double *A, int64_t lda, const double *B,
+                         int64_t ldb, double beta, double *C, int64_t ldc, int num_moduli,
+                         hipStream_t stream);
+oz2_status oz2_ctx_sgemm(oz2_context *ctx, oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n,
+                         int64_t k, float alpha, const float *A, int64_t lda, const float *B,
+                         int64_t ldb, float beta, float *C, int64_t ldc, int num_moduli,
+                         hipStream_t stream);
+
+/*
  * Prepared operands: Algorithm 1 lines 1-5 (fast mode) for ONE matrix, kept for reuse.
  * In fast mode the scale vector and the residues of A do not depend on B and vice versa,
  * so a matrix that enters many products (the panel of a blocked factorisation, a fixed
@@ -168,6 +219,10 @@ oz2_status oz2_dgemm_prepared(const oz2_operand *left, const oz2_operand *right,
                               double beta, double *C, int64_t ldc, hipStream_t stream);
 oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right, float alpha,
                               float beta, float *C, int64_t ldc, hipStream_t stream);
+oz2_status oz2_ctx_dgemm_prepared(oz2_context *ctx, const oz2_operand *left, const oz2_operand *right,
+                                  double alpha, double beta, double *C, int64_t ldc, hipStream_t stream);
+oz2_status oz2_ctx_sgemm_prepared(oz2_context *ctx, const oz2_operand *left, const oz2_operand *right,
+                                  float alpha, float beta, float *C, int64_t ldc, hipStream_t stream);
 
 /*
  * Workspace.  A call needs device scratch for the shift vectors (and the
@@ -181,9 +236,9 @@ oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right,
  * call; a call made with another device current allocates anew there), growing it on
  * demand and keeping it until oz2_release.  The library's own buffer is sized for
  * oz2_workspace_bytes, except for calls that take the overlapped form described under
- * oz2_set_overlap: those work through C in panels of at most 4096 x 4096 anyway, so their
- * buffer holds the products of one such panel beside the residues (at m = n = k = 16384 and
- * 16 moduli 8.9 GB instead of 12.9 GB).
+ * oz2_set_overlap (an option): those work through C in panels of at most 4096 x 4096
+ * anyway, so their buffer holds the products of one such panel beside the residues (at
+ * m = n = k = 16384 and 16 moduli 8.9 GB instead of 12.9 GB).
  *
  * Bounded workspace ("block matrix multiplication" over the rows and columns of C): the
  * products U_s are the largest part (num_moduli * m * n bytes).  When the workspace may
@@ -208,6 +263,15 @@ oz2_status oz2_plan_panels(int64_t m, int64_t n, int64_t k, int num_moduli, size
                            int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
 oz2_status oz2_last_panels(int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
 void oz2_release(void);
+size_t oz2_ctx_workspace_bytes(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli);
+size_t oz2_ctx_workspace_min_bytes(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli);
+oz2_status oz2_ctx_set_workspace(oz2_context *ctx, void *dev_ptr, size_t bytes);
+oz2_status oz2_ctx_set_workspace_limit(oz2_context *ctx, size_t bytes);
+oz2_status oz2_ctx_plan_panels(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli,
+                               size_t workspace_bytes, int64_t *panel_rows, int64_t *panel_cols,
+                               int64_t *count);
+oz2_status oz2_ctx_last_panels(oz2_context *ctx, int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
+oz2_status oz2_ctx_release(oz2_context *ctx);    /* frees what the context owns on the device, keeps the context */
 
 /*
  * Constants of Section 4.1 for `num_moduli` moduli, written to HOST arrays of
@@ -234,7 +298,8 @@ oz2_status oz2_shift_table(int num_moduli, int32_t *f_max, int32_t *levels, uint
 /*
  * The accurate-mode counterpart: P'_accu (binary32) and the table for
  * f = floor(P'_accu - 0.51 log2 c) over the integer c = maximum of a row or column of Cbar
- * (1 <= c <= 2^29): f = f_max - min{ j : c <= theta[j] }; the shift is t = (5 - e) + f.
+ * (1 <= c <= 2^32: up to eight K ranges of at most 2^29 each): f = f_max - min{ j : c <= theta[j] };
+ * the shift is t = (5 - e) + f.
  * Writes to HOST memory; theta needs room for 20 entries.
  */
 oz2_status oz2_shift_table_accurate(int num_moduli, float *Paccu, int32_t *f_max, int32_t *levels,
@@ -273,6 +338,7 @@ int oz2_residue_rounds(int num_moduli, int accurate);
 enum { OZ2_STAGE_SHIFT_A = 0, OZ2_STAGE_SHIFT_B = 1, OZ2_STAGE_RES_A = 2,
        OZ2_STAGE_RES_B = 3, OZ2_STAGE_PROD = 4, OZ2_STAGE_U = 5 };
 oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims);
+oz2_status oz2_ctx_stage_ptr(oz2_context *ctx, int stage, void **dev_ptr, int64_t *dims);
 void oz2_set_int32_products(int on);
 
 /*
@@ -301,17 +367,18 @@ oz2_status oz2_mfma_probe(int random_operands, double seconds, double *tops, int
                           int *clock_mhz);
 
 /*
- * Overlap (on by default).  A product with a long contraction and a large C (k >= 8192, at
- * least four panels of at most 4096 x 4096, k times the number of panels at least 9 x 8192) is
- * computed panel by panel: the INT8 GEMMs and the accumulation
+ * Overlap (an option, off by default).  With it, a product with a long contraction and a large C
+ * (k >= 8192, at least four panels of at most 4096 x 4096, k times the number of panels at
+ * least 9 x 8192) is computed panel by panel: the INT8 GEMMs and the accumulation
  * of the panels run one after the other on `stream`, while a second stream owned by the
- * library (default priority, created at the first such call, destroyed by oz2_release)
+ * context (default priority, created at the first such call, destroyed by oz2_release)
  * computes the residues of the blocks of A and B that the coming panels need.  The second
  * stream forks from `stream` after the shifts and has joined it again when the last panel
  * starts, so for the caller the call is ordered on `stream` as always (it can also be captured
  * into a graph once the second stream exists).  The result is bit-identical.  The product
  * stages of oz2_stage_ptr are not available after such a call (shifts and residues are).
- * oz2_set_overlap(0) computes everything on `stream`, one step after the other.
+ * Whether it pays depends on the device: the matrix cores run against the board's power limit,
+ * and work beside the GEMMs takes clock from them (measured between -2 % and +1 % of the call).
  */
 void oz2_set_overlap(int on);
 
@@ -337,6 +404,7 @@ void oz2_set_small_conversion(int on);
  */
 void oz2_set_profiling(int on);
 oz2_status oz2_last_stage_times_ms(float *out4);
+oz2_status oz2_ctx_last_stage_times_ms(oz2_context *ctx, float *out4);
 
 /* Static text for a status code. */
 const char *oz2_status_string(oz2_status s);

@@ -7,7 +7,8 @@ only marshal arguments; torch supplies device memory and streams.
 """
 from . import binding as _binding
 from .binding import (  # noqa: F401
-    OZ2Error, lib_path, load, stage_tensor, matmul, block_slices, unblock_slices, OZ2_OP_N, OZ2_OP_T, Operand,
+    OZ2Error, lib_path, load, stage_tensor, matmul, block_slices, unblock_slices, OZ2_OP_N, OZ2_OP_T, Operand, Context,
+    OZ2_OPT_INT32_PRODUCTS, OZ2_OPT_OVERLAP, OZ2_OPT_SMALL_CONVERSION, OZ2_OPT_PROFILING,
 )
 
 # one Python function per C entry point, under the same name

@@ -24,7 +24,14 @@ EXPORTS = [
     "oz2_operand_bytes", "oz2_dgemm_prepared", "oz2_sgemm_prepared", "oz2_workspace_min_bytes",
     "oz2_set_workspace_limit", "oz2_last_panels", "oz2_plan_panels", "oz2_set_overlap",
     "oz2_set_small_conversion", "oz2_dgemm_colmajor", "oz2_sgemm_colmajor", "oz2_residue_rounds",
+    "oz2_create", "oz2_destroy", "oz2_ctx_set_option", "oz2_ctx_dgemm", "oz2_ctx_sgemm",
+    "oz2_ctx_dgemm_prepared", "oz2_ctx_sgemm_prepared", "oz2_ctx_workspace_bytes",
+    "oz2_ctx_workspace_min_bytes", "oz2_ctx_set_workspace", "oz2_ctx_set_workspace_limit",
+    "oz2_ctx_plan_panels", "oz2_ctx_last_panels", "oz2_ctx_release", "oz2_ctx_stage_ptr",
+    "oz2_ctx_last_stage_times_ms",
 ]
+
+OZ2_OPT_INT32_PRODUCTS, OZ2_OPT_OVERLAP, OZ2_OPT_SMALL_CONVERSION, OZ2_OPT_PROFILING = range(4)
 
 OZ2_OP_N, OZ2_OP_T = 0, 1
 
@@ -98,6 +105,29 @@ def load():
     lib.oz2_set_small_conversion.argtypes = [ci]
     lib.oz2_set_small_conversion.restype = None
     lib.oz2_last_stage_times_ms.argtypes = [C.POINTER(flt)]
+    lib.oz2_create.argtypes = [C.POINTER(vp)]
+    lib.oz2_destroy.argtypes = [vp]
+    lib.oz2_ctx_set_option.argtypes = [vp, ci, ci]
+    lib.oz2_ctx_dgemm.argtypes = [vp, ci, ci, ci] + lib.oz2_dgemm.argtypes
+    lib.oz2_ctx_sgemm.argtypes = [vp, ci, ci, ci] + lib.oz2_sgemm.argtypes
+    lib.oz2_ctx_dgemm_prepared.argtypes = [vp] + lib.oz2_dgemm_prepared.argtypes
+    lib.oz2_ctx_sgemm_prepared.argtypes = [vp] + lib.oz2_sgemm_prepared.argtypes
+    lib.oz2_ctx_workspace_bytes.argtypes = [vp, i64, i64, i64, ci]
+    lib.oz2_ctx_workspace_bytes.restype = C.c_size_t
+    lib.oz2_ctx_workspace_min_bytes.argtypes = [vp, i64, i64, i64, ci]
+    lib.oz2_ctx_workspace_min_bytes.restype = C.c_size_t
+    lib.oz2_ctx_set_workspace.argtypes = [vp, vp, C.c_size_t]
+    lib.oz2_ctx_set_workspace_limit.argtypes = [vp, C.c_size_t]
+    lib.oz2_ctx_plan_panels.argtypes = [vp] + lib.oz2_plan_panels.argtypes
+    lib.oz2_ctx_last_panels.argtypes = [vp] + lib.oz2_last_panels.argtypes
+    lib.oz2_ctx_release.argtypes = [vp]
+    lib.oz2_ctx_stage_ptr.argtypes = [vp] + lib.oz2_stage_ptr.argtypes
+    lib.oz2_ctx_last_stage_times_ms.argtypes = [vp, C.POINTER(flt)]
+    for name in EXPORTS:
+        if name.startswith("oz2_ctx_") or name in ("oz2_create", "oz2_destroy"):
+            getattr(lib, name).restype = ci
+    lib.oz2_ctx_workspace_bytes.restype = C.c_size_t
+    lib.oz2_ctx_workspace_min_bytes.restype = C.c_size_t
     lib.oz2_residue_rounds.argtypes = [ci, ci]
     lib.oz2_residue_rounds.restype = ci
     lib.oz2_status_string.argtypes = [ci]
@@ -383,12 +413,137 @@ def oz2_last_stage_times_ms():
     return [float(x) for x in out]
 
 
-# ------------------------------------------------------------------ conveniences (no arithmetic)
-def stage_tensor(stage: int, copy: bool = True):
-    """A stage buffer of the last call as a torch tensor (synchronises first).  With
-    copy=False the tensor aliases the library's workspace and is valid until the next call."""
+# ------------------------------------------------------------------ contexts
+def _ctx(ctx) -> C.c_void_p:
+    """None (the default context), a Context, or a raw handle."""
+    if ctx is None:
+        return C.c_void_p(0)
+    return C.c_void_p(ctx.handle if isinstance(ctx, Context) else int(ctx))
+
+
+class Context:
+    """Owner of an oz2_context handle (oz2_create); destroyed with the object."""
+
+    def __init__(self):
+        out = C.c_void_p(0)
+        _check(load().oz2_create(C.byref(out)), "oz2_create")
+        self.handle = int(out.value)
+
+    def destroy(self) -> None:
+        if self.handle:
+            _check(load().oz2_destroy(C.c_void_p(self.handle)), "oz2_destroy")
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def oz2_create() -> Context:
+    return Context()
+
+
+def oz2_destroy(ctx: Context) -> None:
+    ctx.destroy()
+
+
+def oz2_ctx_set_option(ctx, option: int, value) -> None:
+    _check(load().oz2_ctx_set_option(_ctx(ctx), int(option), int(bool(value))), "oz2_ctx_set_option")
+
+
+def oz2_ctx_dgemm(ctx, opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli,
+                  stream=None) -> None:
     import torch
-    ptr, dims = oz2_stage_ptr(stage)
+    _check(load().oz2_ctx_dgemm(_ctx(ctx), int(opA), int(opB), int(bool(accurate)), m, n, k, float(alpha),
+                                _dev(A, torch.float64), lda, _dev(B, torch.float64), ldb, float(beta),
+                                _dev(C_, torch.float64), ldc, int(num_moduli), _stream(stream)),
+           "oz2_ctx_dgemm")
+
+
+def oz2_ctx_sgemm(ctx, opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli,
+                  stream=None) -> None:
+    import torch
+    _check(load().oz2_ctx_sgemm(_ctx(ctx), int(opA), int(opB), int(bool(accurate)), m, n, k, float(alpha),
+                                _dev(A, torch.float32), lda, _dev(B, torch.float32), ldb, float(beta),
+                                _dev(C_, torch.float32), ldc, int(num_moduli), _stream(stream)),
+           "oz2_ctx_sgemm")
+
+
+def oz2_ctx_dgemm_prepared(ctx, left: Operand, right: Operand, alpha, beta, C_, ldc, stream=None) -> None:
+    import torch
+    _check(load().oz2_ctx_dgemm_prepared(_ctx(ctx), C.c_void_p(left.handle), C.c_void_p(right.handle),
+                                         float(alpha), float(beta), _dev(C_, torch.float64), ldc,
+                                         _stream(stream)), "oz2_ctx_dgemm_prepared")
+
+
+def oz2_ctx_sgemm_prepared(ctx, left: Operand, right: Operand, alpha, beta, C_, ldc, stream=None) -> None:
+    import torch
+    _check(load().oz2_ctx_sgemm_prepared(_ctx(ctx), C.c_void_p(left.handle), C.c_void_p(right.handle),
+                                         float(alpha), float(beta), _dev(C_, torch.float32), ldc,
+                                         _stream(stream)), "oz2_ctx_sgemm_prepared")
+
+
+def oz2_ctx_workspace_bytes(ctx, m, n, k, num_moduli) -> int:
+    return int(load().oz2_ctx_workspace_bytes(_ctx(ctx), m, n, k, int(num_moduli)))
+
+
+def oz2_ctx_workspace_min_bytes(ctx, m, n, k, num_moduli) -> int:
+    return int(load().oz2_ctx_workspace_min_bytes(_ctx(ctx), m, n, k, int(num_moduli)))
+
+
+def oz2_ctx_set_workspace(ctx, buf) -> None:
+    if buf is None:
+        _check(load().oz2_ctx_set_workspace(_ctx(ctx), C.c_void_p(0), 0), "oz2_ctx_set_workspace")
+    else:
+        _check(load().oz2_ctx_set_workspace(_ctx(ctx), _dev(buf), buf.numel() * buf.element_size()),
+               "oz2_ctx_set_workspace")
+
+
+def oz2_ctx_set_workspace_limit(ctx, nbytes: int) -> None:
+    _check(load().oz2_ctx_set_workspace_limit(_ctx(ctx), int(nbytes)), "oz2_ctx_set_workspace_limit")
+
+
+def oz2_ctx_plan_panels(ctx, m, n, k, num_moduli, workspace_bytes) -> Tuple[int, int, int]:
+    pr, pc, cnt = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(load().oz2_ctx_plan_panels(_ctx(ctx), m, n, k, int(num_moduli), int(workspace_bytes), C.byref(pr),
+                                      C.byref(pc), C.byref(cnt)), "oz2_ctx_plan_panels")
+    return int(pr.value), int(pc.value), int(cnt.value)
+
+
+def oz2_ctx_last_panels(ctx) -> Tuple[int, int, int]:
+    pr, pc, cnt = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(load().oz2_ctx_last_panels(_ctx(ctx), C.byref(pr), C.byref(pc), C.byref(cnt)), "oz2_ctx_last_panels")
+    return int(pr.value), int(pc.value), int(cnt.value)
+
+
+def oz2_ctx_release(ctx) -> None:
+    _check(load().oz2_ctx_release(_ctx(ctx)), "oz2_ctx_release")
+
+
+def oz2_ctx_stage_ptr(ctx, stage: int) -> Tuple[int, Tuple[int, int, int, int]]:
+    ptr = C.c_void_p(0)
+    dims = (C.c_int64 * 4)()
+    _check(load().oz2_ctx_stage_ptr(_ctx(ctx), int(stage), C.byref(ptr), dims), "oz2_ctx_stage_ptr")
+    return int(ptr.value or 0), tuple(int(d) for d in dims)
+
+
+def oz2_ctx_last_stage_times_ms(ctx):
+    out = (C.c_float * 4)()
+    _check(load().oz2_ctx_last_stage_times_ms(_ctx(ctx), out), "oz2_ctx_last_stage_times_ms")
+    return [float(x) for x in out]
+
+
+# ------------------------------------------------------------------ conveniences (no arithmetic)
+def stage_tensor(stage: int, copy: bool = True, ctx=None, sync: bool = True):
+    """A stage buffer of the last call (of `ctx`; None: the default context) as a torch tensor.
+    Synchronises the device first unless sync=False.  With copy=False the tensor aliases the
+    library's workspace and is valid until the next call."""
+    import torch
+    ptr, dims = oz2_ctx_stage_ptr(ctx, stage)
+    if sync:
+        torch.cuda.synchronize()
     torch.cuda.synchronize()
     if stage in (OZ2_STAGE_SHIFT_A, OZ2_STAGE_SHIFT_B):
         shape, dtype = (dims[0],), torch.int32
@@ -435,9 +590,9 @@ def _ld(t):
 
 
 def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=None, stream=None,
-           accurate: bool = False):
+           accurate: bool = False, ctx=None):
     """C = alpha * A @ B + beta * out for device tensors that are row-major or transposed views
-    (`X.t()`) of row-major ones, via oz2_dgemm_op / oz2_sgemm_op."""
+    (`X.t()`) of row-major ones, via oz2_ctx_dgemm / oz2_ctx_sgemm (ctx None: the default context)."""
     import torch
     if A.dim() != 2 or B.dim() != 2 or A.shape[1] != B.shape[0] or A.dtype != B.dtype:
         raise ValueError("A (m x k) and B (k x n) of one dtype expected")
@@ -452,7 +607,7 @@ def matmul(A, B, num_moduli: int, alpha: float = 1.0, beta: float = 0.0, out=Non
     if out.stride(1) != 1 and n > 1:
         raise ValueError("row-major `out` expected")
     ldc = out.stride(0) if m > 1 else max(n, 1)
-    fn = oz2_dgemm_op if A.dtype == torch.float64 else oz2_sgemm_op
-    fn(OZ2_OP_T if ta else OZ2_OP_N, OZ2_OP_T if tb else OZ2_OP_N, accurate, m, n, k, alpha, A, lda, B, ldb,
+    fn = oz2_ctx_dgemm if A.dtype == torch.float64 else oz2_ctx_sgemm
+    fn(ctx, OZ2_OP_T if ta else OZ2_OP_N, OZ2_OP_T if tb else OZ2_OP_N, accurate, m, n, k, alpha, A, lda, B, ldb,
        beta, out, ldc, num_moduli, stream)
     return out

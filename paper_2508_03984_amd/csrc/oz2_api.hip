@@ -1,5 +1,6 @@
 // C ABI of the library (declared in include/oz2.h): argument checks, workspace
-// carving and the launch sequence of Algorithm 1 on the caller's stream.
+// carving and the launch sequence of Algorithm 1 on the caller's stream.  All state lives in
+// contexts (oz2_context); the entry points without a context use the process's default one.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -12,116 +13,56 @@
 #include "../../include/oz2.h"
 #include "oz2_constants.hpp"
 #include "oz2_kernels.hpp"
+#include "oz2_plan.hpp"
 
-namespace {
-
-using namespace oz2;
-
-inline int64_t round_up(int64_t x, int64_t to) { return (x + to - 1) / to * to; }
-inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
-
-// Workspace: [scratch | tA | tB | residues of A | residues of B | products].  A product of
-// prepared operands uses the product part only (its shifts and residues live in the operands).
-struct Layout {
-    int64_t m, n, k, Mp, Np, Kp;
-    int N;
-    bool prod_u8;
-    size_t off_bt, off_ta, off_tb, off_ra, off_rb, off_prod;
-    size_t prod_whole, prod_min;           // product part: all of C at once / one 256 x 256 panel
-};
-
-// Bytes of product workspace per entry of C: N planes of uint8, or of int32 (diagnostic form).
-inline size_t bytes_per_entry(int N, bool prod_u8) { return (size_t)N * (prod_u8 ? 1 : 4); }
-
-Layout make_layout(int64_t m, int64_t n, int64_t k, int N, bool prod_u8, bool with_operands = true) {
-    Layout L{};
-    L.m = m; L.n = n; L.k = k; L.N = N; L.prod_u8 = prod_u8;
-    L.Mp = round_up(m, kPadMN); L.Np = round_up(n, kPadMN); L.Kp = round_up(k, kPadK);
-    size_t o = 0;
-    if (with_operands) {
-        L.off_bt = o;   o += align256(std::max(column_scratch_bytes(std::max(m, n)), accurate_scratch_bytes(m, n)));
-        L.off_ta = o;   o += align256((size_t)m * 4);
-        L.off_tb = o;   o += align256((size_t)n * 4);
-        L.off_ra = o;   o += align256((size_t)N * L.Mp * L.Kp);
-        L.off_rb = o;   o += align256((size_t)N * L.Np * L.Kp);
-    }
-    L.off_prod = o;
-    L.prod_whole = align256((size_t)L.Mp * L.Np * bytes_per_entry(N, prod_u8));
-    L.prod_min = align256((size_t)kPadMN * kPadMN * bytes_per_entry(N, prod_u8));
-    return L;
-}
-
-// How C is cut: panels of (pr x pc) entries (multiples of 256; the last ones may be smaller).
-struct Panels {
-    int64_t pr, pc, count;
-};
-
-// Panels whose N product planes fit into `avail` bytes: all of C if possible, otherwise as
-// square as the shape allows (the INT8 GEMM re-reads a row panel of the A slices once per
-// column panel and vice versa).  Panel sides below the full side are 256 times a power of two
-// up to 4096 and multiples of 4096 beyond: then the workgroups of a launch (tiles x moduli) fill
-// the 256 compute units evenly and the GEMM's tile map stays XCD-aware (measured at 16384^3,
-// N = 16: panels of 2816^2 72 ms against 67.8 ms for 2048^2 and 62.9 ms for 4096^2).
-inline int64_t panel_side(int64_t w) {
-    if (w >= 4096) return w / 4096 * 4096;
-    int64_t s = kPadMN;
-    while (2 * s <= w) s *= 2;
-    return s;
-}
-
-bool plan_panels(const Layout &L, size_t avail, Panels *out) {
-    const size_t per = bytes_per_entry(L.N, L.prod_u8);
-    if (avail >= L.prod_whole) { *out = Panels{L.Mp, L.Np, 1}; return true; }
-    const int64_t entries = (int64_t)(avail / per);
-    if (entries < kPadMN * kPadMN) return false;
-    int64_t s = kPadMN;
-    while ((s + kPadMN) * (s + kPadMN) <= entries) s += kPadMN;
-    s = panel_side(s);
-    int64_t pr = std::min(L.Mp, s), pc = std::min(L.Np, s);
-    auto widen = [&](int64_t other, int64_t now, int64_t limit) {   // what fits beside `other`
-        const int64_t w = entries / other / kPadMN * kPadMN;
-        return std::max(now, w >= limit ? limit : panel_side(w));
-    };
-    pc = widen(pr, pc, L.Np);
-    pr = widen(pc, pr, L.Mp);
-    *out = Panels{pr, pc, ((L.Mp + pr - 1) / pr) * ((L.Np + pc - 1) / pc)};
-    return true;
-}
-
-struct State {
-    std::mutex mu;
+// Everything a product call keeps between its launches and for the diagnostics that follow it:
+// one workspace, the options, the events of the per-stage timing and the second stream of the
+// overlapped form.  Calls on one context share its workspace, so they must be ordered by the
+// caller (one stream, or events); calls on different contexts are independent.
+struct oz2_context {
+    std::mutex mu;                         // guards the host-side fields below, not the device buffers
     char *ws = nullptr;
     size_t ws_bytes = 0;
     bool ws_owned = false;
     int ws_device = -1;                    // device of the library's own buffer
     size_t ws_limit = 0;                   // for the library's own buffer; 0 = none
-    Layout last{};
-    Panels last_panels{0, 0, 0};
+    oz2::Layout last{};
+    oz2::Panels last_panels{0, 0, 0};
     bool have_last = false;                // shifts and residues of the last call are in the workspace
     bool have_last_prod = false;           // ... and so are all its products
     bool have_panels = false;
     bool profiling = false;
     bool int32_products = false;           // diagnostic form: keep C'_s as int32
+    bool overlap = false;                  // conversion of later panels beside the GEMMs (run_overlapped)
+    bool small_conversion = true;          // fused conversion launches for small problems (oz2_small.hip)
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     bool ev_recorded = false;
-    // overlapped form (run_overlapped): a second stream, ordering events, and with profiling
-    // one pair of timing events per panel around its INT8 GEMMs
-    bool overlap = true;
-    bool small_conversion = true;   // fused conversion launches for small problems (oz2_small.hip)
+    // overlapped form: a second stream, ordering events, and with profiling one pair of timing
+    // events per panel around its INT8 GEMMs
     hipStream_t aux = nullptr;
     std::vector<hipEvent_t> sync_ev, time_ev;
     int64_t last_overlapped_panels = 0;    // > 0: the last call ran overlapped, with this many panels
     int res_device = -1;                   // device the events and the second stream belong to
 };
-State g;
 
-bool supported(int64_t k, int N) {
-    return N >= OZ2_MIN_MODULI && N <= OZ2_MAX_MODULI && k <= OZ2_MAX_K_BLOCKED;
+namespace {
+
+using namespace oz2;
+typedef oz2_context Ctx;
+
+// The context behind the entry points that take none.  It is never destroyed: at process exit the
+// HIP runtime may already be gone, and the driver reclaims the device memory anyway.
+Ctx &default_context() {
+    static Ctx *c = new Ctx();
+    return *c;
 }
+inline Ctx &resolve(oz2_context *c) { return c ? *c : default_context(); }
 
 // Makes at least `need_min` bytes of workspace available, `need_whole` if nothing limits it;
-// *have receives the bytes the call may use.
-oz2_status ensure_workspace(size_t need_whole, size_t need_min, size_t *have) {
+// *have receives the bytes the call may use.  Growing the library's own buffer (or moving it to
+// another device) waits for the device, frees and allocates: the only synchronising step of a
+// product call, and only when the buffer is too small.
+oz2_status ensure_workspace(Ctx &g, size_t need_whole, size_t need_min, size_t *have) {
     if (g.ws && !g.ws_owned) {                                // caller-owned: take it as it is
         if (g.ws_bytes < need_min) return OZ2_WORKSPACE;
         *have = g.ws_bytes;
@@ -154,7 +95,7 @@ oz2_status ensure_workspace(size_t need_whole, size_t need_min, size_t *have) {
 
 // Events and the second stream belong to one device: a call made with another device current
 // drops them (they are created again when needed).
-void drop_device_resources() {
+void drop_device_resources(Ctx &g) {
     for (auto &e : g.ev) if (e) { (void)hipEventDestroy(e); e = nullptr; }
     for (auto &e : g.sync_ev) (void)hipEventDestroy(e);
     for (auto &e : g.time_ev) (void)hipEventDestroy(e);
@@ -163,17 +104,17 @@ void drop_device_resources() {
     g.ev_recorded = false; g.last_overlapped_panels = 0;
 }
 
-oz2_status bind_device_resources() {
+oz2_status bind_device_resources(Ctx &g) {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return OZ2_HIP_ERROR;
     if (g.res_device != dev) {
-        drop_device_resources();
+        drop_device_resources(g);
         g.res_device = dev;
     }
     return OZ2_OK;
 }
 
-oz2_status mark(int i, hipStream_t stream) {
+oz2_status mark(Ctx &g, int i, hipStream_t stream) {
     if (!g.profiling) return OZ2_OK;
     if (!g.ev[i]) OZ2_TRY(hipEventCreate(&g.ev[i]));
     OZ2_TRY(hipEventRecord(g.ev[i], stream));
@@ -216,7 +157,7 @@ hipError_t launch_block_residues(const T *X, int64_t ld, bool k_contiguous, int6
 // INT32 accumulation for k <= 2^17; a longer contraction is cut into K ranges of at most 2^17
 // whose reduced results are folded together modulo p_s), then its accumulation and unscaling.
 template <typename T>
-oz2_status run_products(const Layout &L, const Panels &P, const int8_t *rA, const int8_t *rB,
+oz2_status run_products(Ctx &g, const Layout &L, const Panels &P, const int8_t *rA, const int8_t *rB,
                         const int32_t *tA, const int32_t *tB, void *prod, const ModArgs &ma,
                         double alpha, double beta, T *C, int64_t ldc, hipStream_t stream) {
     int64_t done = 0;
@@ -230,18 +171,15 @@ oz2_status run_products(const Layout &L, const Panels &P, const int8_t *rA, cons
                                          &ma, stream, &pn));
             }
             if (++done == P.count)                            // stage times: the last accumulation only
-                if (oz2_status st = mark(3, stream)) return st;
+                if (oz2_status st = mark(g, 3, stream)) return st;
             OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, rows, cols, std::min(L.m - row0, rows),
                                        std::min(L.n - col0, cols), tA + row0, tB + col0, ma, alpha, beta,
                                        C + row0 * ldc + col0, ldc, stream));
         }
-    return mark(4, stream);
+    return mark(g, 4, stream);
 }
 
-// Side of a panel of the overlapped form: the INT8 GEMM loses nothing down to 4096 x 4096.
-constexpr int64_t kOverlapPanel = 4096;
-
-oz2_status overlap_resources(size_t n_sync, size_t n_time) {
+oz2_status overlap_resources(Ctx &g, size_t n_sync, size_t n_time) {
     if (!g.aux) OZ2_TRY(hipStreamCreateWithFlags(&g.aux, hipStreamNonBlocking));   // default priority
     while (g.sync_ev.size() < n_sync) {
         hipEvent_t e = nullptr;
@@ -268,14 +206,14 @@ oz2_status overlap_resources(size_t n_sync, size_t n_time) {
 // GEMMs lose more to the accumulations beside them than those take on their own), and so were
 // launches made "thin" for the registers a resident GEMM workgroup leaves free (64.6 ms).
 template <typename T>
-oz2_status run_overlapped(const Layout &L, const Panels &P, const T *A, int64_t lda, bool a_kc, const T *B,
+oz2_status run_overlapped(Ctx &g, const Layout &L, const Panels &P, const T *A, int64_t lda, bool a_kc, const T *B,
                           int64_t ldb, bool b_kc, const int32_t *tA, const int32_t *tB, int8_t *rA,
                           int8_t *rB, void *prod, const ModArgs &ma, double alpha, double beta, T *C,
                           int64_t ldc, hipStream_t stream) {
     const int64_t nR = (L.Mp + P.pr - 1) / P.pr, nC = (L.Np + P.pc - 1) / P.pc, count = nR * nC;
     // events: [0] fork, [1 .. nR] residues of the A blocks, then nC for the B blocks
     const size_t eA = 1, eB = eA + (size_t)nR;
-    if (oz2_status st = overlap_resources(eB + (size_t)nC, g.profiling ? 2 * (size_t)count : 0)) return st;
+    if (oz2_status st = overlap_resources(g, eB + (size_t)nC, g.profiling ? 2 * (size_t)count : 0)) return st;
     hipEvent_t *ev = g.sync_ev.data();
     hipStream_t aux = g.aux;
     OZ2_TRY(hipEventRecord(ev[0], stream));
@@ -319,55 +257,43 @@ oz2_status run_overlapped(const Layout &L, const Panels &P, const T *A, int64_t 
     }
     // The caller's stream has waited for every event of the second one: the two have joined.
     g.last_overlapped_panels = count;
-    return mark(4, stream);
+    return mark(g, 4, stream);
 }
 
 template <typename T>
-oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, double alpha, const T *A,
+oz2_status gemm_impl(Ctx &g, int opA, int opB, int64_t m, int64_t n, int64_t k, double alpha, const T *A,
                      int64_t lda, const T *B, int64_t ldb, double beta, T *C, int64_t ldc, int N,
                      hipStream_t stream, bool accurate) {
-    if (m < 0 || n < 0 || k < 0 || (opA != OZ2_OP_N && opA != OZ2_OP_T) ||
-        (opB != OZ2_OP_N && opB != OZ2_OP_T))
-        return OZ2_INVALID_ARG;
-    if (!supported(k, N) || (accurate && k > OZ2_MAX_K)) return OZ2_UNSUPPORTED;
-    if (m == 0 || n == 0) return OZ2_OK;
-    if (!C || ldc < n) return OZ2_INVALID_ARG;
-    if (k == 0) {
+    Action action;
+    if (oz2_status st = check_gemm_args(opA, opB, m, n, k, A, lda, B, ldb, C, ldc, N, &action)) return st;
+    if (action == Action::kNothing) return OZ2_OK;
+    if (action == Action::kScaleC) {
         OZ2_TRY(launch_scale_c<T>(C, ldc, m, n, beta, stream));
         return OZ2_OK;
     }
     const bool a_kc = opA == OZ2_OP_N, b_kc = opB == OZ2_OP_T;   // is k the contiguous index?
-    if (!A || !B || lda < (a_kc ? k : m) || ldb < (b_kc ? k : n)) return OZ2_INVALID_ARG;
 
     std::lock_guard<std::mutex> lock(g.mu);
-    if (oz2_status st = bind_device_resources()) return st;
+    if (oz2_status st = bind_device_resources(g)) return st;
     const bool is_double = sizeof(T) == 8;
     const Table &tab = table(N, is_double);
     const ModArgs ma = make_mod_args(tab, accurate);
     const ShiftArgs sa = make_shift_args(tab);
     const Layout L = make_layout(m, n, k, N, !g.int32_products);
-    // Large products with a long contraction run overlapped (run_overlapped): panels of at most
-    // 4096 x 4096, at least four of them, k >= 8192 and k x panels >= 9 x 8192.  With less the
-    // conversion that precedes the first GEMM, or what the shorter GEMM launches lose, outweighs
-    // what is hidden (measured: 16 x 16384^3 -2.9 %, 8192 x 8192 x 65536 -3 %, but 8192^3 +1.5 %,
-    // 16384 x 16384 x 4096 +3 %).  Such a call needs the products of one panel only, so the
-    // library's own workspace is sized for that.
+    // The overlapped form (an option, see run_overlapped) works through C in panels of at most
+    // 4096 x 4096 whatever the workspace could hold, so the library's own buffer is then sized for
+    // the products of one such panel.
     const int64_t side_r = std::min(L.Mp, kOverlapPanel), side_c = std::min(L.Np, kOverlapPanel);
     const int64_t panels_4096 = ((L.Mp + side_r - 1) / side_r) * ((L.Np + side_c - 1) / side_c);
-    auto overlap_pays = [&](int64_t panels) {
-        return g.overlap && panels >= 4 && panels <= 4096 && L.Kp >= 8192 && L.Kp * panels >= (int64_t)9 * 8192;
-    };
-    const size_t prod_want = overlap_pays(panels_4096)
+    const size_t prod_want = g.overlap && overlap_applies(L.Kp, panels_4096)
                                  ? align256((size_t)side_r * side_c * bytes_per_entry(N, L.prod_u8))
                                  : L.prod_whole;
     size_t have = 0;
     Panels P{};
-    if (oz2_status st = ensure_workspace(L.off_prod + prod_want, L.off_prod + L.prod_min, &have)) return st;
+    if (oz2_status st = ensure_workspace(g, L.off_prod + prod_want, L.off_prod + L.prod_min, &have)) return st;
     if (!plan_panels(L, have - L.off_prod, &P)) return OZ2_WORKSPACE;
-    Panels Po = P;
-    Po.pr = std::min(Po.pr, kOverlapPanel); Po.pc = std::min(Po.pc, kOverlapPanel);
-    Po.count = ((L.Mp + Po.pr - 1) / Po.pr) * ((L.Np + Po.pc - 1) / Po.pc);
-    const bool overlapped = overlap_pays(Po.count);        // a workspace limit may have made the panels smaller
+    const Panels Po = overlap_panels(L, P);                // a workspace limit may have made the panels smaller
+    const bool overlapped = g.overlap && overlap_applies(L.Kp, Po.count);
     if (overlapped) P = Po;
     g.last = L; g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0;
     g.have_last = true; g.have_last_prod = P.count == 1; g.ev_recorded = false;
@@ -382,26 +308,34 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
     // Small problems: the conversion of both factors in two launches instead of seven (and
     // likewise the passes of accurate mode that precede Cbar).
     const bool small = g.small_conversion && small_conversion_applies(m, n, k);
-    if (oz2_status st = mark(0, stream)) return st;
+    if (oz2_status st = mark(g, 0, stream)) return st;
     if (accurate) {
         // Section 4.2, accurate mode: 7-bit matrices into slice 0; of Cbar only the row and
-        // column maxima are kept (it is never stored).
-        OZ2_TRY(launch_accurate_prescale<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, scratch, rA, rB, L.Mp,
+        // column maxima are kept (it is never stored).  A contraction beyond 2^17 is cut into K
+        // ranges (Section 4.3, last sentence), each an exact INT32 product with maxima of its own;
+        // their sum bounds the maxima of the whole Cbar from above, which is all that the chain of
+        // inequalities behind the scale vectors needs.
+        const int ranges = (int)((L.Kp + OZ2_MAX_K - 1) / OZ2_MAX_K);
+        OZ2_TRY(launch_accurate_prescale<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, ranges, scratch, rA, rB, L.Mp,
                                             L.Np, L.Kp, small, stream));
-        int *row_max = nullptr, *col_max = nullptr;
-        accurate_maxima(scratch, m, n, &row_max, &col_max);
         const GemmPanel all{0, L.Mp, 0, L.Np, L.Np, L.Mp * L.Np};      // nothing is stored: no panels needed
-        OZ2_TRY(launch_int8_gemm_maxima(rA, rB, L.Mp, L.Np, L.Kp, all, m, n, row_max, col_max, stream));
-        OZ2_TRY(launch_accurate_finish(m, n, make_accu_shift_args(tab), scratch, tA, tB, stream));
+        for (int r = 0; r < ranges; ++r) {
+            int *row_max = nullptr, *col_max = nullptr;
+            accurate_maxima(scratch, m, n, r, &row_max, &col_max);
+            const int64_t k0 = (int64_t)r * OZ2_MAX_K;
+            OZ2_TRY(launch_int8_gemm_maxima(rA, rB, L.Mp, L.Np, L.Kp, k0, std::min<int64_t>(OZ2_MAX_K, L.Kp - k0),
+                                            all, m, n, row_max, col_max, stream));
+        }
+        OZ2_TRY(launch_accurate_finish(m, n, ranges, make_accu_shift_args(tab), scratch, tA, tB, stream));
     } else if (small) {
         OZ2_TRY(launch_small_shifts<T>(A, lda, a_kc, B, ldb, b_kc, m, n, k, sa, tA, tB, stream));
     } else {
         OZ2_TRY(launch_fast_shifts<T>(A, lda, a_kc, m, k, sa, scratch, tA, stream));
         OZ2_TRY(launch_fast_shifts<T>(B, ldb, b_kc, n, k, sa, scratch, tB, stream));
     }
-    if (oz2_status st = mark(1, stream)) return st;
+    if (oz2_status st = mark(g, 1, stream)) return st;
     if (overlapped) {
-        if (oz2_status st = run_overlapped<T>(L, P, A, lda, a_kc, B, ldb, b_kc, tA, tB, rA, rB, prod, ma, alpha,
+        if (oz2_status st = run_overlapped<T>(g, L, P, A, lda, a_kc, B, ldb, b_kc, tA, tB, rA, rB, prod, ma, alpha,
                                               beta, C, ldc, stream))
             return st;
         g.ev_recorded = g.profiling;
@@ -414,8 +348,8 @@ oz2_status gemm_impl(oz2_op opA, oz2_op opB, int64_t m, int64_t n, int64_t k, do
         OZ2_TRY(launch_any_residues<T>(A, lda, a_kc, m, k, tA, ma, rA, L.Mp, L.Kp, stream));
         OZ2_TRY(launch_any_residues<T>(B, ldb, b_kc, n, k, tB, ma, rB, L.Np, L.Kp, stream));
     }
-    if (oz2_status st = mark(2, stream)) return st;
-    if (oz2_status st = run_products<T>(L, P, rA, rB, tA, tB, prod, ma, alpha, beta, C, ldc, stream)) return st;
+    if (oz2_status st = mark(g, 2, stream)) return st;
+    if (oz2_status st = run_products<T>(g, L, P, rA, rB, tA, tB, prod, ma, alpha, beta, C, ldc, stream)) return st;
     g.ev_recorded = g.profiling;
     return OZ2_OK;
 }
@@ -437,7 +371,7 @@ struct oz2_operand {
 namespace {
 
 template <typename T>
-oz2_status prepare_impl(int side, oz2_op op, int64_t rows, int64_t k, const T *X, int64_t ld, int N,
+oz2_status prepare_impl(int side, int op, int64_t rows, int64_t k, const T *X, int64_t ld, int N,
                         hipStream_t stream, oz2_operand **out) {
     if (!out || (side != 0 && side != 1) || (op != OZ2_OP_N && op != OZ2_OP_T) || rows < 1 || k < 1 || !X)
         return OZ2_INVALID_ARG;
@@ -470,74 +404,252 @@ oz2_status prepare_impl(int side, oz2_op op, int64_t rows, int64_t k, const T *X
 }
 
 template <typename T>
-oz2_status prepared_impl(const oz2_operand *l, const oz2_operand *r, double alpha, double beta, T *C,
+oz2_status prepared_impl(Ctx &g, const oz2_operand *l, const oz2_operand *r, double alpha, double beta, T *C,
                          int64_t ldc, hipStream_t stream) {
     const bool is_double = sizeof(T) == 8;
     if (!l || !r || l->side != 0 || r->side != 1 || l->k != r->k || l->N != r->N ||
         l->is_double != is_double || r->is_double != is_double || !C || ldc < r->rows)
         return OZ2_INVALID_ARG;
     std::lock_guard<std::mutex> lock(g.mu);
-    if (oz2_status st = bind_device_resources()) return st;
+    if (oz2_status st = bind_device_resources(g)) return st;
     const ModArgs ma = make_mod_args(table(l->N, is_double), false);
     const Layout L = make_layout(l->rows, r->rows, l->k, l->N, !g.int32_products, false);
     size_t have = 0;
     Panels P{};
-    if (oz2_status st = ensure_workspace(L.prod_whole, L.prod_min, &have)) return st;
+    if (oz2_status st = ensure_workspace(g, L.prod_whole, L.prod_min, &have)) return st;
     if (!plan_panels(L, have, &P)) return OZ2_WORKSPACE;
     g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0;
     g.have_last = g.have_last_prod = false; g.ev_recorded = false;
     for (int i = 0; i < 3; ++i)
-        if (oz2_status st = mark(i, stream)) return st;
-    if (oz2_status st = run_products<T>(L, P, l->res, r->res, l->t, r->t, g.ws, ma, alpha, beta, C, ldc, stream))
+        if (oz2_status st = mark(g, i, stream)) return st;
+    if (oz2_status st = run_products<T>(g, L, P, l->res, r->res, l->t, r->t, g.ws, ma, alpha, beta, C, ldc, stream))
         return st;
     g.ev_recorded = g.profiling;
     return OZ2_OK;
+}
+
+void release_workspace(Ctx &g) {                           // g.mu is held
+    if (g.ws && g.ws_owned) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(g.ws);
+    }
+    g.ws = nullptr; g.ws_bytes = 0; g.ws_owned = false; g.have_last = g.have_last_prod = false;
+    drop_device_resources(g);
+    g.res_device = -1;
 }
 
 }  // namespace
 
 extern "C" {
 
+// ------------------------------------------------------------------ contexts
+oz2_status oz2_create(oz2_context **out) {
+    if (!out) return OZ2_INVALID_ARG;
+    oz2_context *c = new (std::nothrow) oz2_context();
+    if (!c) return OZ2_WORKSPACE;
+    *out = c;
+    return OZ2_OK;
+}
+
+oz2_status oz2_destroy(oz2_context *ctx) {
+    if (!ctx) return OZ2_INVALID_ARG;
+    {
+        std::lock_guard<std::mutex> lock(ctx->mu);
+        release_workspace(*ctx);
+    }
+    delete ctx;
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_set_option(oz2_context *ctx, oz2_option option, int value) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    const bool on = value != 0;
+    switch (option) {
+    case OZ2_OPT_INT32_PRODUCTS: g.int32_products = on; break;
+    case OZ2_OPT_OVERLAP: g.overlap = on; break;
+    case OZ2_OPT_SMALL_CONVERSION: g.small_conversion = on; break;
+    case OZ2_OPT_PROFILING: g.profiling = on; if (!on) g.ev_recorded = false; break;
+    default: return OZ2_INVALID_ARG;
+    }
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_dgemm(oz2_context *ctx, oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                         double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
+                         double beta, double *C, int64_t ldc, int num_moduli, hipStream_t stream) {
+    return gemm_impl<double>(resolve(ctx), opA, opB, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli,
+                             stream, accurate != 0);
+}
+
+oz2_status oz2_ctx_sgemm(oz2_context *ctx, oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
+                         float alpha, const float *A, int64_t lda, const float *B, int64_t ldb, float beta,
+                         float *C, int64_t ldc, int num_moduli, hipStream_t stream) {
+    return gemm_impl<float>(resolve(ctx), opA, opB, m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
+                            num_moduli, stream, accurate != 0);
+}
+
+oz2_status oz2_ctx_dgemm_prepared(oz2_context *ctx, const oz2_operand *left, const oz2_operand *right,
+                                  double alpha, double beta, double *C, int64_t ldc, hipStream_t stream) {
+    return prepared_impl<double>(resolve(ctx), left, right, alpha, beta, C, ldc, stream);
+}
+
+oz2_status oz2_ctx_sgemm_prepared(oz2_context *ctx, const oz2_operand *left, const oz2_operand *right,
+                                  float alpha, float beta, float *C, int64_t ldc, hipStream_t stream) {
+    return prepared_impl<float>(resolve(ctx), left, right, (double)alpha, (double)beta, C, ldc, stream);
+}
+
+size_t oz2_ctx_workspace_bytes(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli) {
+    if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
+    return L.off_prod + L.prod_whole;
+}
+
+size_t oz2_ctx_workspace_min_bytes(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli) {
+    if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
+    return L.off_prod + L.prod_min;
+}
+
+oz2_status oz2_ctx_set_workspace(oz2_context *ctx, void *dev_ptr, size_t bytes) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255)) return OZ2_INVALID_ARG;
+    if (g.ws && g.ws_owned) {
+        if (hipDeviceSynchronize() != hipSuccess) return OZ2_HIP_ERROR;
+        (void)hipFree(g.ws);
+    }
+    g.ws = static_cast<char *>(dev_ptr);
+    g.ws_bytes = dev_ptr ? bytes : 0;
+    g.ws_owned = false;
+    g.have_last = g.have_last_prod = false;
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_set_workspace_limit(oz2_context *ctx, size_t bytes) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    g.ws_limit = bytes;
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_release(oz2_context *ctx) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    release_workspace(g);
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_plan_panels(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli,
+                               size_t workspace_bytes, int64_t *panel_rows, int64_t *panel_cols, int64_t *count) {
+    if (m <= 0 || n <= 0 || k <= 0) return OZ2_INVALID_ARG;
+    if (!supported(k, num_moduli)) return OZ2_UNSUPPORTED;
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
+    Panels P{};
+    if (workspace_bytes < L.off_prod || !plan_panels(L, workspace_bytes - L.off_prod, &P)) return OZ2_WORKSPACE;
+    if (panel_rows) *panel_rows = P.pr;
+    if (panel_cols) *panel_cols = P.pc;
+    if (count) *count = P.count;
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_last_panels(oz2_context *ctx, int64_t *panel_rows, int64_t *panel_cols, int64_t *count) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (!g.have_panels) return OZ2_INVALID_ARG;
+    if (panel_rows) *panel_rows = g.last_panels.pr;
+    if (panel_cols) *panel_cols = g.last_panels.pc;
+    if (count) *count = g.last_panels.count;
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_stage_ptr(oz2_context *ctx, int stage, void **dev_ptr, int64_t *dims) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (!g.have_last || !dev_ptr || !dims) return OZ2_INVALID_ARG;
+    const Layout &L = g.last;
+    switch (stage) {
+    case OZ2_STAGE_SHIFT_A: *dev_ptr = g.ws + L.off_ta; dims[0] = L.m; dims[1] = dims[2] = dims[3] = 0; break;
+    case OZ2_STAGE_SHIFT_B: *dev_ptr = g.ws + L.off_tb; dims[0] = L.n; dims[1] = dims[2] = dims[3] = 0; break;
+    case OZ2_STAGE_RES_A: *dev_ptr = g.ws + L.off_ra; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Kp; dims[3] = L.m; break;
+    case OZ2_STAGE_RES_B: *dev_ptr = g.ws + L.off_rb; dims[0] = L.N; dims[1] = L.Np; dims[2] = L.Kp; dims[3] = L.n; break;
+    case OZ2_STAGE_PROD:
+        if (L.prod_u8 || !g.have_last_prod) return OZ2_INVALID_ARG;                // not kept in this form: see OZ2_OPT_INT32_PRODUCTS
+        *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
+    case OZ2_STAGE_U:
+        if (!L.prod_u8 || !g.have_last_prod) return OZ2_INVALID_ARG;
+        *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
+    default: return OZ2_INVALID_ARG;
+    }
+    return OZ2_OK;
+}
+
+oz2_status oz2_ctx_last_stage_times_ms(oz2_context *ctx, float *out4) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (!out4 || !g.ev_recorded) return OZ2_INVALID_ARG;
+    OZ2_TRY(hipEventSynchronize(g.ev[4]));
+    if (g.last_overlapped_panels > 0) {
+        // overlapped call: shifts; what of the residues was exposed before the first GEMM; the
+        // sum of the panels' GEMM launches; the rest (gaps between them, the last accumulation)
+        float after_shifts = 0.f, gemm = 0.f;
+        OZ2_TRY(hipEventElapsedTime(&out4[0], g.ev[0], g.ev[1]));
+        OZ2_TRY(hipEventElapsedTime(&out4[1], g.ev[1], g.time_ev[0]));
+        OZ2_TRY(hipEventElapsedTime(&after_shifts, g.ev[1], g.ev[4]));
+        for (int64_t p = 0; p < g.last_overlapped_panels; ++p) {
+            float t = 0.f;
+            OZ2_TRY(hipEventElapsedTime(&t, g.time_ev[2 * p], g.time_ev[2 * p + 1]));
+            gemm += t;
+        }
+        out4[2] = gemm;
+        out4[3] = after_shifts - out4[1] - gemm;
+        return OZ2_OK;
+    }
+    for (int i = 0; i < 4; ++i) OZ2_TRY(hipEventElapsedTime(&out4[i], g.ev[i], g.ev[i + 1]));
+    return OZ2_OK;
+}
+
+// ------------------------------------------------------------------ the same on the default context
 oz2_status oz2_dgemm(int64_t m, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
                      const double *B, int64_t ldb, double beta, double *C, int64_t ldc,
                      int num_moduli, hipStream_t stream) {
-    return gemm_impl<double>(OZ2_OP_N, OZ2_OP_N, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli,
-                             stream, false);
-}
-
-oz2_status oz2_dgemm_accurate(int64_t m, int64_t n, int64_t k, double alpha, const double *A,
-                              int64_t lda, const double *B, int64_t ldb, double beta, double *C,
-                              int64_t ldc, int num_moduli, hipStream_t stream) {
-    return gemm_impl<double>(OZ2_OP_N, OZ2_OP_N, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli,
-                             stream, true);
-}
-
-oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha, const float *A,
-                              int64_t lda, const float *B, int64_t ldb, float beta, float *C,
-                              int64_t ldc, int num_moduli, hipStream_t stream) {
-    return gemm_impl<float>(OZ2_OP_N, OZ2_OP_N, m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
-                            num_moduli, stream, true);
+    return oz2_ctx_dgemm(nullptr, OZ2_OP_N, OZ2_OP_N, 0, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
 }
 
 oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha, const float *A, int64_t lda,
                      const float *B, int64_t ldb, float beta, float *C, int64_t ldc,
                      int num_moduli, hipStream_t stream) {
-    return gemm_impl<float>(OZ2_OP_N, OZ2_OP_N, m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
-                            num_moduli, stream, false);
+    return oz2_ctx_sgemm(nullptr, OZ2_OP_N, OZ2_OP_N, 0, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
+}
+
+oz2_status oz2_dgemm_accurate(int64_t m, int64_t n, int64_t k, double alpha, const double *A,
+                              int64_t lda, const double *B, int64_t ldb, double beta, double *C,
+                              int64_t ldc, int num_moduli, hipStream_t stream) {
+    return oz2_ctx_dgemm(nullptr, OZ2_OP_N, OZ2_OP_N, 1, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
+}
+
+oz2_status oz2_sgemm_accurate(int64_t m, int64_t n, int64_t k, float alpha, const float *A,
+                              int64_t lda, const float *B, int64_t ldb, float beta, float *C,
+                              int64_t ldc, int num_moduli, hipStream_t stream) {
+    return oz2_ctx_sgemm(nullptr, OZ2_OP_N, OZ2_OP_N, 1, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
 }
 
 oz2_status oz2_dgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
                         double alpha, const double *A, int64_t lda, const double *B, int64_t ldb,
                         double beta, double *C, int64_t ldc, int num_moduli, hipStream_t stream) {
-    return gemm_impl<double>(opA, opB, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream,
-                             accurate != 0);
+    return oz2_ctx_dgemm(nullptr, opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
 }
 
 oz2_status oz2_sgemm_op(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
                         float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
                         float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream) {
-    return gemm_impl<float>(opA, opB, m, n, k, (double)alpha, A, lda, B, ldb, (double)beta, C, ldc,
-                            num_moduli, stream, accurate != 0);
+    return oz2_ctx_sgemm(nullptr, opA, opB, accurate, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli, stream);
 }
 
 // Column-major callers: C^T = op(B)^T op(A)^T in row-major terms (see include/oz2.h).
@@ -545,15 +657,13 @@ oz2_status oz2_dgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, i
                               double alpha, const double *A, int64_t lda, const double *B,
                               int64_t ldb, double beta, double *C, int64_t ldc, int num_moduli,
                               hipStream_t stream) {
-    return gemm_impl<double>(opB, opA, n, m, k, alpha, B, ldb, A, lda, beta, C, ldc, num_moduli, stream,
-                             accurate != 0);
+    return oz2_ctx_dgemm(nullptr, opB, opA, accurate, n, m, k, alpha, B, ldb, A, lda, beta, C, ldc, num_moduli, stream);
 }
 
 oz2_status oz2_sgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, int64_t n, int64_t k,
                               float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
                               float beta, float *C, int64_t ldc, int num_moduli, hipStream_t stream) {
-    return gemm_impl<float>(opB, opA, n, m, k, (double)alpha, B, ldb, A, lda, (double)beta, C, ldc,
-                            num_moduli, stream, accurate != 0);
+    return oz2_ctx_sgemm(nullptr, opB, opA, accurate, n, m, k, alpha, B, ldb, A, lda, beta, C, ldc, num_moduli, stream);
 }
 
 oz2_status oz2_prepare_d(int side, oz2_op op, int64_t rows, int64_t k, const double *X, int64_t ld,
@@ -576,80 +686,49 @@ size_t oz2_operand_bytes(const oz2_operand *operand) { return operand ? operand-
 
 oz2_status oz2_dgemm_prepared(const oz2_operand *left, const oz2_operand *right, double alpha,
                               double beta, double *C, int64_t ldc, hipStream_t stream) {
-    return prepared_impl<double>(left, right, alpha, beta, C, ldc, stream);
+    return oz2_ctx_dgemm_prepared(nullptr, left, right, alpha, beta, C, ldc, stream);
 }
 
 oz2_status oz2_sgemm_prepared(const oz2_operand *left, const oz2_operand *right, float alpha,
                               float beta, float *C, int64_t ldc, hipStream_t stream) {
-    return prepared_impl<float>(left, right, (double)alpha, (double)beta, C, ldc, stream);
+    return oz2_ctx_sgemm_prepared(nullptr, left, right, alpha, beta, C, ldc, stream);
 }
 
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double) {
-    if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
     (void)is_double;                                          // the workspace holds no input-typed data
-    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
-    return L.off_prod + L.prod_whole;
+    return oz2_ctx_workspace_bytes(nullptr, m, n, k, num_moduli);
 }
 
 size_t oz2_workspace_min_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double) {
-    if (m <= 0 || n <= 0 || k <= 0 || !supported(k, num_moduli)) return 0;
     (void)is_double;
-    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
-    return L.off_prod + L.prod_min;
+    return oz2_ctx_workspace_min_bytes(nullptr, m, n, k, num_moduli);
 }
 
-void oz2_set_workspace_limit(size_t bytes) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.ws_limit = bytes;
-}
+void oz2_set_workspace_limit(size_t bytes) { (void)oz2_ctx_set_workspace_limit(nullptr, bytes); }
 
 oz2_status oz2_plan_panels(int64_t m, int64_t n, int64_t k, int num_moduli, size_t workspace_bytes,
                            int64_t *panel_rows, int64_t *panel_cols, int64_t *count) {
-    if (m <= 0 || n <= 0 || k <= 0) return OZ2_INVALID_ARG;
-    if (!supported(k, num_moduli)) return OZ2_UNSUPPORTED;
-    const Layout L = make_layout(m, n, k, num_moduli, !g.int32_products);
-    Panels P{};
-    if (workspace_bytes < L.off_prod || !plan_panels(L, workspace_bytes - L.off_prod, &P)) return OZ2_WORKSPACE;
-    if (panel_rows) *panel_rows = P.pr;
-    if (panel_cols) *panel_cols = P.pc;
-    if (count) *count = P.count;
-    return OZ2_OK;
+    return oz2_ctx_plan_panels(nullptr, m, n, k, num_moduli, workspace_bytes, panel_rows, panel_cols, count);
 }
 
 oz2_status oz2_last_panels(int64_t *panel_rows, int64_t *panel_cols, int64_t *count) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    if (!g.have_panels) return OZ2_INVALID_ARG;
-    if (panel_rows) *panel_rows = g.last_panels.pr;
-    if (panel_cols) *panel_cols = g.last_panels.pc;
-    if (count) *count = g.last_panels.count;
-    return OZ2_OK;
+    return oz2_ctx_last_panels(nullptr, panel_rows, panel_cols, count);
 }
 
-oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255)) return OZ2_INVALID_ARG;
-    if (g.ws && g.ws_owned) {
-        if (hipDeviceSynchronize() != hipSuccess) return OZ2_HIP_ERROR;
-        (void)hipFree(g.ws);
-    }
-    g.ws = static_cast<char *>(dev_ptr);
-    g.ws_bytes = dev_ptr ? bytes : 0;
-    g.ws_owned = false;
-    g.have_last = g.have_last_prod = false;
-    return OZ2_OK;
-}
+oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes) { return oz2_ctx_set_workspace(nullptr, dev_ptr, bytes); }
 
-void oz2_release(void) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    if (g.ws && g.ws_owned) {
-        (void)hipDeviceSynchronize();
-        (void)hipFree(g.ws);
-    }
-    g.ws = nullptr; g.ws_bytes = 0; g.ws_owned = false; g.have_last = g.have_last_prod = false;
-    drop_device_resources();
-    g.res_device = -1;
-}
+void oz2_release(void) { (void)oz2_ctx_release(nullptr); }
 
+oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims) { return oz2_ctx_stage_ptr(nullptr, stage, dev_ptr, dims); }
+
+void oz2_set_int32_products(int on) { (void)oz2_ctx_set_option(nullptr, OZ2_OPT_INT32_PRODUCTS, on); }
+void oz2_set_overlap(int on) { (void)oz2_ctx_set_option(nullptr, OZ2_OPT_OVERLAP, on); }
+void oz2_set_small_conversion(int on) { (void)oz2_ctx_set_option(nullptr, OZ2_OPT_SMALL_CONVERSION, on); }
+void oz2_set_profiling(int on) { (void)oz2_ctx_set_option(nullptr, OZ2_OPT_PROFILING, on); }
+
+oz2_status oz2_last_stage_times_ms(float *out4) { return oz2_ctx_last_stage_times_ms(nullptr, out4); }
+
+// ------------------------------------------------------------------ stateless entry points
 oz2_status oz2_constants(int num_moduli, int is_double, int32_t *p, uint32_t *pinv_prime,
                          double *s1, double *s2, double *P1P2Pinv, float *Pfast) {
     if (num_moduli < OZ2_MIN_MODULI || num_moduli > OZ2_MAX_MODULI) return OZ2_UNSUPPORTED;
@@ -692,26 +771,6 @@ int oz2_residue_rounds(int num_moduli, int accurate) {
     return residue_rounds(table(num_moduli, true), accurate != 0);
 }
 
-oz2_status oz2_stage_ptr(int stage, void **dev_ptr, int64_t *dims) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    if (!g.have_last || !dev_ptr || !dims) return OZ2_INVALID_ARG;
-    const Layout &L = g.last;
-    switch (stage) {
-    case OZ2_STAGE_SHIFT_A: *dev_ptr = g.ws + L.off_ta; dims[0] = L.m; dims[1] = dims[2] = dims[3] = 0; break;
-    case OZ2_STAGE_SHIFT_B: *dev_ptr = g.ws + L.off_tb; dims[0] = L.n; dims[1] = dims[2] = dims[3] = 0; break;
-    case OZ2_STAGE_RES_A: *dev_ptr = g.ws + L.off_ra; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Kp; dims[3] = L.m; break;
-    case OZ2_STAGE_RES_B: *dev_ptr = g.ws + L.off_rb; dims[0] = L.N; dims[1] = L.Np; dims[2] = L.Kp; dims[3] = L.n; break;
-    case OZ2_STAGE_PROD:
-        if (L.prod_u8 || !g.have_last_prod) return OZ2_INVALID_ARG;                // not kept in this form: see oz2_set_int32_products
-        *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
-    case OZ2_STAGE_U:
-        if (!L.prod_u8 || !g.have_last_prod) return OZ2_INVALID_ARG;
-        *dev_ptr = g.ws + L.off_prod; dims[0] = L.N; dims[1] = L.Mp; dims[2] = L.Np; dims[3] = 0; break;
-    default: return OZ2_INVALID_ARG;
-    }
-    return OZ2_OK;
-}
-
 oz2_status oz2_int8_gemm(const int8_t *dev_A, const int8_t *dev_B, int32_t *dev_C, int batch,
                          int64_t Mp, int64_t Np, int64_t Kp, hipStream_t stream) {
     if (!dev_A || !dev_B || !dev_C || batch < 1 || batch > 65535 || Mp < kPadMN || Np < kPadMN ||
@@ -722,56 +781,11 @@ oz2_status oz2_int8_gemm(const int8_t *dev_A, const int8_t *dev_B, int32_t *dev_
     return OZ2_OK;
 }
 
-void oz2_set_int32_products(int on) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.int32_products = on != 0;
-}
-
-void oz2_set_overlap(int on) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.overlap = on != 0;
-}
-
-void oz2_set_small_conversion(int on) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.small_conversion = on != 0;
-}
-
-void oz2_set_profiling(int on) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    g.profiling = on != 0;
-    if (!g.profiling) g.ev_recorded = false;
-}
-
-oz2_status oz2_last_stage_times_ms(float *out4) {
-    std::lock_guard<std::mutex> lock(g.mu);
-    if (!out4 || !g.ev_recorded) return OZ2_INVALID_ARG;
-    OZ2_TRY(hipEventSynchronize(g.ev[4]));
-    if (g.last_overlapped_panels > 0) {
-        // overlapped call: shifts; what of the residues was exposed before the first GEMM; the
-        // sum of the panels' GEMM launches; the rest (gaps between them, the last accumulation)
-        float after_shifts = 0.f, gemm = 0.f;
-        OZ2_TRY(hipEventElapsedTime(&out4[0], g.ev[0], g.ev[1]));
-        OZ2_TRY(hipEventElapsedTime(&out4[1], g.ev[1], g.time_ev[0]));
-        OZ2_TRY(hipEventElapsedTime(&after_shifts, g.ev[1], g.ev[4]));
-        for (int64_t p = 0; p < g.last_overlapped_panels; ++p) {
-            float t = 0.f;
-            OZ2_TRY(hipEventElapsedTime(&t, g.time_ev[2 * p], g.time_ev[2 * p + 1]));
-            gemm += t;
-        }
-        out4[2] = gemm;
-        out4[3] = after_shifts - out4[1] - gemm;
-        return OZ2_OK;
-    }
-    for (int i = 0; i < 4; ++i) OZ2_TRY(hipEventElapsedTime(&out4[i], g.ev[i], g.ev[i + 1]));
-    return OZ2_OK;
-}
-
 const char *oz2_status_string(oz2_status s) {
     switch (s) {
     case OZ2_OK: return "ok";
     case OZ2_INVALID_ARG: return "invalid argument";
-    case OZ2_UNSUPPORTED: return "unsupported number of moduli, or k > 2^20 (accurate mode: k > 2^17)";
+    case OZ2_UNSUPPORTED: return "unsupported number of moduli, or k > 2^20";
     case OZ2_WORKSPACE: return "workspace too small or allocation failed";
     case OZ2_HIP_ERROR: return "HIP runtime error";
     }

@@ -106,8 +106,6 @@ __global__ __launch_bounds__(256) void k_residues_cols(const T *__restrict__ X, 
 
 }  // namespace
 
-size_t column_scratch_bytes(int64_t cols) { return (size_t)cols * 16; }
-
 template <typename T>
 hipError_t launch_shifts_cols(const T *X, int64_t ld, int64_t rows, int64_t cols,
                               const ShiftArgs &sa, void *scratch, int32_t *t, hipStream_t stream) {

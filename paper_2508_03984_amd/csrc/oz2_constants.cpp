@@ -241,9 +241,10 @@ Table build(int n, bool is_double) {
     }
     if (t.levels > kMaxLevels) t.levels = -1;               // cannot happen for N <= 20
 
-    // Accurate-mode table over c in [1, 2^29] (k <= 2^17 entries of at most 64 * 64).
+    // Accurate-mode table over c in [1, 2^32]: a K range of 2^17 gives entries of at most
+    // 2^17 * 64 * 64 = 2^29, and up to 8 ranges are summed.
     t.Paccu = (float)(0.5 * log2_wide(Wide::sub(P, Wide::from_u64(1))) - 0.5);
-    const uint64_t Cmax = 1ull << 29;
+    const uint64_t Cmax = 1ull << 32;
     double Pa = (double)t.Paccu;
     t.accu_f_max = accu_level_of(1, Pa);
     t.accu_levels = t.accu_f_max - accu_level_of(Cmax, Pa) + 1;

@@ -23,7 +23,7 @@ struct Table {
     uint64_t theta[kMaxLevels];
     // Accurate mode (Section 4.2): P'_accu = single(0.5*log2(P-1) - 0.5) and the same kind of
     // table for f = floor(P'_accu - 0.51 log2 c) over the integer c = max entry of a row or
-    // column of Abar*Bbar, 1 <= c <= 2^29: f = accu_f_max - min{ j : c <= accu_theta[j] }.
+    // column of Abar*Bbar (summed over K ranges), 1 <= c <= 2^32: f = accu_f_max - min{ j : c <= accu_theta[j] }.
     float Paccu;
     int32_t accu_f_max, accu_levels;
     uint64_t accu_theta[kMaxLevels];

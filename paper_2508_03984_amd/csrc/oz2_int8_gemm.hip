@@ -594,7 +594,7 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm_persistent(const int
 
 // Compute units of the current device (cached per device id).
 int compute_units() {
-    static int cached_dev = -1, cached = 0;
+    static thread_local int cached_dev = -1, cached = 0;     // contexts may launch from several threads
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (dev != cached_dev) {
@@ -612,7 +612,7 @@ hipError_t launch_persistent(const int8_t *A, const int8_t *B, void *C, int batc
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
     static_assert(lds_bytes > 80 * 1024, "one workgroup per compute unit is assumed");
-    static int attr_device = -1;                             // the attribute is per device
+    static thread_local int attr_device = -1;                // the attribute is per device (set again per thread: harmless)
     int dev = -1;
     if (hipError_t e = hipGetDevice(&dev)) return e;
     if (attr_device != dev) {
@@ -644,7 +644,7 @@ hipError_t launch(const int8_t *A, const int8_t *B, void *C, int batch, int64_t 
                   const GemmMods &mods, hipStream_t stream) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * BK;
-    static int attr_device = -1;                             // the attribute is per device
+    static thread_local int attr_device = -1;                // the attribute is per device (set again per thread: harmless)
     int dev = -1;
     if (hipError_t e = hipGetDevice(&dev)) return e;
     if (attr_device != dev) {
@@ -687,12 +687,13 @@ hipError_t launch_out(const int8_t *A, const int8_t *B, void *C, int batch, int6
 }  // namespace
 
 hipError_t launch_int8_gemm_maxima(const int8_t *A, const int8_t *B, int64_t Mp, int64_t Np, int64_t Kp,
-                                   const GemmPanel &pn, int64_t valid_rows, int64_t valid_cols,
-                                   int *row_max, int *col_max, hipStream_t stream) {
+                                   int64_t k_begin, int64_t k_len, const GemmPanel &pn, int64_t valid_rows,
+                                   int64_t valid_cols, int *row_max, int *col_max, hipStream_t stream) {
     if (pn.row0 < 0 || pn.col0 < 0 || pn.rows < kPadMN || pn.cols < kPadMN || pn.row0 % kPadMN ||
         pn.col0 % kPadMN || pn.rows % kPadMN || pn.cols % kPadMN || pn.row0 + pn.rows > Mp ||
         pn.col0 + pn.cols > Np || valid_rows < 0 || valid_cols < 0 || valid_rows > pn.rows ||
-        valid_cols > pn.cols || Kp > kMaxExactK || !row_max || !col_max)
+        valid_cols > pn.cols || k_begin < 0 || k_len < kPadK || k_len > kMaxExactK || k_begin % kPadK ||
+        k_len % kPadK || k_begin + k_len > Kp || !row_max || !col_max)
         return hipErrorInvalidValue;
     // the kernel's view of these arguments: see kOutMax
     GemmPanel q = pn;
@@ -700,8 +701,8 @@ hipError_t launch_int8_gemm_maxima(const int8_t *A, const int8_t *B, int64_t Mp,
     q.c_plane = col_max - row_max;
     const GemmMods none{};
     if (pn.rows * pn.cols < (int64_t)256 * 256 * 128)        // as in launch_out
-        return launch<2, 2, 2, 2, 64, 4, kOutMax>(A, B, row_max, 1, Mp, Np, Kp, 0, Kp, q, none, stream);
-    return launch<2, 4, 4, 2, 64, 4, kOutMax>(A, B, row_max, 1, Mp, Np, Kp, 0, Kp, q, none, stream);
+        return launch<2, 2, 2, 2, 64, 4, kOutMax>(A, B, row_max, 1, Mp, Np, Kp, k_begin, k_len, q, none, stream);
+    return launch<2, 4, 4, 2, 64, 4, kOutMax>(A, B, row_max, 1, Mp, Np, Kp, k_begin, k_len, q, none, stream);
 }
 
 hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch, int64_t Mp,

@@ -8,13 +8,9 @@
 #include <cstdint>
 
 #include "oz2_constants.hpp"
+#include "oz2_plan.hpp"           // padding granularity, scratch sizes (host-only header)
 
 namespace oz2 {
-
-// Tile granularity the INT8 GEMM assumes for its padded operands.
-constexpr int64_t kPadMN = 256;   // rows of the A slices, rows of the B^T slices
-constexpr int64_t kPadK = 128;    // contraction length
-constexpr int kBlockK = 64;       // K block of the residue-slice layout [Kp/64][rows][64]
 
 // Per-modulus constants handed to kernels by value (Section 4.1).
 constexpr int kModGroup = 5;             // moduli per pre-reduction group: 256^5 = 2^40 < 2^45
@@ -82,7 +78,6 @@ hipError_t launch_residues(const T *X, int64_t ld, int64_t rows, int64_t len, co
 // place: one shift per column, and residue slices of X transposed, K-blocked:
 // out[s][h / 64][c][h % 64] for c < cols_pad, h < rows_pad (zero beyond cols / rows).
 // scratch: column_scratch_bytes(cols) bytes of device memory, overwritten.
-size_t column_scratch_bytes(int64_t cols);
 template <typename T>
 hipError_t launch_shifts_cols(const T *X, int64_t ld, int64_t rows, int64_t cols,
                               const ShiftArgs &sa, void *scratch, int32_t *t, hipStream_t stream);
@@ -95,8 +90,7 @@ hipError_t launch_residues_cols(const T *X, int64_t ld, int64_t rows, int64_t co
 // sets the time: one launch for the shifts of both factors and one for their residues, with the
 // results of the launchers above.  A is the left factor (m vectors of k elements: its rows when
 // a_k_contiguous, else its columns), B the right one (n vectors); slices as in launch_residues.
-// small_conversion_applies says for which shapes these launchers may be used.
-bool small_conversion_applies(int64_t m, int64_t n, int64_t k);
+// small_conversion_applies (oz2_plan.hpp) says for which shapes these launchers may be used.
 template <typename T>
 hipError_t launch_small_shifts(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
                                bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const ShiftArgs &sa,
@@ -121,22 +115,24 @@ hipError_t launch_small_magnitudes(const T *A, int64_t lda, bool a_k_contiguous,
 
 // Accurate mode (Section 4.2, second half).  All vectors live in `scratch`
 // (accurate_scratch_bytes(m, n) bytes); the 7-bit matrices go to slice 0 of the residue
-// buffers (same K-blocked layout) and Cbar to plane 0 of the product buffer:
+// buffers (same K-blocked layout); Cbar itself is never stored:
 //   launch_accurate_prescale   max|.| per row of A / column of B, mu' = 2^(5-e), nu', and
 //                              Abar = ceil(mu' |A|), Bbar = ceil(|B| nu') as int8; clears the
-//                              maxima of Cbar.  small: with the fused launches for small problems
-//   (the caller then runs launch_int8_gemm_maxima on Cbar = Abar * Bbar)
-//   launch_accurate_finish     t = (5 - e) + floor(P'_accu - 0.51 log2 max), zero vectors -> 0
-size_t accurate_scratch_bytes(int64_t m, int64_t n);
+//                              maxima of Cbar for `ranges` K ranges.  small: with the fused
+//                              launches for small problems
+//   (the caller then runs launch_int8_gemm_maxima on Cbar_r = Abar * Bbar over each K range r)
+//   launch_accurate_finish     t = (5 - e) + floor(P'_accu - 0.51 log2 c), c = the sum over the
+//                              ranges of the maxima of Cbar_r (one range: the maximum of Cbar, the
+//                              paper's formula; more: an upper bound of it); zero vectors -> 0
 template <typename T>
 hipError_t launch_accurate_prescale(const T *A, int64_t lda, bool a_k_contiguous, const T *B,
                                     int64_t ldb, bool b_k_contiguous, int64_t m, int64_t n,
-                                    int64_t k, void *scratch, int8_t *Abar, int8_t *Bbar,
+                                    int64_t k, int ranges, void *scratch, int8_t *Abar, int8_t *Bbar,
                                     int64_t Mp, int64_t Np, int64_t Kp, bool small, hipStream_t stream);
-// Where the maxima of Cbar live in `scratch` (m row maxima, then n column maxima; the caller
+// Where the maxima of Cbar_r live in `scratch` (m row maxima, then n column maxima; the caller
 // fills them with launch_int8_gemm_maxima); _finish turns them into the shifts.
-void accurate_maxima(void *scratch, int64_t m, int64_t n, int **row_max, int **col_max);
-hipError_t launch_accurate_finish(int64_t m, int64_t n, const ShiftArgs &sa, void *scratch,
+void accurate_maxima(void *scratch, int64_t m, int64_t n, int range, int **row_max, int **col_max);
+hipError_t launch_accurate_finish(int64_t m, int64_t n, int ranges, const ShiftArgs &sa, void *scratch,
                                   int32_t *tA, int32_t *tB, hipStream_t stream);
 
 // Row / column kernels in "magnitude" form, used by accurate mode:
@@ -177,14 +173,16 @@ hipError_t launch_int8_gemm(const int8_t *A, const int8_t *B, void *C, int batch
                             bool fold, const ModArgs *ma, hipStream_t stream,
                             const GemmPanel *panel = nullptr);
 
-// Accurate mode (Section 4.2): the contraction of slice 0 of A and B over all of K for one panel
-// (as above), of which only the maxima are kept: row_max[i] = max(row_max[i], max_j c_ij) for
-// the panel's rows i < valid_rows, col_max[j] likewise for its columns j < valid_cols (entries
-// are sums of products of non-negative numbers; Kp <= 2^17).  Both arrays are indexed from the
-// panel's first row / column and are updated with integer atomic maxima.
+// Accurate mode (Section 4.2): the contraction of slice 0 of A and B over the K range
+// [k_begin, k_begin + k_len) (k_len <= 2^17) for one panel (as above), of which only the maxima
+// are kept: row_max[i] = max(row_max[i], max_j c_ij) for the panel's rows i < valid_rows,
+// col_max[j] likewise for its columns j < valid_cols (entries are sums of products of
+// non-negative numbers).  Both arrays are indexed from the panel's first row / column and are
+// updated with integer atomic maxima.
 hipError_t launch_int8_gemm_maxima(const int8_t *A, const int8_t *B, int64_t Mp, int64_t Np, int64_t Kp,
-                                   const GemmPanel &panel, int64_t valid_rows, int64_t valid_cols,
-                                   int *row_max, int *col_max, hipStream_t stream);
+                                   int64_t k_begin, int64_t k_len, const GemmPanel &panel,
+                                   int64_t valid_rows, int64_t valid_cols, int *row_max, int *col_max,
+                                   hipStream_t stream);
 
 // Algorithm 1 lines 7-12 and the alpha/beta update, fused:
 // C[i][j] = alpha * ldexp(C''(i,j), -(tA[i]+tB[j])) + beta * C[i][j]   (OutT = double or float)

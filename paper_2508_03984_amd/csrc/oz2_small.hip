@@ -221,12 +221,6 @@ unsigned residue_blocks(const SmallSide<T> &s) {
 
 }  // namespace
 
-bool small_conversion_applies(int64_t m, int64_t n, int64_t k) {
-    // Both operands within 2 x 2048^2 elements (they and their slices then sit in the caches)
-    // and columns short enough for one workgroup per strip.
-    return k <= 4096 && m <= 8192 && n <= 8192 && (m + n) * k <= (int64_t)2 * 2048 * 2048;
-}
-
 template <typename T>
 hipError_t launch_small_shifts(const T *A, int64_t lda, bool a_k_contiguous, const T *B, int64_t ldb,
                                bool b_k_contiguous, int64_t m, int64_t n, int64_t k, const ShiftArgs &sa,

@@ -91,8 +91,8 @@ def test_accurate_shift_table_matches_the_formula_at_every_threshold(oz, oracle,
     c = K.constants(n)
     assert tab["Paccu"] == c.Paccu
     theta = [int(x) for x in tab["theta"]]
-    assert theta == sorted(theta) and theta[-1] == 2 ** 29 and theta[0] >= 1
-    probes = sorted({1, 2, 2 ** 29} | {v for th in theta for v in (th - 1, th, th + 1) if 1 <= v <= 2 ** 29})
+    assert theta == sorted(theta) and theta[-1] == 2 ** 32 and theta[0] >= 1
+    probes = sorted({1, 2, 2 ** 29, 2 ** 32} | {v for th in theta for v in (th - 1, th, th + 1) if 1 <= v <= 2 ** 32})
     e = np.full(len(probes), 3, np.int32)
     t = oracle.accu_shift_from_max(e, np.array(probes, np.int64), c.Paccu)
     for cm, tv in zip(probes, t):
@@ -138,7 +138,7 @@ def test_general_entry_points_check_their_arguments_without_a_gpu(oz):
     assert op(1, 0, 4, 6, 5, 3, 6, 6) == 1                    # A^T is stored 5 x 4: lda >= 4
     assert op(0, 1, 4, 6, 5, 5, 4, 6) == 1                    # B^T is stored 6 x 5: ldb >= 5
     assert op(1, 1, 0, 6, 5, 1, 5, 6) == 0                    # empty: no-op
-    assert op(1, 1, 4, 6, 2 ** 17 + 1, 4, 2 ** 17 + 1, 6, acc=1) == 2   # accurate mode: k <= 2^17
+    assert op(1, 1, 4, 6, 2 ** 20 + 1, 4, 2 ** 20 + 1, 6, acc=1) == 2   # either mode: k <= 2^20
     # column-major form: A (m x k) needs lda >= m, A^T (k x m) lda >= k, C ldc >= m
     cm = lambda opA, opB, m, n, k, lda, ldb, ldc: lib.oz2_dgemm_colmajor(
         opA, opB, 0, m, n, k, 1.0, one, lda, one, ldb, 0.0, one, ldc, 14, null)
@@ -215,6 +215,12 @@ def test_binding_layout_helpers_on_the_host():
         b.matmul(X, torch.zeros((8, 3)), 14)                  # inner dimensions differ
 
 
+# AddressSanitizer + UBSan for host code built by the host compiler; the runtime is linked
+# statically so that it comes first whatever else the environment loads into the process.
+SANITIZE = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan"]
+SAN_ENV = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:verify_asan_link_order=0")
+
+
 def test_host_constants_code_is_clean_under_sanitizers(tmp_path):
     """The library's only non-trivial host code (the wide-integer arithmetic behind the
     constants and the threshold tables) built with AddressSanitizer and UBSan by the host
@@ -240,11 +246,9 @@ int main() {
 }
 ''')
     exe = tmp_path / "consts_san"
-    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
-                           "-fno-sanitize-recover=all", "-I", src, str(main),
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g"] + SANITIZE + ["-I", src, str(main),
                            os.path.join(src, "oz2_constants.cpp"), "-o", str(exe)])
-    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1", LD_PRELOAD="")
-    out = subprocess.run([str(exe)], env=env, capture_output=True, text=True)
+    out = subprocess.run([str(exe)], env=SAN_ENV, capture_output=True, text=True)
     assert out.returncode == 0, out.stderr[-2000:]
     lines = out.stdout.strip().splitlines()
     assert len(lines) == 2 * 19
@@ -307,3 +311,119 @@ def test_one_round_is_not_enough_at_the_accurate_mode_bound_of_12_moduli():
         for x in _adversarial(p, 52, rng):
             misses += 2 * abs(_one_round(x, p)) > p
     assert misses > 0
+
+
+def test_host_planning_is_clean_under_sanitizers_and_is_what_the_library_runs(oz, tmp_path):
+    """The host logic of a product call that needs no GPU -- argument checks, workspace layout,
+    the panel plan, the rules that pick a form of the call (csrc/oz2_plan.hpp) -- built by the host
+    compiler with AddressSanitizer and UBSan and driven over many shapes and workspace sizes; the
+    plans it prints equal the ones the library returns through the ABI for the same inputs."""
+    import subprocess
+    src = os.path.join(ROOT, "paper_2508_03984_amd", "csrc")
+    main = tmp_path / "plan_main.cpp"
+    main.write_text(r'''
+#include <cstdio>
+#include <cstdlib>
+#include "oz2_plan.hpp"
+using namespace oz2;
+int main(int argc, char **argv) {
+    // 1. argument checks: every combination of a few good and bad values
+    const int64_t sizes[] = {-1, 0, 1, 300, (int64_t)1 << 20, ((int64_t)1 << 20) + 1};
+    const int ops[] = {0, 1, 2}, mods[] = {1, 2, 14, 20, 21};
+    char mem[8];
+    unsigned long long h = 0;
+    for (int64_t m : sizes) for (int64_t n : sizes) for (int64_t k : sizes)
+        for (int oa : ops) for (int ob : ops) for (int N : mods)
+            for (int nulls = 0; nulls < 8; ++nulls) for (int64_t dl : {(int64_t)-1, (int64_t)0}) {
+                Action a;
+                const int64_t lda = (oa == 0 ? k : m) + dl, ldb = (ob == 1 ? k : n) + dl, ldc = n + dl;
+                oz2_status st = check_gemm_args(oa, ob, m, n, k, (nulls & 1) ? nullptr : mem, lda,
+                                                (nulls & 2) ? nullptr : mem, ldb, (nulls & 4) ? nullptr : mem, ldc, N, &a);
+                h = h * 31 + (unsigned)st * 5 + (unsigned)a;
+            }
+    std::printf("checks %llu\n", h);
+    // 2. layouts and panel plans for the shapes and workspace sizes on the command line
+    for (int i = 1; i + 5 <= argc; i += 5) {
+        const int64_t m = atoll(argv[i]), n = atoll(argv[i + 1]), k = atoll(argv[i + 2]);
+        const int N = atoi(argv[i + 3]);
+        const size_t ws = strtoull(argv[i + 4], nullptr, 10);
+        for (int u8 = 0; u8 < 2; ++u8) {
+            const Layout L = make_layout(m, n, k, N, u8 != 0);
+            Panels P{0, 0, 0};
+            const bool ok = ws >= L.off_prod && plan_panels(L, ws - L.off_prod, &P);
+            const Panels Po = ok ? overlap_panels(L, P) : P;
+            std::printf("%lld %lld %lld %d %zu %d : %zu %zu %d %lld %lld %lld | %lld %lld %lld %d %d\n", (long long)m,
+                        (long long)n, (long long)k, N, ws, u8, L.off_prod + L.prod_whole, L.off_prod + L.prod_min, (int)ok,
+                        (long long)P.pr, (long long)P.pc, (long long)P.count, (long long)Po.pr, (long long)Po.pc,
+                        (long long)Po.count, (int)(ok && overlap_applies(L.Kp, Po.count)), (int)small_conversion_applies(m, n, k));
+        }
+    }
+    return 0;
+}
+''')
+    exe = tmp_path / "plan_san"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g"] + SANITIZE + ["-I", src, str(main), "-o", str(exe)])
+    rng = np.random.default_rng(5)
+    cases = []
+    for m, n, k, N in [(700, 1100, 200, 15), (16384, 16384, 16384, 16), (8192, 300, 1000, 20), (256, 40000, 512, 2),
+                       (100000, 5000, 128, 12), (1, 1, 1, 2), (8192, 8192, 65536, 18), (5000, 7000, 2 ** 20, 9)]:
+        need, least = oz.oz2_workspace_bytes(m, n, k, N), oz.oz2_workspace_min_bytes(m, n, k, N)
+        for ws in [0, least - 1, least, need - 1, need, need * 2] + [int(x) for x in rng.integers(least, need + 1, 6)]:
+            cases.append((m, n, k, N, ws))
+    args = [str(v) for c in cases for v in c]
+    out = subprocess.run([str(exe)] + args, env=SAN_ENV, capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr[-3000:]
+    lines = out.stdout.strip().splitlines()
+    assert lines[0].startswith("checks ") and len(lines) == 1 + 2 * len(cases)
+    lib = oz.load()
+    try:
+        for (m, n, k, N, ws), (line_i32, line_u8) in zip(cases, zip(lines[1::2], lines[2::2])):
+            for int32, line in ((True, line_i32), (False, line_u8)):
+                lib.oz2_set_int32_products(int(int32))
+                f = line.split(":")[1].split("|")[0].split()
+                assert int(f[0]) == oz.oz2_workspace_bytes(m, n, k, N) and int(f[1]) == oz.oz2_workspace_min_bytes(m, n, k, N)
+                try:
+                    plan = oz.oz2_plan_panels(m, n, k, N, ws)
+                    assert f[2] == "1" and tuple(int(x) for x in f[3:6]) == plan, (m, n, k, N, ws, int32)
+                except oz.OZ2Error as e:
+                    assert e.status == 3 and f[2] == "0"
+    finally:
+        lib.oz2_set_int32_products(0)
+
+
+def test_header_is_c99_and_a_c_caller_links(oz, tmp_path):
+    """include/oz2.h is a C header: a C99 translation unit that uses every kind of declaration in
+    it compiles without warnings, links against the library and runs (host-side calls only)."""
+    import subprocess
+    main = tmp_path / "caller.c"
+    main.write_text(r'''
+#include <stdio.h>
+#include "oz2.h"
+int main(void) {
+    int64_t pr = 0, pc = 0, cnt = 0;
+    oz2_context *ctx = NULL;
+    oz2_operand *none = NULL;
+    double c3[3];
+    int32_t p[OZ2_MAX_MODULI];
+    if (oz2_create(&ctx) != OZ2_OK) return 1;
+    if (oz2_ctx_set_option(ctx, OZ2_OPT_INT32_PRODUCTS, 1) != OZ2_OK) return 2;
+    if (oz2_ctx_workspace_bytes(ctx, 256, 256, 256, 14) <= oz2_workspace_bytes(256, 256, 256, 14, 1)) return 3;
+    if (oz2_ctx_plan_panels(ctx, 700, 1100, 200, 15, (size_t)1 << 40, &pr, &pc, &cnt) != OZ2_OK || cnt != 1) return 4;
+    if (oz2_ctx_dgemm(ctx, OZ2_OP_N, OZ2_OP_T, 0, 4, 4, 4, 1.0, NULL, 4, NULL, 4, 0.0, NULL, 4, 14, NULL) != OZ2_INVALID_ARG) return 5;
+    if (oz2_dgemm(4, 4, 4, 1.0, NULL, 4, NULL, 4, 0.0, NULL, 4, 99, NULL) != OZ2_UNSUPPORTED) return 6;
+    if (oz2_constants(14, 1, p, NULL, NULL, NULL, c3, NULL) != OZ2_OK || p[0] != 256) return 7;
+    if (oz2_operand_bytes(none) != 0 || oz2_residue_rounds(12, 1) != 2 || oz2_residue_rounds(12, 0) != 1) return 8;
+    if (oz2_ctx_stage_ptr(ctx, OZ2_STAGE_U, NULL, NULL) != OZ2_INVALID_ARG) return 9;
+    if (oz2_destroy(ctx) != OZ2_OK) return 10;
+    printf("%s\n", oz2_status_string(OZ2_WORKSPACE));
+    return 0;
+}
+''')
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(oz.lib_path())
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(main), "-L", libdir, "-l:liboz2.so", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib",
+                           "-Wl,--allow-shlib-undefined", "-o", str(exe)])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, (out.returncode, out.stderr[-2000:])
+    assert "workspace" in out.stdout

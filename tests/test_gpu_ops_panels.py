@@ -24,6 +24,17 @@ def oz():
     oz.oz2_release()
 
 
+@pytest.fixture(autouse=True)
+def overlap_option_for_the_overlapped_tests(request, oz):
+    """The overlapped form is an option (off by default): the tests about it switch it on."""
+    on = "overlapped" in request.node.name
+    if on:
+        oz.oz2_set_overlap(True)
+    yield
+    if on:
+        oz.oz2_set_overlap(False)
+
+
 def stored(X, transposed, ld_extra, dt):
     """X (numpy) on the device as op(stored): stored = X or X^T, rows padded by ld_extra."""
     import torch
@@ -515,7 +526,7 @@ def test_small_conversion_equals_the_general_kernels(oz, m, n, k, N, dtype, opA,
 # ------------------------------------------------------------------ overlapped form
 @pytest.mark.parametrize("opA,opB,accurate", [(0, 0, False), (1, 1, False), (1, 0, True)])
 def test_overlapped_form_equals_the_single_stream_form(oz, oracle, opA, opB, accurate):
-    """k >= 8192 and a padded C of 8448 x 8704 (3 x 3 panels with ragged last ones): the default
+    """k >= 8192 and a padded C of 8448 x 8704 (3 x 3 panels with ragged last ones): the overlapped
     form converts the blocks of A and B on a second stream while the GEMMs of earlier panels
     run; it must equal the single-stream form bit for bit, call after call, and the oracle."""
     import torch

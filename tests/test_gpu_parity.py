@@ -143,11 +143,10 @@ def test_k_beyond_2_pow_17_is_blocked(oz, oracle):
     assert_parity(got, ref, True)
     A32, B32 = A[:, :2 ** 17 + 128].astype(np.float32), B[:2 ** 17 + 128].astype(np.float32)
     assert_parity(gpu_gemm(oz, A32, B32, 8), oracle.gemm(A32, B32, 8, is_double=False), False)
-    import torch
-    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
-    with pytest.raises(oz.OZ2Error) as e:                 # accurate mode: single INT32 Cbar only
-        oz.matmul(dA, dB, 14, accurate=True)
-    assert e.value.status == 2
+    # accurate mode: Cbar in two K ranges, the sums of their maxima in place of the maxima
+    assert_parity(gpu_gemm(oz, A, B, 14, accurate=True), oracle.gemm(A, B, 14, accurate=True), True)
+    assert_parity(gpu_gemm(oz, A32, B32, 8, accurate=True),
+                  oracle.gemm(A32, B32, 8, is_double=False, accurate=True), False)
 
 
 def test_longest_contraction_k_2_pow_20(oz, oracle):
@@ -161,6 +160,8 @@ def test_longest_contraction_k_2_pow_20(oz, oracle):
     assert_parity(gpu_gemm(oz, A, B, 20), oracle.gemm(A, B, 20), True)
     A32, B32 = A.astype(np.float32), B.astype(np.float32)
     assert_parity(gpu_gemm(oz, A32, B32, 9), oracle.gemm(A32, B32, 9, is_double=False), False)
+    # accurate mode over eight K ranges; the row of +-2^17 makes 7-bit magnitudes of 32 throughout
+    assert_parity(gpu_gemm(oz, A, B, 18, accurate=True), oracle.gemm(A, B, 18, accurate=True), True)
     dA = torch.zeros((2, k + 1), dtype=torch.float64, device="cuda")
     dB = torch.zeros((k + 1, 2), dtype=torch.float64, device="cuda")
     with pytest.raises(oz.OZ2Error) as e:
@@ -410,19 +411,22 @@ def sampled_parity(oz, oracle, m, n, k, N, phi, dtype, seed, n_rows=6, n_entries
         dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     else:
         A, B, dA, dB = inputs
-    # the default (overlapped above 4096 x 4096) form first, then everything on one stream, which
-    # keeps the products of all of C for the checks below; the two must agree bit for bit
-    dC_default = oz.matmul(dA, dB, N, accurate=accurate)
+    # the overlapped form (an option; it applies above 4096 x 4096 with a long k) first, then the
+    # default form, everything on one stream, which keeps the products of all of C for the checks
+    # below; the two must agree bit for bit
+    oz.oz2_set_overlap(True)
+    try:
+        dC_overlapped = oz.matmul(dA, dB, N, accurate=accurate)
+    finally:
+        oz.oz2_set_overlap(False)
     oz.oz2_set_int32_products(int32_products)
-    oz.oz2_set_overlap(False)
     try:
         dC = oz.matmul(dA, dB, N, accurate=accurate)
     finally:
         oz.oz2_set_int32_products(False)
-        oz.oz2_set_overlap(True)
     torch.cuda.synchronize()
-    assert torch.equal(dC_default, dC), "overlapped and single-stream results differ"
-    del dC_default
+    assert torch.equal(dC_overlapped, dC), "overlapped and single-stream results differ"
+    del dC_overlapped
     prep = oracle.prepare(A, B, N, is_double, accurate)
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_A).cpu().numpy(), prep["tA"])
     assert np.array_equal(oz.stage_tensor(b.OZ2_STAGE_SHIFT_B).cpu().numpy(), prep["tB"])
