@@ -91,6 +91,25 @@ oz2_status oz2_sgemm(int64_t m, int64_t n, int64_t k, float alpha,
                      hipStream_t stream);
 
 /*
+ * oz2_dgemm for callers that cannot allocate device memory at the time of the call: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * result (bit for bit) and errors as oz2_dgemm, but the workspace is a fixed array of
+ * OZ2_NOALLOC_WORKSPACE_BYTES in the library's device image (each GPU the library runs on holds
+ * its copy until the process ends; the first call on a GPU looks its address up there), so the
+ * call neither allocates nor frees anything, on the device or through any library.  A product whose workspace (oz2_workspace_bytes) exceeds that
+ * size returns OZ2_WORKSPACE and does nothing: with 16 moduli the limit is reached at about
+ * m = n = k = 1100.  All calls on one GPU share that GPU's array: the caller orders them (one
+ * stream, or events); calls that overlap on one GPU race.  Nothing is assumed about what an
+ * earlier call left in the array.  Contexts, options and the diagnostics (oz2_stage_ptr, stage
+ * times) do not apply to this entry point.
+ */
+#define OZ2_NOALLOC_WORKSPACE_BYTES (64 * 1024 * 1024)
+oz2_status oz2_dgemm_noalloc(int64_t m, int64_t n, int64_t k, double alpha,
+                             const double *A, int64_t lda, const double *B, int64_t ldb,
+                             double beta, double *C, int64_t ldc, int num_moduli,
+                             hipStream_t stream);
+
+/*
  * The same product with the scale vectors of ACCURATE mode (Section 4.2, second half):
  * A and B are first reduced to 7-bit matrices Abar = ceil(mu' |A|), Bbar = ceil(|B| nu')
  * (mu', nu' powers of two that bring each row / column maximum into [32, 64)), their

@@ -28,7 +28,7 @@ EXPORTS = [
     "oz2_ctx_dgemm_prepared", "oz2_ctx_sgemm_prepared", "oz2_ctx_workspace_bytes",
     "oz2_ctx_workspace_min_bytes", "oz2_ctx_set_workspace", "oz2_ctx_set_workspace_limit",
     "oz2_ctx_plan_panels", "oz2_ctx_last_panels", "oz2_ctx_release", "oz2_ctx_stage_ptr",
-    "oz2_ctx_last_stage_times_ms",
+    "oz2_ctx_last_stage_times_ms", "oz2_dgemm_noalloc",
 ]
 
 OZ2_OPT_INT32_PRODUCTS, OZ2_OPT_OVERLAP, OZ2_OPT_SMALL_CONVERSION, OZ2_OPT_PROFILING = range(4)
@@ -66,6 +66,8 @@ def load():
     lib.oz2_dgemm.argtypes = [i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, ci, vp]
     lib.oz2_sgemm.argtypes = [i64, i64, i64, flt, vp, i64, vp, i64, flt, vp, i64, ci, vp]
     lib.oz2_dgemm_accurate.argtypes = lib.oz2_dgemm.argtypes
+    lib.oz2_dgemm_noalloc.argtypes = lib.oz2_dgemm.argtypes
+    lib.oz2_dgemm_noalloc.restype = ci
     lib.oz2_sgemm_accurate.argtypes = lib.oz2_sgemm.argtypes
     lib.oz2_shift_table_accurate.argtypes = [ci, vp, vp, vp, vp]
     lib.oz2_dgemm_op.argtypes = [ci, ci, ci] + lib.oz2_dgemm.argtypes
@@ -176,6 +178,16 @@ def oz2_dgemm(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=
     _check(load().oz2_dgemm(m, n, k, float(alpha), _dev(A, torch.float64), lda,
                             _dev(B, torch.float64), ldb, float(beta), _dev(C_, torch.float64), ldc,
                             int(num_moduli), _stream(stream)), "oz2_dgemm")
+
+
+OZ2_NOALLOC_WORKSPACE_BYTES = 64 * 1024 * 1024
+
+
+def oz2_dgemm_noalloc(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=None) -> None:
+    import torch
+    _check(load().oz2_dgemm_noalloc(m, n, k, float(alpha), _dev(A, torch.float64), lda,
+                                    _dev(B, torch.float64), ldb, float(beta), _dev(C_, torch.float64), ldc,
+                                    int(num_moduli), _stream(stream)), "oz2_dgemm_noalloc")
 
 
 def oz2_sgemm(m, n, k, alpha, A, lda, B, ldb, beta, C_, ldc, num_moduli, stream=None) -> None:

@@ -728,6 +728,63 @@ void oz2_set_profiling(int on) { (void)oz2_ctx_set_option(nullptr, OZ2_OPT_PROFI
 
 oz2_status oz2_last_stage_times_ms(float *out4) { return oz2_ctx_last_stage_times_ms(nullptr, out4); }
 
+// ------------------------------------------------------------------ allocation-free entry point
+}  // extern "C"
+
+namespace {
+
+// The workspace of oz2_dgemm_noalloc: a fixed array in the library's device image, one copy per
+// GPU, held from the moment the image is loaded on that GPU until the process ends.
+static __device__ __align__(256) unsigned char scratch[OZ2_NOALLOC_WORKSPACE_BYTES];
+
+constexpr int kMaxNoallocDevices = 64;
+struct NoallocSlot {
+    void *ptr = nullptr;                   // device address of `scratch` on this GPU (hipGetSymbolAddress)
+    Ctx ctx;                               // a context whose workspace is that array, for good
+};
+NoallocSlot noalloc_slots[kMaxNoallocDevices];
+std::mutex noalloc_mu;                     // guards the set-up of the slots
+
+}  // namespace
+
+extern "C" {
+
+oz2_status oz2_dgemm_noalloc(int64_t m, int64_t n, int64_t k, double alpha, const double *A, int64_t lda,
+                             const double *B, int64_t ldb, double beta, double *C, int64_t ldc,
+                             int num_moduli, hipStream_t stream) {
+    Action action;
+    if (oz2_status st = check_gemm_args(OZ2_OP_N, OZ2_OP_N, m, n, k, A, lda, B, ldb, C, ldc, num_moduli, &action))
+        return st;
+    if (action == Action::kProduct) {                      // sizes beyond the fixed array are refused
+        const Layout L = make_layout(m, n, k, num_moduli, true);
+        if (L.off_prod + L.prod_whole > (size_t)OZ2_NOALLOC_WORKSPACE_BYTES) return OZ2_WORKSPACE;
+    }
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return OZ2_HIP_ERROR;
+    if (dev < 0 || dev >= kMaxNoallocDevices) return OZ2_UNSUPPORTED;
+    NoallocSlot &slot = noalloc_slots[dev];
+    {
+        std::lock_guard<std::mutex> lock(noalloc_mu);
+        if (!slot.ptr) {
+            // Once per device, with that device current: each GPU holds its own copy of the array
+            // at its own address.  In host code the array's name is not that address.
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                return OZ2_HIP_ERROR;
+            }
+            slot.ptr = p;
+            slot.ctx.ws = static_cast<char *>(p);          // a caller-owned workspace in the context's terms:
+            slot.ctx.ws_bytes = OZ2_NOALLOC_WORKSPACE_BYTES;   // never grown, never freed
+            slot.ctx.ws_owned = false;
+        }
+    }
+    // Profiling and the overlapped form stay off in this context (they would create events and a
+    // stream); what is left of the call path only launches kernels on `stream`.
+    return gemm_impl<double>(slot.ctx, OZ2_OP_N, OZ2_OP_N, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, num_moduli,
+                             stream, false);
+}
+
 // ------------------------------------------------------------------ stateless entry points
 oz2_status oz2_constants(int num_moduli, int is_double, int32_t *p, uint32_t *pinv_prime,
                          double *s1, double *s2, double *P1P2Pinv, float *Pfast) {
