@@ -25,6 +25,7 @@
 // flight, then one s_barrier.  The compiler does not track LDS writes made by
 // global_load_lds, so these two are what orders them against the ds_reads.
 #include <algorithm>
+#include <type_traits>
 
 #include "oz2_kernels.hpp"
 
@@ -98,22 +99,25 @@ struct GemmMods {                       // moduli of the slices and their mulhi 
     int32_t pinv_prime[kMaxModuli];
 };
 
-template <int WM, int WN, int TM, int TN, int BK, int STAGES, int OUT>
-__global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__restrict__ A,
-                                                   const int8_t *__restrict__ B,
-                                                   void *__restrict__ C, int64_t Mp,
-                                                   int64_t Np, int64_t KB, int kb0, int KT,
-                                                   int64_t c_ld, int64_t c_plane,
-                                                   TileMap tmap, GemmMods mods) {
-    constexpr int THREADS = 64 * WM * WN;              // WM x WN wavefronts
-    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
-    constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
-    constexpr int ROWS = BM + BN;                      // A rows then B rows in one LDS stage
-    constexpr int CHUNKS = ROWS * CPR;
-    constexpr int LPT = CHUNKS / THREADS;              // LDS-direct loads per lane and tile
-    constexpr int KK = BK / 32;                        // MFMA K steps per tile
-    constexpr int STAGE_BYTES = CHUNKS * 16;
-    constexpr int ROWS_PER_LOAD = 64 / CPR;            // rows one wavefront-wide load covers
+// The LDS of a workgroup: STAGES stages of (A rows | B rows) x 64 bytes.  Declared here, not
+// passed around, so that every access is an offset from a base the compiler knows.
+extern __shared__ v4i lds[];                              // [STAGES][ROWS][CPR]
+
+// Everything one workgroup does for one output tile, shared by the two kernels below: where its
+// lanes fetch from, the K loop, and the store phase.  A tile is identified by the global address
+// its loads start at (tile_source) and by (slice, first row, first column) for the store.
+template <int WM, int WN, int TM, int TN, int BK, int STAGES>
+struct GemmCore {
+    static constexpr int THREADS = 64 * WM * WN;              // WM x WN wavefronts
+    static constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    static constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
+    static constexpr int ROWS = BM + BN;                      // A rows then B rows in one LDS stage
+    static constexpr int CHUNKS = ROWS * CPR;
+    static constexpr int LPT = CHUNKS / THREADS;              // LDS-direct loads per lane and tile
+    static constexpr int KK = BK / 32;                        // MFMA K steps per tile
+    static constexpr int STAGE_BYTES = CHUNKS * 16;
+    static constexpr int ROWS_PER_LOAD = 64 / CPR;            // rows one wavefront-wide load covers
+    static constexpr int SRC_STEP = ROWS_PER_LOAD * BK;
     static_assert(CHUNKS % THREADS == 0 && (BM * CPR) % (64 * LPT) == 0,
                   "each wavefront must load from one operand only");
     static_assert(BK == kBlockK, "the K tile is the K block of the operand layout");
@@ -121,134 +125,154 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
     static_assert(STAGES >= 3 && (STAGES - 3) * LPT < 64, "vmcnt is a 6-bit counter");
     static_assert(KK >= 2, "operand double-buffering assumes an even number of K steps");
 
-    extern __shared__ v4i lds[];                       // [STAGES][ROWS][CPR]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    int s, tile_r, tile_c;
-    map_tile(tmap, (int)blockIdx.x, s, tile_r, tile_c);
-    const int64_t bm = (int64_t)tile_r * BM, bn = (int64_t)tile_c * BN;
-    // KB = K blocks per slice; this launch contracts over blocks [kb0, kb0 + KT).
-    const int8_t *Ab = A + (((int64_t)s * KB + kb0) * Mp + bm) * BK;
-    const int8_t *Bb = B + (((int64_t)s * KB + kb0) * Np + bn) * BK;
-
+    int wm, wn, lrow, lhalf;
     // Load i of this wavefront fills LDS chunks [64 q, 64 q + 64) of a stage, q = wave*LPT + i,
     // i.e. rows q*ROWS_PER_LOAD ...; lane -> (row, physical chunk) -> logical chunk to fetch.
-    // In the blocked layout those 64 chunks are 1 KiB of contiguous memory.
-    const int row0 = wave * LPT * ROWS_PER_LOAD + lane / CPR;
-    const int ch = (lane % CPR) ^ swizzle_mask<CPR>(row0);
-    const bool from_a = row0 < BM;
-    const int8_t *src0 = (from_a ? Ab + (int64_t)row0 * BK : Bb + (int64_t)(row0 - BM) * BK) + ch * 16;
-    const int64_t tile_step = (from_a ? Mp : Np) * BK;  // next K block of the same rows
-    constexpr int src_step = ROWS_PER_LOAD * BK;
-    char *const lds_bytes = reinterpret_cast<char *>(lds);
-    char *const my_dst = lds_bytes + wave * LPT * 1024;
-
-    // Loads [i0, i1) of tile t for this wavefront.
-    auto issue_loads = [&](int t, int i0, int i1) {
-        const int8_t *src = src0 + (int64_t)t * tile_step;
-        char *dst = my_dst + (t % STAGES) * STAGE_BYTES;
-#pragma unroll
-        for (int i = i0; i < i1; ++i)
-            __builtin_amdgcn_global_load_lds((global_ptr_t)(src + i * src_step),
-                                             (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
-    };
-    auto issue_tile = [&](int t) { issue_loads(t, 0, LPT); };
-
-    // KT >= 2: every K range is a multiple of 128.
-#pragma unroll
-    for (int t = 0; t < STAGES - 1; ++t)
-        if (t < KT) issue_tile(t);
-
-    v16i acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-
+    // In the blocked layout those 64 chunks are 1 KiB of contiguous memory, so the LPT loads of a
+    // wavefront and tile differ by i KiB in the global AND in the LDS address: one address and
+    // one LDS base (M0) per tile, the rest is the instruction's immediate offset, which the
+    // hardware applies to both.
+    static_assert(ROWS_PER_LOAD * BK == 1024 && (LPT - 1) * 1024 < 4096, "immediate offset of the loads");
+    int row0, ch;
+    bool from_a;                                              // uniform over the wavefront
+    int64_t tile_step;                                        // next K block of the same rows
+    int my_dst;                                               // uniform: byte offset within a stage
     // Fragment addressing: lane l reads row (l % 32) of a 32-row fragment, 16-byte chunk
     // 2*kk + l/32 of the K tile.  The swizzle mask depends on l % 32 only.
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int mask = swizzle_mask<CPR>(lrow);
-    const int a_off = (wm * 32 * TM + lrow) * CPR;             // in chunks
-    const int b_off = (BM + wn * 32 * TN + lrow) * CPR;
+    int a_addr[KK], b_addr[KK];                               // byte offsets within a stage, per K step
 
-    v4i fa[2][TM], fb[2][TN];
-    auto load_frags = [&](int buf, int t, int kk) {
-        const v4i *st = lds + (t % STAGES) * CHUNKS;
-        const int c = (kk * 2 + lhalf) ^ mask;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[buf][i] = st[a_off + i * 32 * CPR + c];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[buf][j] = st[b_off + j * 32 * CPR + c];
-    };
-
-    // Tiles 0 and 1 must have landed before the first fragment reads.
-    if (KT >= STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, 0);
-
-    // The LPT loads of a tile are spread over the MFMA rows of a K tile (after every row
-    // but the first of each K step), so that a load that has to wait for room in the memory
-    // pipeline holds up one MFMA row, not the whole tile.
-    constexpr int SLOTS = KK * (TM - 1);
-    constexpr int PER_SLOT = (LPT + SLOTS - 1) / SLOTS;
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool issued = kt + STAGES - 1 < KT;      // loads go into the stage read during kt - 1
+    __device__ __forceinline__ GemmCore(int64_t Mp, int64_t Np) {
+        const int tid = threadIdx.x, lane = tid & 63;
+        // the wavefront index as a scalar: everything derived from it stays in scalar registers
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        wm = wave / WN; wn = wave % WN;
+        const int row0u = wave * LPT * ROWS_PER_LOAD;
+        row0 = row0u + lane / CPR;
+        ch = (lane % CPR) ^ swizzle_mask<CPR>(row0);
+        from_a = row0u < BM;
+        tile_step = (from_a ? Mp : Np) * BK;
+        my_dst = wave * LPT * 1024;
+        lrow = lane & 31; lhalf = lane >> 5;
+        const int mask = swizzle_mask<CPR>(lrow);
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            const int cur = kk & 1, nxt = cur ^ 1;
-            // The first MFMA row runs before the next operands are requested: its operands
-            // were requested a whole K step ago, so waiting for them (the LDS counter is
-            // waited down to zero at that point) does not wait for the new requests.
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][0],
-                                                                  acc[0][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (kk + 1 < KK) load_frags(nxt, kt, kk + 1);
-            else if (kt + 1 < KT) load_frags(nxt, kt + 1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 1; i < TM; ++i) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][i],
-                                                                      acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                const int slot = kk * (TM - 1) + (i - 1);
-                const int i0 = slot * PER_SLOT, i1 = (i0 + PER_SLOT < LPT) ? i0 + PER_SLOT : LPT;
-                if (issued && i0 < LPT) issue_loads(kt + STAGES - 1, i0, i1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            const int c = (kk * 2 + lhalf) ^ mask;
+            a_addr[kk] = ((wm * 32 * TM + lrow) * CPR + c) * 16;
+            b_addr[kk] = ((BM + wn * 32 * TN + lrow) * CPR + c) * 16;
         }
-        // Tile kt + 2 must be complete (and visible to every wavefront) before iteration
-        // kt + 1 prefetches fragments from it; the barrier also frees stage kt % STAGES.
-        if (issued) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __builtin_amdgcn_s_barrier();
     }
 
-    // The B fragment is the MFMA's first operand, so the 32x32 accumulator is the transposed
-    // tile: lane l holds row (l % 32) of the C tile and, in registers 4g .. 4g+3, the four
-    // consecutive columns 8g + 4*(l / 32) + {0,1,2,3}.  One 16-byte (int32) or 4-byte (uint8)
-    // store per g.  (Staging the uint8 tile through LDS to store whole 64-byte row segments
-    // was measured 3.5 ms slower per launch at 16 x 16384^3, although the 4-byte stores make
-    // the L2 fetch the lines it merges them into.)
-    // (the mulhi form: an FP64 floor/fma version of this reduction measured 1.1 ms slower
-    // per launch at 16 x 16384^3)
-    if (OUT == kOutMax) {
-        // Entries are sums of products of non-negative 7-bit numbers (k <= 2^17: below 2^29), the
-        // maxima start at 0 and zero entries (all the padding) are skipped, so integer atomic
-        // maxima give the exact result whatever the order.  A lane holds, per 32 x 32 tile, 16
-        // columns of one row: the row maximum is completed by the lane 32 further on, a column
-        // maximum by the 32 lanes of the same half-wavefront.
-        int *rmax = static_cast<int *>(C);
-        int *cmax = rmax + c_plane;
-        const int valid_rows = (int)(c_ld & 0xffffffff), valid_cols = (int)(c_ld >> 32);
+    // Where this lane's loads of tile (s, tr, tc) start.  KB = K blocks per slice; the launch
+    // contracts over blocks [kb0, kb0 + KT).
+    __device__ __forceinline__ const int8_t *tile_source(const int8_t *A, const int8_t *B, int s, int tr, int tc,
+                                                         int64_t Mp, int64_t Np, int64_t KB, int kb0) const {
+        const int8_t *Ab = A + (((int64_t)s * KB + kb0) * Mp + (int64_t)tr * BM) * BK;
+        const int8_t *Bb = B + (((int64_t)s * KB + kb0) * Np + (int64_t)tc * BN) * BK;
+        return (from_a ? Ab + (int64_t)row0 * BK : Bb + (int64_t)(row0 - BM) * BK) + ch * 16;
+    }
+
+    // Loads [I0, I1) of the K tile whose loads start at src_t, into the stage at byte offset
+    // stage_off (uniform).
+    template <int I0, int I1>
+    __device__ __forceinline__ void issue_loads(const int8_t *src_t, int stage_off) const {
+        if constexpr (I0 < I1) {
+            __builtin_amdgcn_global_load_lds((global_ptr_t)src_t,
+                                             (lds_ptr_t)(reinterpret_cast<char *>(lds) + stage_off + my_dst), 16,
+                                             I0 * 1024, 0);
+            issue_loads<I0 + 1, I1>(src_t, stage_off);
+        }
+    }
+
+    // The first STAGES - 1 K tiles of a tile.  KT >= 2: every K range is a multiple of 128.
+    __device__ __forceinline__ void issue_head(const int8_t *src_tile, int KT) const {
+#pragma unroll
+        for (int t = 0; t < STAGES - 1; ++t)
+            if (t < KT) issue_loads<0, LPT>(src_tile + (int64_t)t * tile_step, t * STAGE_BYTES);
+    }
+
+    // The K loop over a tile whose head has been requested: acc += A tile * B tile^T.
+    // It is written so that the instruction stream between the MFMAs stays as short as it can be:
+    // the loop is split into iterations that prefetch (all but the last STAGES - 1) and ones that
+    // do not, so there is no branch per load; the LDS stage offsets are carried along, not
+    // recomputed (measured against the same pipeline with a branch and a readfirstlane per load:
+    // 3.5 % faster at 16 x 4096 x 4096 x 16384).
+    __device__ __forceinline__ void contract(const int8_t *src_tile, int KT, v16i (&acc)[TM][TN]) const {
+        v4i fa[2][TM], fb[2][TN];
+        const char *const lds_bytes = reinterpret_cast<const char *>(lds);
+        auto load_frags = [&](int buf, int stage_off, int kk) {
+            const char *st = lds_bytes + stage_off;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[buf][i] = *reinterpret_cast<const v4i *>(st + a_addr[kk] + i * 32 * CPR * 16);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[buf][j] = *reinterpret_cast<const v4i *>(st + b_addr[kk] + j * 32 * CPR * 16);
+        };
+
+        // K tiles 0 and 1 must have landed before the first fragment reads.  (In the persistent
+        // kernel the stores of this workgroup's previous tile are outstanding as well; they were
+        // issued after these loads, and loads complete in order, so "at most the youngest K tile
+        // outstanding" still implies that K tiles 0 and 1 are complete.)
+        if (KT >= STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __builtin_amdgcn_s_barrier();
+        load_frags(0, 0, 0);
+
+        // One K tile: it is read from the stage at cur_off, the K tile STAGES - 1 ahead is
+        // requested into the stage read during the previous iteration.  Its LPT loads go out in
+        // two halves, each behind the second MFMA row of a K step.
+        int cur_off = 0;
+        const int8_t *src_ld = src_tile + (int64_t)(STAGES - 1) * tile_step;
+        auto iteration = [&](auto issued_c, bool last) {
+            constexpr bool issued = decltype(issued_c)::value;
+            const int nxt_off = cur_off + STAGE_BYTES == STAGES * STAGE_BYTES ? 0 : cur_off + STAGE_BYTES;
+            const int ld_off = cur_off == 0 ? (STAGES - 1) * STAGE_BYTES : cur_off - STAGE_BYTES;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const int cur = kk & 1, nxt = cur ^ 1;
+                // The first MFMA row runs before the next operands are requested: its operands
+                // were requested a whole K step ago, so waiting for them (the LDS counter is
+                // waited down to zero at that point) does not wait for the new requests.
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][0], acc[0][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (kk + 1 < KK) load_frags(nxt, cur_off, kk + 1);
+                else if (!last) load_frags(nxt, nxt_off, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 1; i < TM; ++i) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (issued && i == 1) {
+                        if (kk == 0) issue_loads<0, LPT / 2>(src_ld, ld_off);
+                        if (kk == KK - 1) issue_loads<LPT / 2, LPT>(src_ld, ld_off);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // Tile kt + 2 must be complete (and visible to every wavefront) before iteration
+            // kt + 1 prefetches fragments from it; the barrier also frees the stage just read.
+            if (issued) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_s_barrier();
+            cur_off = nxt_off;
+            src_ld += tile_step;
+        };
+        int kt = 0;
+        for (; kt + STAGES - 1 < KT; ++kt) iteration(std::true_type{}, false);
+        for (; kt < KT; ++kt) iteration(std::false_type{}, kt + 1 == KT);
+    }
+
+    // Row and column maxima of the tile (kOutMax).  Entries are sums of products of non-negative
+    // 7-bit numbers (k <= 2^17: below 2^29), the maxima start at 0 and zero entries (all the
+    // padding) are skipped, so integer atomic maxima give the exact result whatever the order.  A
+    // lane holds, per 32 x 32 block, 16 columns of one row: the row maximum is completed by the
+    // lane 32 further on, a column maximum by the 32 lanes of the same half-wavefront.
+    __device__ __forceinline__ void store_maxima(const v16i (&acc)[TM][TN], int *rmax, int *cmax, int64_t bm,
+                                                 int64_t bn, int valid_rows, int valid_cols) const {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             int v = 0;
@@ -276,86 +300,130 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
                 const int col = (int)bn + wn * 32 * TN + j * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
                 if (lrow == 0 && v > 0 && col < valid_cols) atomicMax(&cmax[col], v);
             }
-        return;
     }
-    const int p = mods.p[s], pv = mods.pinv_prime[s];
-    const int64_t c_off = (int64_t)s * c_plane + bm * c_ld + bn;   // C: [slice][row][column]
-    if (OUT == kOutU8) {
-        // Four residues per register quad pack into one dword; the two half-wavefronts hold
-        // alternating dwords of a row (columns 8g + 4*(l/32) ...), so they swap two dwords
-        // each and every lane stores 16 contiguous bytes: a lane pair completes a 32-byte
-        // sector of the row, and the L2 no longer has to fetch lines to merge 4-byte stores.
+
+    // The store phase (Algorithm 1 lines 6-7 in the forms listed at kOut...).  The B fragment is
+    // the MFMA's first operand, so the 32x32 accumulator is the transposed block: lane l holds
+    // row (l % 32) of the C block and, in registers 4g .. 4g+3, the four consecutive columns
+    // 8g + 4*(l / 32) + {0,1,2,3}.  The reduction is the mulhi form of Section 4.3 (an FP64
+    // floor/fma version measured 1.1 ms slower per launch at 16 x 16384^3).
+    template <int OUT>
+    __device__ __forceinline__ void store(const v16i (&acc)[TM][TN], void *C, int s, int64_t bm, int64_t bn,
+                                          int64_t c_ld, int64_t c_plane, const GemmMods &mods) const {
+        const int p = mods.p[s], pv = mods.pinv_prime[s];
+        const int64_t c_off = (int64_t)s * c_plane + bm * c_ld + bn;   // C: [slice][row][column]
+        if (OUT == kOutU8) {
+            // Four residues per register quad pack into one dword; the two half-wavefronts hold
+            // alternating dwords of a row (columns 8g + 4*(l/32) ...), so they swap two dwords
+            // each and every lane stores 16 contiguous bytes: a lane pair completes a 32-byte
+            // sector of the row, and the L2 does not have to fetch lines to merge 4-byte stores.
+            // (Staging the whole uint8 tile through LDS to store 64-byte row segments was measured
+            // 3.5 ms slower per launch at 16 x 16384^3.)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    uint32_t d[4];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        d[g] = 0;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            d[g] |= (uint32_t)mod_small(acc[i][j][4 * g + c], p, pv) << (8 * c);
+                    }
+                    const uint32_t r0 = __shfl_xor(lhalf ? d[0] : d[2], 32, 64);
+                    const uint32_t r1 = __shfl_xor(lhalf ? d[1] : d[3], 32, 64);
+                    const v4i q = lhalf ? v4i{(int)r0, (int)d[2], (int)r1, (int)d[3]}
+                                        : v4i{(int)d[0], (int)r0, (int)d[1], (int)r1};
+                    const int row = wm * 32 * TM + i * 32 + lrow;
+                    const int col = wn * 32 * TN + j * 32 + 16 * lhalf;
+                    *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * c_ld + col) = q;
+                }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                uint32_t d[4];
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    d[g] = 0;
+                    const int row = wm * 32 * TM + i * 32 + lrow;
+                    const int col = wn * 32 * TN + j * 32 + 8 * g + 4 * lhalf;
+                    const int64_t at = c_off + (int64_t)row * c_ld + col;
+                    int v[4];
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        d[g] |= (uint32_t)mod_small(acc[i][j][4 * g + c], p, pv) << (8 * c);
+                    for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
+                    if (OUT == kOutI32 || OUT == kOutI32Fold) {
+                        v4i *dst = reinterpret_cast<v4i *>(static_cast<int32_t *>(C) + at);
+                        if (OUT == kOutI32Fold) {
+                            const v4i old = *dst;
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) v[c] = mod_small(old[c], p, pv) + mod_small(v[c], p, pv);
+                        }
+                        *dst = v4i{v[0], v[1], v[2], v[3]};
+                    } else {                                   // kOutU8Fold
+                        uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(C) + at);
+                        uint32_t packed = 0;
+                        const uint32_t old = *dst;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            int u = mod_small(v[c], p, pv) + (int)((old >> (8 * c)) & 0xffu);
+                            u -= (u >= p) ? p : 0;
+                            packed |= (uint32_t)u << (8 * c);
+                        }
+                        *dst = packed;
+                    }
                 }
-                const uint32_t r0 = __shfl_xor(lhalf ? d[0] : d[2], 32, 64);
-                const uint32_t r1 = __shfl_xor(lhalf ? d[1] : d[3], 32, 64);
-                const v4i q = lhalf ? v4i{(int)r0, (int)d[2], (int)r1, (int)d[3]}
-                                    : v4i{(int)d[0], (int)r0, (int)d[1], (int)r1};
-                const int row = wm * 32 * TM + i * 32 + lrow;
-                const int col = wn * 32 * TN + j * 32 + 16 * lhalf;
-                *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * c_ld + col) = q;
-            }
-        return;
     }
 
+    static __device__ __forceinline__ void clear(v16i (&acc)[TM][TN]) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int row = wm * 32 * TM + i * 32 + lrow;
-                const int col = wn * 32 * TN + j * 32 + 8 * g + 4 * lhalf;
-                const int64_t at = c_off + (int64_t)row * c_ld + col;
-                int v[4];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
-                if (OUT == kOutI32 || OUT == kOutI32Fold) {
-                    v4i *dst = reinterpret_cast<v4i *>(static_cast<int32_t *>(C) + at);
-                    if (OUT == kOutI32Fold) {
-                        const v4i old = *dst;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) v[c] = mod_small(old[c], p, pv) + mod_small(v[c], p, pv);
-                    }
-                    *dst = v4i{v[0], v[1], v[2], v[3]};
-                } else {
-                    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(C) + at);
-                    uint32_t packed = 0;
-                    const uint32_t old = OUT == kOutU8Fold ? *dst : 0u;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        int u = mod_small(v[c], p, pv);
-                        if (OUT == kOutU8Fold) {
-                            u += (int)((old >> (8 * c)) & 0xffu);
-                            u -= (u >= p) ? p : 0;
-                        }
-                        packed |= (uint32_t)u << (8 * c);
-                    }
-                    *dst = packed;
-                }
-            }
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    }
+};
+
+// One workgroup per output tile.  For kOutMax the arguments mean: C = the row maxima of the
+// panel's rows, C + c_plane (in ints) = the column maxima of its columns, c_ld = the number of
+// valid rows of the panel in its low and of valid columns in its high 32 bits.
+template <int WM, int WN, int TM, int TN, int BK, int STAGES, int OUT>
+__global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__restrict__ A,
+                                                   const int8_t *__restrict__ B,
+                                                   void *__restrict__ C, int64_t Mp,
+                                                   int64_t Np, int64_t KB, int kb0, int KT,
+                                                   int64_t c_ld, int64_t c_plane,
+                                                   TileMap tmap, GemmMods mods) {
+    typedef GemmCore<WM, WN, TM, TN, BK, STAGES> Core;
+    const Core core(Mp, Np);
+    int s, tile_r, tile_c;
+    map_tile(tmap, (int)blockIdx.x, s, tile_r, tile_c);
+    const int8_t *src = core.tile_source(A, B, s, tile_r, tile_c, Mp, Np, KB, kb0);
+    core.issue_head(src, KT);
+    v16i acc[TM][TN];
+    Core::clear(acc);
+    core.contract(src, KT, acc);
+    const int64_t bm = (int64_t)tile_r * Core::BM, bn = (int64_t)tile_c * Core::BN;
+    if (OUT == kOutMax) {
+        int *rmax = static_cast<int *>(C);
+        core.store_maxima(acc, rmax, rmax + c_plane, bm, bn, (int)(c_ld & 0xffffffff), (int)(c_ld >> 32));
+    } else {
+        core.template store<OUT>(acc, C, s, bm, bn, c_ld, c_plane, mods);
+    }
 }
 
-// The same kernel as a persistent grid, for short contractions: as many workgroups as compute
-// units, each walking over the tiles id = blockIdx.x, blockIdx.x + gridDim.x, ...  The head of
-// the next tile (its first STAGES - 1 K tiles) is requested before the results of the last one
-// are reduced and stored, and no workgroup is dispatched per tile.  With k <= 1024 a tile is a
-// few microseconds of matrix-core work, so that the store phase and the dispatch between tiles
-// weigh as much as the contraction (16384 x 16384 x 512, N = 15: 3.84 -> 3.09 ms).  For long
+// The same as a persistent grid, for short contractions: as many workgroups as compute units,
+// each walking over the tiles id = blockIdx.x, blockIdx.x + gridDim.x, ...  The head of the next
+// tile (its first STAGES - 1 K tiles) is requested before the results of the last one are
+// reduced and stored, and no workgroup is dispatched per tile.  With k <= 1024 a tile is a few
+// microseconds of matrix-core work, so that the store phase and the dispatch between tiles weigh
+// as much as the contraction (16384 x 16384 x 512, N = 15: 3.84 -> 3.09 ms).  For long
 // contractions the one-workgroup-per-tile kernel above is faster: a workgroup that ends does not
 // wait for its stores, a persistent one does at its next wait for loads (loads and stores share
 // one counter on this chip), which costs more than the dispatch it saves (16 x 16384^3 on one
-// device: 62.0 against 60.8 ms); the body of the kernel above is left as it is for that reason.
+// device: 62.0 against 60.8 ms).
 template <int WM, int WN, int TM, int TN, int BK, int STAGES, int OUT>
 __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm_persistent(const int8_t *__restrict__ A,
                                                    const int8_t *__restrict__ B,
@@ -363,232 +431,33 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm_persistent(const int
                                                    int64_t Np, int64_t KB, int kb0, int KT,
                                                    int64_t c_ld, int64_t c_plane,
                                                    TileMap tmap, int total_tiles, GemmMods mods) {
-    constexpr int THREADS = 64 * WM * WN;              // WM x WN wavefronts
-    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
-    constexpr int CPR = BK / 16;                       // 16-byte chunks per tile row
-    constexpr int ROWS = BM + BN;                      // A rows then B rows in one LDS stage
-    constexpr int CHUNKS = ROWS * CPR;
-    constexpr int LPT = CHUNKS / THREADS;              // LDS-direct loads per lane and tile
-    constexpr int KK = BK / 32;                        // MFMA K steps per tile
-    constexpr int STAGE_BYTES = CHUNKS * 16;
-    constexpr int ROWS_PER_LOAD = 64 / CPR;            // rows one wavefront-wide load covers
-    static_assert(CHUNKS % THREADS == 0 && (BM * CPR) % (64 * LPT) == 0,
-                  "each wavefront must load from one operand only");
-    static_assert(BK == kBlockK, "the K tile is the K block of the operand layout");
-    static_assert(CPR == 4, "the load-side swizzle below assumes one mask per lane");
-    static_assert(STAGES >= 3 && (STAGES - 3) * LPT < 64, "vmcnt is a 6-bit counter");
-    static_assert(KK >= 2, "operand double-buffering assumes an even number of K steps");
-
-    extern __shared__ v4i lds[];                       // [STAGES][ROWS][CPR]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    // Load i of this wavefront fills LDS chunks [64 q, 64 q + 64) of a stage, q = wave*LPT + i,
-    // i.e. rows q*ROWS_PER_LOAD ...; lane -> (row, physical chunk) -> logical chunk to fetch.
-    // In the blocked layout those 64 chunks are 1 KiB of contiguous memory.
-    const int row0 = wave * LPT * ROWS_PER_LOAD + lane / CPR;
-    const int ch = (lane % CPR) ^ swizzle_mask<CPR>(row0);
-    const bool from_a = row0 < BM;
-    const int64_t tile_step = (from_a ? Mp : Np) * BK;  // next K block of the same rows
-    constexpr int src_step = ROWS_PER_LOAD * BK;
-    char *const lds_bytes = reinterpret_cast<char *>(lds);
-    char *const my_dst = lds_bytes + wave * LPT * 1024;
-
-    // A workgroup takes the tiles id = blockIdx.x, blockIdx.x + gridDim.x, ...  Where this
-    // lane's loads of a tile start:
-    // KB = K blocks per slice; this launch contracts over blocks [kb0, kb0 + KT).
-    auto tile_source = [&](int id, int &s_, int &tr_, int &tc_) {
-        map_tile(tmap, id, s_, tr_, tc_);
-        const int8_t *Ab = A + (((int64_t)s_ * KB + kb0) * Mp + (int64_t)tr_ * BM) * BK;
-        const int8_t *Bb = B + (((int64_t)s_ * KB + kb0) * Np + (int64_t)tc_ * BN) * BK;
-        return (from_a ? Ab + (int64_t)row0 * BK : Bb + (int64_t)(row0 - BM) * BK) + ch * 16;
-    };
-
-    // Loads [i0, i1) of K tile t of the tile whose loads start at src_tile.
-    auto issue_loads = [&](const int8_t *src_tile, int t, int i0, int i1) {
-        const int8_t *src = src_tile + (int64_t)t * tile_step;
-        char *dst = my_dst + (t % STAGES) * STAGE_BYTES;
-#pragma unroll
-        for (int i = i0; i < i1; ++i)
-            __builtin_amdgcn_global_load_lds((global_ptr_t)(src + i * src_step),
-                                             (lds_ptr_t)(dst + i * 1024), 16, 0, 0);
-    };
-    // The first STAGES - 1 K tiles of a tile.  KT >= 2: every K range is a multiple of 128.
-    auto issue_head = [&](const int8_t *src_tile) {
-#pragma unroll
-        for (int t = 0; t < STAGES - 1; ++t)
-            if (t < KT) issue_loads(src_tile, t, 0, LPT);
-    };
-
+    typedef GemmCore<WM, WN, TM, TN, BK, STAGES> Core;
+    static_assert(OUT != kOutMax, "the maxima form runs one workgroup per tile");
+    const Core core(Mp, Np);
     int tile = (int)blockIdx.x;
     int s, tile_r, tile_c;
-    const int8_t *src0 = tile_source(tile, s, tile_r, tile_c);
-    issue_head(src0);
-
-    // Fragment addressing: lane l reads row (l % 32) of a 32-row fragment, 16-byte chunk
-    // 2*kk + l/32 of the K tile.  The swizzle mask depends on l % 32 only.
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int mask = swizzle_mask<CPR>(lrow);
-    const int a_off = (wm * 32 * TM + lrow) * CPR;             // in chunks
-    const int b_off = (BM + wn * 32 * TN + lrow) * CPR;
-
-    v4i fa[2][TM], fb[2][TN];
-    auto load_frags = [&](int buf, int t, int kk) {
-        const v4i *st = lds + (t % STAGES) * CHUNKS;
-        const int c = (kk * 2 + lhalf) ^ mask;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[buf][i] = st[a_off + i * 32 * CPR + c];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[buf][j] = st[b_off + j * 32 * CPR + c];
-    };
-
+    map_tile(tmap, tile, s, tile_r, tile_c);
+    const int8_t *src = core.tile_source(A, B, s, tile_r, tile_c, Mp, Np, KB, kb0);
+    core.issue_head(src, KT);
     for (;;) {
-    v16i acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-
-    // K tiles 0 and 1 must have landed before the first fragment reads.  (After a previous
-    // tile of this workgroup its stores are outstanding as well; they were issued after these
-    // loads, and loads complete in order, so "at most the youngest K tile outstanding" still
-    // implies that K tiles 0 and 1 are complete.)
-    if (KT >= STAGES - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, 0);
-
-    // The LPT loads of a tile are spread over the MFMA rows of a K tile (after every row
-    // but the first of each K step), so that a load that has to wait for room in the memory
-    // pipeline holds up one MFMA row, not the whole tile.
-    constexpr int SLOTS = KK * (TM - 1);
-    constexpr int PER_SLOT = (LPT + SLOTS - 1) / SLOTS;
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool issued = kt + STAGES - 1 < KT;      // loads go into the stage read during kt - 1
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const int cur = kk & 1, nxt = cur ^ 1;
-            // The first MFMA row runs before the next operands are requested: its operands
-            // were requested a whole K step ago, so waiting for them (the LDS counter is
-            // waited down to zero at that point) does not wait for the new requests.
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[0][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][0],
-                                                                  acc[0][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (kk + 1 < KK) load_frags(nxt, kt, kk + 1);
-            else if (kt + 1 < KT) load_frags(nxt, kt + 1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 1; i < TM; ++i) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[cur][j], fa[cur][i],
-                                                                      acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                const int slot = kk * (TM - 1) + (i - 1);
-                const int i0 = slot * PER_SLOT, i1 = (i0 + PER_SLOT < LPT) ? i0 + PER_SLOT : LPT;
-                if (issued && i0 < LPT) issue_loads(src0, kt + STAGES - 1, i0, i1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        v16i acc[TM][TN];
+        Core::clear(acc);
+        core.contract(src, KT, acc);
+        // Every wavefront has passed the last barrier, so nothing reads the LDS stages any more:
+        // the head of this workgroup's next tile is requested now and travels while the results
+        // of this one are reduced and stored.
+        const int next = tile + (int)gridDim.x;
+        int s_next = 0, tile_r_next = 0, tile_c_next = 0;
+        const int8_t *src_next = nullptr;
+        if (next < total_tiles) {
+            map_tile(tmap, next, s_next, tile_r_next, tile_c_next);
+            src_next = core.tile_source(A, B, s_next, tile_r_next, tile_c_next, Mp, Np, KB, kb0);
+            core.issue_head(src_next, KT);
         }
-        // Tile kt + 2 must be complete (and visible to every wavefront) before iteration
-        // kt + 1 prefetches fragments from it; the barrier also frees stage kt % STAGES.
-        if (issued) __builtin_amdgcn_s_waitcnt(vmcnt_imm((STAGES - 3) * LPT));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        __builtin_amdgcn_s_barrier();
-    }
-
-    // Every wavefront has passed the last barrier, so nothing reads the LDS stages any more: the
-    // head of this workgroup's next tile is requested now and travels while the results of
-    // this one are reduced and stored.
-    const int next = tile + (int)gridDim.x;
-    int s_next = 0, tile_r_next = 0, tile_c_next = 0;
-    const int8_t *src_next = nullptr;
-    if (next < total_tiles) {
-        src_next = tile_source(next, s_next, tile_r_next, tile_c_next);
-        issue_head(src_next);
-    }
-    const int64_t bm = (int64_t)tile_r * BM, bn = (int64_t)tile_c * BN;
-
-    // The B fragment is the MFMA's first operand, so the 32x32 accumulator is the transposed
-    // tile: lane l holds row (l % 32) of the C tile and, in registers 4g .. 4g+3, the four
-    // consecutive columns 8g + 4*(l / 32) + {0,1,2,3}.  One 16-byte (int32) or 4-byte (uint8)
-    // store per g.  (Staging the uint8 tile through LDS to store whole 64-byte row segments
-    // was measured 3.5 ms slower per launch at 16 x 16384^3, although the 4-byte stores make
-    // the L2 fetch the lines it merges them into.)
-    // (the mulhi form: an FP64 floor/fma version of this reduction measured 1.1 ms slower
-    // per launch at 16 x 16384^3)
-    const int p = mods.p[s], pv = mods.pinv_prime[s];
-    const int64_t c_off = (int64_t)s * c_plane + bm * c_ld + bn;   // C: [slice][row][column]
-    if (OUT == kOutU8) {
-        // Four residues per register quad pack into one dword; the two half-wavefronts hold
-        // alternating dwords of a row (columns 8g + 4*(l/32) ...), so they swap two dwords
-        // each and every lane stores 16 contiguous bytes: a lane pair completes a 32-byte
-        // sector of the row, and the L2 no longer has to fetch lines to merge 4-byte stores.
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                uint32_t d[4];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    d[g] = 0;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        d[g] |= (uint32_t)mod_small(acc[i][j][4 * g + c], p, pv) << (8 * c);
-                }
-                const uint32_t r0 = __shfl_xor(lhalf ? d[0] : d[2], 32, 64);
-                const uint32_t r1 = __shfl_xor(lhalf ? d[1] : d[3], 32, 64);
-                const v4i q = lhalf ? v4i{(int)r0, (int)d[2], (int)r1, (int)d[3]}
-                                    : v4i{(int)d[0], (int)r0, (int)d[1], (int)r1};
-                const int row = wm * 32 * TM + i * 32 + lrow;
-                const int col = wn * 32 * TN + j * 32 + 16 * lhalf;
-                *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * c_ld + col) = q;
-            }
-    } else {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int row = wm * 32 * TM + i * 32 + lrow;
-                const int col = wn * 32 * TN + j * 32 + 8 * g + 4 * lhalf;
-                const int64_t at = c_off + (int64_t)row * c_ld + col;
-                int v[4];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
-                if (OUT == kOutI32 || OUT == kOutI32Fold) {
-                    v4i *dst = reinterpret_cast<v4i *>(static_cast<int32_t *>(C) + at);
-                    if (OUT == kOutI32Fold) {
-                        const v4i old = *dst;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) v[c] = mod_small(old[c], p, pv) + mod_small(v[c], p, pv);
-                    }
-                    *dst = v4i{v[0], v[1], v[2], v[3]};
-                } else {
-                    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(C) + at);
-                    uint32_t packed = 0;
-                    const uint32_t old = OUT == kOutU8Fold ? *dst : 0u;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        int u = mod_small(v[c], p, pv);
-                        if (OUT == kOutU8Fold) {
-                            u += (int)((old >> (8 * c)) & 0xffu);
-                            u -= (u >= p) ? p : 0;
-                        }
-                        packed |= (uint32_t)u << (8 * c);
-                    }
-                    *dst = packed;
-                }
-            }
-    }
-
-    if (next >= total_tiles) break;                    // uniform over the workgroup
-    tile = next; s = s_next; tile_r = tile_r_next; tile_c = tile_c_next; src0 = src_next;
+        core.template store<OUT>(acc, C, s, (int64_t)tile_r * Core::BM, (int64_t)tile_c * Core::BN, c_ld, c_plane,
+                                 mods);
+        if (next >= total_tiles) break;                    // uniform over the workgroup
+        tile = next; s = s_next; tile_r = tile_r_next; tile_c = tile_c_next; src = src_next;
     }
 }
 
