@@ -35,11 +35,23 @@ if ROOT not in sys.path:
 INT8_PEAK_TOPS = 5000.0          # MI355X dense INT8 MFMA, published
 HBM_PEAK_GBS = 8000.0
 
-# L2<->memory bytes per launch of k_int8_gemm (a 4096 x 4096 panel of the 16 moduli: 16 launches
-# per call) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the
-# counters read for `--stage copy` (x2.000 / x1.000); the summary is
-# profiles/oz2_dgemm_16384_N16_counters.txt.  Keyed by (dtype, m=n=k, N).
-MEASURED_GEMM_TRAFFIC_BYTES = {("f64", 16384, 16): 6.44e9 + 0.27e9}
+def measured_gemm_traffic(dtype: str, size: int, num_moduli: int):
+    """L2<->memory bytes per launch of k_int8_gemm for this workload, as measured with rocprofv3
+    (FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the counters read for
+    `--stage copy`).  The figure is not measured by this run: it is read from the committed
+    summary under profiles/ that holds it, from a line of the form
+        bench.roofline.traffic: dtype=f64 size=16384 N=16 bytes=1.09e11 commit=abc1234
+    (the commit the profile was taken at).  None when no summary covers the workload."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(path):
+            if not line.startswith("bench.roofline.traffic:"):
+                continue
+            kv = dict(re.findall(r"(\w+)=(\S+)", line))
+            if kv.get("dtype") == dtype and int(kv.get("size", -1)) == size and int(kv.get("N", -1)) == num_moduli:
+                return {"bytes": float(kv["bytes"]), "commit": kv.get("commit"), "file": os.path.basename(path)}
+    return None
 
 
 def log(*a):
@@ -744,6 +756,7 @@ def main() -> int:
                 np.max(np.abs(sub - r) / np.where(r == 0, 1.0, np.abs(r))))
         log(f"cpu oracle {cpu}")
 
+    traffic = measured_gemm_traffic("f32" if args.sgemm else "f64", m, N) if m == n == k else None
     out = {
         "metric": "emulated FP64 TFLOPS (2mnk/s) at m=n=k=16384; INT8 MFMA % of peak"
                   if not args.sgemm else "emulated FP32 TFLOPS (2mnk/s); INT8 MFMA % of peak",
@@ -762,7 +775,8 @@ def main() -> int:
         "roofline": {"bound": "mfma", "kernel": "k_int8_gemm (batched over moduli)",
                      "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",
                      "frac": gemm_tops / INT8_PEAK_TOPS,
-                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(("f32" if args.sgemm else "f64", m, N)),
+                     "traffic": (traffic or {}).get("bytes"),
+                     "traffic_source": traffic,
                      "ops_per_launch": gemm_ops / gemm_launches,
                      "avg_launch_ms": float(stage_ms[2] / gemm_launches),
                      "launches_per_step": gemm_launches,

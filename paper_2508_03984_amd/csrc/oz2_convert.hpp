@@ -56,7 +56,10 @@ __device__ __forceinline__ void residues_block(int64_t block, const T *__restric
                                                int64_t rows, int64_t len,
                                                const int32_t *__restrict__ t, const ModArgs &ma,
                                                int8_t *__restrict__ out, int64_t rows_pad,
-                                               int64_t len_pad, int64_t rows_stride) {
+                                               int64_t len_pad, int64_t rows_stride, int group_lo = 0,
+                                               int group_hi = 1 << 30) {
+    // Only the moduli of the groups [group_lo, group_hi) (groups of kModGroup) are produced: small
+    // problems spread the groups over several workgroups (see oz2_small.hip).
     // rows_pad rows are written (zeros beyond `rows`); rows_stride >= rows_pad is the number of
     // rows of the whole slice, of which this launch may fill a block.
     // Thread -> (K block, row, 8-element piece of the 64-wide block), piece fastest: a
@@ -105,7 +108,8 @@ __device__ __forceinline__ void residues_block(int64_t block, const T *__restric
         *reinterpret_cast<uint2 *>(o) = make_uint2(w[0], w[1]);
         return;
     }
-    for (int s0 = 0; s0 < ma.n; s0 += kModGroup) {
+    const int s_end = group_hi < (ma.n + kModGroup - 1) / kModGroup ? group_hi * kModGroup : ma.n;
+    for (int s0 = group_lo * kModGroup; s0 < s_end; s0 += kModGroup) {
         double y[kResPerThread];
 #pragma unroll
         for (int i = 0; i < kResPerThread; ++i)
@@ -131,7 +135,9 @@ __device__ __forceinline__ void residues_cols_block(int64_t block_x, int64_t blo
                                                     int64_t cols, const int32_t *__restrict__ t,
                                                     const ModArgs &ma, int8_t *__restrict__ out,
                                                     int64_t cols_pad, int64_t rows_pad,
-                                                    int64_t cols_stride) {
+                                                    int64_t cols_stride, int group_lo = 0,
+                                                    int group_hi = 1 << 30) {
+    // Only the moduli of the groups [group_lo, group_hi) are produced (as in residues_block).
     // cols_pad columns are written (the grid covers them); cols_stride >= cols_pad is the number
     // of rows of the whole transposed slice, of which this launch may fill a block.
     // LDS: per modulus 8 pieces x 64 columns x 8 bytes, piece-major so that the writes of a
@@ -163,8 +169,9 @@ __device__ __forceinline__ void residues_cols_block(int64_t block_x, int64_t blo
     const int col = threadIdx.x >> 2, quarter = threadIdx.x & 3;
     int8_t *dst = out + (kb * cols_stride + block_x * kColStrip) * kBlockK + threadIdx.x * 16;
 
-    const int n_slices = KIND == 0 ? ma.n : 1;
-    for (int s0 = 0; s0 < n_slices; s0 += kGroup) {
+    const int n_all = KIND == 0 ? ma.n : 1;
+    const int n_slices = group_hi < (n_all + kGroup - 1) / kGroup ? group_hi * kGroup : n_all;
+    for (int s0 = group_lo * kGroup; s0 < n_slices; s0 += kGroup) {
         const int ns = n_slices - s0 < kGroup ? n_slices - s0 : kGroup;
         double y[2][8];
 #pragma unroll

@@ -33,6 +33,10 @@ namespace oz2 {
 namespace {
 
 constexpr int64_t kMaxExactK = (int64_t)1 << 17;   // Section 4.3: no INT32 overflow up to here
+#ifndef OZ2_PERSISTENT_MAX_K
+#define OZ2_PERSISTENT_MAX_K 4096
+#endif
+constexpr int64_t kPersistentMaxK = OZ2_PERSISTENT_MAX_K;   // contractions up to here run as a persistent grid
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -417,13 +421,12 @@ __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm(const int8_t *__rest
 // The same as a persistent grid, for short contractions: as many workgroups as compute units,
 // each walking over the tiles id = blockIdx.x, blockIdx.x + gridDim.x, ...  The head of the next
 // tile (its first STAGES - 1 K tiles) is requested before the results of the last one are
-// reduced and stored, and no workgroup is dispatched per tile.  With k <= 1024 a tile is a few
-// microseconds of matrix-core work, so that the store phase and the dispatch between tiles weigh
-// as much as the contraction (16384 x 16384 x 512, N = 15: 3.84 -> 3.09 ms).  For long
-// contractions the one-workgroup-per-tile kernel above is faster: a workgroup that ends does not
-// wait for its stores, a persistent one does at its next wait for loads (loads and stores share
-// one counter on this chip), which costs more than the dispatch it saves (16 x 16384^3 on one
-// device: 62.0 against 60.8 ms).
+// reduced and stored, and no workgroup is dispatched per tile.  With a short k a tile is a few
+// microseconds of matrix-core work, so that the dispatch between tiles and the wait for the
+// first operands weigh as much as the contraction (16384 x 16384 x 512, N = 15: 3.84 -> 3.09 ms;
+// 2048^3, N = 14: 2.5 % faster).  For long contractions the two forms take the same time (the
+// store phase, which nothing overlaps in either form, is what a tile costs beyond its K loop),
+// so the plain one-workgroup-per-tile kernel is kept there.
 template <int WM, int WN, int TM, int TN, int BK, int STAGES, int OUT>
 __global__ __launch_bounds__(64 * WM * WN) void k_int8_gemm_persistent(const int8_t *__restrict__ A,
                                                    const int8_t *__restrict__ B,
@@ -547,7 +550,7 @@ hipError_t launch_out(const int8_t *A, const int8_t *B, void *C, int batch, int6
     // 8 wavefronts (2 per SIMD), each 128 x 64: measured against 4 wavefronts of 128 x 128 on
     // the same device it is 2 % faster at 16 x 16384^3 -- a wavefront that is held up issuing
     // a load leaves the matrix core to its SIMD partner.
-    if (k_len <= 1024)                                 // short contraction: see k_int8_gemm_persistent
+    if (k_len <= kPersistentMaxK)                      // short contraction: see k_int8_gemm_persistent
         return launch_persistent<2, 4, 4, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods,
                                                          stream);
     return launch<2, 4, 4, 2, 64, 4, OUT>(A, B, C, batch, Mp, Np, Kp, k_begin, k_len, pn, mods, stream);

@@ -46,6 +46,11 @@ __device__ inline int shift_from(uint64_t T_, int e, const ShiftArgs &sa) {
     return (sa.f_max - j) - e;
 }
 
+#ifndef OZ2_SPLIT_MODULI_BELOW
+#define OZ2_SPLIT_MODULI_BELOW 600
+#endif
+constexpr unsigned kSplitModuliBelow = OZ2_SPLIT_MODULI_BELOW;   // residue launches with fewer workgroups split the moduli
+
 constexpr int kShiftThreads = 256;      // (1024 threads per workgroup were measured: slower at every size)
 constexpr int kShiftWaves = kShiftThreads / kWave;
 
@@ -187,18 +192,22 @@ __global__ __launch_bounds__(kShiftThreads) void k_small_maxbits(SmallSide<T> a,
 }
 
 // KIND 0: residues for all moduli; KIND 1 (accurate mode): the 7-bit magnitudes ceil(|x| 2^t).
+// gridDim.y > 1: workgroup row y produces the moduli of group y only (groups of kModGroup), so
+// that the smallest problems, whose few workgroups would each walk through all N moduli one after
+// the other, fill more of the chip; the operand is then read once per group, from the caches.
 template <typename T, int ROUNDS, int KIND>
 __global__ __launch_bounds__(256) void k_small_residues(SmallSide<T> a, SmallSide<T> b, ModArgs ma) {
     const bool first = blockIdx.x < a.blocks;
     const SmallSide<T> s = first ? a : b;
     const int64_t blk = first ? blockIdx.x : blockIdx.x - a.blocks;
+    const int g_lo = gridDim.y > 1 ? (int)blockIdx.y : 0, g_hi = gridDim.y > 1 ? (int)blockIdx.y + 1 : 1 << 30;
     if (s.k_contiguous) {
         residues_block<T, ROUNDS, KIND>(blk, s.X, s.ld, s.vecs, s.len, s.t, ma, s.out, s.vecs_pad, s.len_pad,
-                                     s.vecs_pad);
+                                     s.vecs_pad, g_lo, g_hi);
     } else {
         const int64_t strips = s.vecs_pad / kColStrip;
         residues_cols_block<T, ROUNDS, KIND>(blk % strips, blk / strips, s.X, s.ld, s.len, s.vecs, s.t, ma, s.out,
-                                          s.vecs_pad, s.len_pad, s.vecs_pad);
+                                          s.vecs_pad, s.len_pad, s.vecs_pad, g_lo, g_hi);
     }
 }
 
@@ -243,10 +252,13 @@ hipError_t launch_small_residues(const T *A, int64_t lda, bool a_k_contiguous, c
     SmallSide<T> b = side_of<T>(B, ldb, b_k_contiguous, n, k, const_cast<int32_t *>(tB), rB, Np, Kp);
     a.blocks = residue_blocks(a);
     b.blocks = residue_blocks(b);
+    // few workgroups: one row of workgroups per group of moduli (see k_small_residues)
+    const unsigned groups = (unsigned)((ma.n + kModGroup - 1) / kModGroup);
+    const unsigned rows = (a.blocks + b.blocks) < kSplitModuliBelow ? groups : 1u;
     if (ma.rounds == 1)
-        hipLaunchKernelGGL((k_small_residues<T, 1, 0>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
+        hipLaunchKernelGGL((k_small_residues<T, 1, 0>), dim3(a.blocks + b.blocks, rows), dim3(256), 0, stream, a, b, ma);
     else
-        hipLaunchKernelGGL((k_small_residues<T, 2, 0>), dim3(a.blocks + b.blocks), dim3(256), 0, stream, a, b, ma);
+        hipLaunchKernelGGL((k_small_residues<T, 2, 0>), dim3(a.blocks + b.blocks, rows), dim3(256), 0, stream, a, b, ma);
     return hipGetLastError();
 }
 

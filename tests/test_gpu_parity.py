@@ -525,7 +525,7 @@ def test_large_and_skewed_shapes_sampled(oz, oracle):
 
 
 def test_short_contractions_use_the_persistent_gemm(oz, oracle):
-    """k <= 1024 with at least 128 large tiles runs the persistent form of the INT8 GEMM (every
+    """k <= 4096 with at least 128 large tiles runs the persistent form of the INT8 GEMM (every
     workgroup walks over several tiles): full parity on a ragged shape in both product forms,
     and the folding store phases (second K range of a k > 2^17 product, 428 deep) on samples."""
     A, B = S.gemm_inputs(1100, 1500, 700, 1.0, seed=21)             # 5 x 6 tiles x 16 moduli
