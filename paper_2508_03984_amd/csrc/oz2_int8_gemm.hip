@@ -319,7 +319,8 @@ struct GemmCore {
         if (OUT == kOutU8) {
             // Four residues per register quad pack into one dword; the two half-wavefronts hold
             // alternating dwords of a row (columns 8g + 4*(l/32) ...), so they swap two dwords
-            // each and every lane stores 16 contiguous bytes: a lane pair completes a 32-byte
+            // each (lanes 0-31 end up with columns 0-15 of the block row, lanes 32-63 with 16-31)
+            // and every lane stores 16 contiguous bytes: a lane pair completes a 32-byte
             // sector of the row, and the L2 does not have to fetch lines to merge 4-byte stores.
             // (Staging the whole uint8 tile through LDS to store 64-byte row segments was measured
             // 3.5 ms slower per launch at 16 x 16384^3.)
@@ -335,10 +336,12 @@ struct GemmCore {
                         for (int c = 0; c < 4; ++c)
                             d[g] |= (uint32_t)mod_small(acc[i][j][4 * g + c], p, pv) << (8 * c);
                     }
-                    const uint32_t r0 = __shfl_xor(lhalf ? d[0] : d[2], 32, 64);
-                    const uint32_t r1 = __shfl_xor(lhalf ? d[1] : d[3], 32, 64);
-                    const v4i q = lhalf ? v4i{(int)r0, (int)d[2], (int)r1, (int)d[3]}
-                                        : v4i{(int)d[0], (int)r0, (int)d[1], (int)r1};
+                    // v_permlane32_swap(a, b): the upper half of a and the lower half of b change
+                    // places, so lanes 0-31 get (d0 | d0 of lane + 32) and lanes 32-63 (d2 of lane
+                    // - 32 | d2) in (a, b): the row's dwords in column order, no selects needed.
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
+                    const v4i q = v4i{(int)s0[0], (int)s0[1], (int)s1[0], (int)s1[1]};
                     const int row = wm * 32 * TM + i * 32 + lrow;
                     const int col = wn * 32 * TN + j * 32 + 16 * lhalf;
                     *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * c_ld + col) = q;

@@ -50,12 +50,15 @@ __device__ inline int floor_log2_of_bits(uint64_t bits) {
 }
 
 // mod(x, p) in [0, p) for any int32 x and the moduli of Section 4.1, by the mulhi reduction
-// of Section 4.3: y = x - mulhi(x, pinv') p, then one conditional subtraction and addition.
+// of Section 4.3: y = x - mulhi(x, pinv') p lies in (-p, 2p), then one conditional addition and
+// one conditional subtraction.  Both are written as unsigned minima (a negative y is a huge
+// unsigned number and y + p wraps into [0, p); for y < p, y - p wraps to a huge one): two
+// instructions each instead of compare, select and add.
 __device__ inline int mod_small(int x, int p, int pinv_prime) {
-    int y = x - __mulhi(x, pinv_prime) * p;
-    y -= (y >= p) ? p : 0;
-    y += (y < 0) ? p : 0;
-    return y;
+    unsigned y = (unsigned)x - (unsigned)__mulhi(x, pinv_prime) * (unsigned)p;
+    y = min(y, y + (unsigned)p);
+    y = min(y, y - (unsigned)p);
+    return (int)y;
 }
 #endif
 
