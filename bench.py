@@ -640,10 +640,11 @@ def main() -> int:
     ms_per_step = 1e3 * elapsed / args.steps
     tflops = 2.0 * m * n * k / (elapsed / args.steps) / 1e12
     panel_rows, panel_cols, panels = oz.oz2_last_panels()
-    gemm_launches = panels * ((k + (1 << 17) - 1) >> 17)          # one per panel and K range of 2^17
+    gemm_launches = oz.oz2_last_gemm_launches()                  # of the last step: per launch panel and K range of 2^17
     log(f"oz2 {'sgemm' if args.sgemm else 'dgemm'} N={N}: {ms_per_step:.2f} ms/step, "
         f"{tflops:.1f} emulated TFLOP/s; stages [shift, residues, gemm, epilogue] ms = "
-        f"{np.round(stage_ms, 3).tolist()}; {panels} panel(s) of {panel_rows} x {panel_cols}")
+        f"{np.round(stage_ms, 3).tolist()}; {panels} panel(s) of {panel_rows} x {panel_cols}, "
+        f"{gemm_launches} INT8 GEMM launch(es)")
     # dominant kernel: the batched INT8 GEMM on the padded slices
     pad = lambda x, to: (x + to - 1) // to * to
     Mp, Np, Kp = pad(m, 256), pad(n, 256), pad(k, 128)

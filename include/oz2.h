@@ -272,7 +272,12 @@ oz2_status oz2_ctx_sgemm_prepared(oz2_context *ctx, const oz2_operand *left, con
  * shape is cut in a workspace of `workspace_bytes` (host pointers, may be NULL: rows and
  * columns of a panel, multiples of 256, the last panels of a row or column may be smaller;
  * and the number of panels); oz2_last_panels reports the same for the most recent product
- * (OZ2_INVALID_ARG if there was none).
+ * (OZ2_INVALID_ARG if there was none).  A product whose planes all fit the workspace (one
+ * panel) may still run its INT8 GEMMs as several launches, each writing its part of the whole
+ * product in place (a launch over all of a large C loses cache locality as its workgroups drift
+ * apart); oz2_last_gemm_launches reports the number of INT8 GEMM launches that produced the
+ * products of the most recent call (host pointer; accurate mode's launches for Cbar are not
+ * counted).
  */
 size_t oz2_workspace_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double);
 size_t oz2_workspace_min_bytes(int64_t m, int64_t n, int64_t k, int num_moduli, int is_double);
@@ -281,6 +286,7 @@ void oz2_set_workspace_limit(size_t bytes);
 oz2_status oz2_plan_panels(int64_t m, int64_t n, int64_t k, int num_moduli, size_t workspace_bytes,
                            int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
 oz2_status oz2_last_panels(int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
+oz2_status oz2_last_gemm_launches(int64_t *launches);
 void oz2_release(void);
 size_t oz2_ctx_workspace_bytes(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli);
 size_t oz2_ctx_workspace_min_bytes(oz2_context *ctx, int64_t m, int64_t n, int64_t k, int num_moduli);
@@ -290,6 +296,7 @@ oz2_status oz2_ctx_plan_panels(oz2_context *ctx, int64_t m, int64_t n, int64_t k
                                size_t workspace_bytes, int64_t *panel_rows, int64_t *panel_cols,
                                int64_t *count);
 oz2_status oz2_ctx_last_panels(oz2_context *ctx, int64_t *panel_rows, int64_t *panel_cols, int64_t *count);
+oz2_status oz2_ctx_last_gemm_launches(oz2_context *ctx, int64_t *launches);
 oz2_status oz2_ctx_release(oz2_context *ctx);    /* frees what the context owns on the device, keeps the context */
 
 /*

@@ -22,7 +22,7 @@ EXPORTS = [
     "oz2_last_stage_times_ms", "oz2_status_string", "oz2_set_int32_products", "oz2_mfma_probe",
     "oz2_dgemm_op", "oz2_sgemm_op", "oz2_prepare_d", "oz2_prepare_s", "oz2_operand_free",
     "oz2_operand_bytes", "oz2_dgemm_prepared", "oz2_sgemm_prepared", "oz2_workspace_min_bytes",
-    "oz2_set_workspace_limit", "oz2_last_panels", "oz2_plan_panels", "oz2_set_overlap",
+    "oz2_set_workspace_limit", "oz2_last_panels", "oz2_last_gemm_launches", "oz2_ctx_last_gemm_launches", "oz2_plan_panels", "oz2_set_overlap",
     "oz2_set_small_conversion", "oz2_dgemm_colmajor", "oz2_sgemm_colmajor", "oz2_residue_rounds",
     "oz2_create", "oz2_destroy", "oz2_ctx_set_option", "oz2_ctx_dgemm", "oz2_ctx_sgemm",
     "oz2_ctx_dgemm_prepared", "oz2_ctx_sgemm_prepared", "oz2_ctx_workspace_bytes",
@@ -122,6 +122,8 @@ def load():
     lib.oz2_ctx_set_workspace_limit.argtypes = [vp, C.c_size_t]
     lib.oz2_ctx_plan_panels.argtypes = [vp] + lib.oz2_plan_panels.argtypes
     lib.oz2_ctx_last_panels.argtypes = [vp] + lib.oz2_last_panels.argtypes
+    lib.oz2_last_gemm_launches.argtypes = [C.POINTER(i64)]
+    lib.oz2_ctx_last_gemm_launches.argtypes = [vp, C.POINTER(i64)]
     lib.oz2_ctx_release.argtypes = [vp]
     lib.oz2_ctx_stage_ptr.argtypes = [vp] + lib.oz2_stage_ptr.argtypes
     lib.oz2_ctx_last_stage_times_ms.argtypes = [vp, C.POINTER(flt)]
@@ -528,6 +530,16 @@ def oz2_ctx_last_panels(ctx) -> Tuple[int, int, int]:
     pr, pc, cnt = C.c_int64(), C.c_int64(), C.c_int64()
     _check(load().oz2_ctx_last_panels(_ctx(ctx), C.byref(pr), C.byref(pc), C.byref(cnt)), "oz2_ctx_last_panels")
     return int(pr.value), int(pc.value), int(cnt.value)
+
+
+def oz2_ctx_last_gemm_launches(ctx) -> int:
+    cnt = C.c_int64()
+    _check(load().oz2_ctx_last_gemm_launches(_ctx(ctx), C.byref(cnt)), "oz2_ctx_last_gemm_launches")
+    return int(cnt.value)
+
+
+def oz2_last_gemm_launches() -> int:
+    return oz2_ctx_last_gemm_launches(None)
 
 
 def oz2_ctx_release(ctx) -> None:

@@ -28,6 +28,7 @@ struct oz2_context {
     size_t ws_limit = 0;                   // for the library's own buffer; 0 = none
     oz2::Layout last{};
     oz2::Panels last_panels{0, 0, 0};
+    int64_t last_gemm_launches = 0;        // INT8 GEMM launches of the products of the last call
     bool have_last = false;                // shifts and residues of the last call are in the workspace
     bool have_last_prod = false;           // ... and so are all its products
     bool have_panels = false;
@@ -160,6 +161,28 @@ template <typename T>
 oz2_status run_products(Ctx &g, const Layout &L, const Panels &P, const int8_t *rA, const int8_t *rB,
                         const int32_t *tA, const int32_t *tB, void *prod, const ModArgs &ma,
                         double alpha, double beta, T *C, int64_t ldc, hipStream_t stream) {
+    if (P.count == 1) {
+        // all planes fit: the GEMM launches are cut (launch_panels) and write their parts of the
+        // whole product in place; one accumulation over all of C follows
+        const Panels Q = launch_panels(L);
+        const int64_t plane = L.Mp * L.Np;
+        const size_t entry = L.prod_u8 ? 1 : 4;
+        for (int64_t row0 = 0; row0 < L.Mp; row0 += Q.pr)
+            for (int64_t col0 = 0; col0 < L.Np; col0 += Q.pc) {
+                const int64_t rows = std::min(Q.pr, L.Mp - row0), cols = std::min(Q.pc, L.Np - col0);
+                const GemmPanel pn{row0, rows, col0, cols, L.Np, plane};
+                void *dst = static_cast<char *>(prod) + (size_t)(row0 * L.Np + col0) * entry;
+                for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
+                    const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
+                    ++g.last_gemm_launches;
+                    OZ2_TRY(launch_int8_gemm(rA, rB, dst, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0, &ma,
+                                             stream, &pn));
+                }
+            }
+        if (oz2_status st = mark(g, 3, stream)) return st;
+        OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, L.Mp, L.Np, L.m, L.n, tA, tB, ma, alpha, beta, C, ldc, stream));
+        return mark(g, 4, stream);
+    }
     int64_t done = 0;
     for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
         for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
@@ -167,6 +190,7 @@ oz2_status run_products(Ctx &g, const Layout &L, const Panels &P, const int8_t *
             const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
             for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
                 const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
+                ++g.last_gemm_launches;
                 OZ2_TRY(launch_int8_gemm(rA, rB, prod, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0,
                                          &ma, stream, &pn));
             }
@@ -247,6 +271,7 @@ oz2_status run_overlapped(Ctx &g, const Layout &L, const Panels &P, const T *A, 
         const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
         for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
             const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
+            ++g.last_gemm_launches;
             OZ2_TRY(launch_int8_gemm(rA, rB, prod, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0, &ma, stream,
                                      &pn));
         }
@@ -295,7 +320,7 @@ oz2_status gemm_impl(Ctx &g, int opA, int opB, int64_t m, int64_t n, int64_t k, 
     const Panels Po = overlap_panels(L, P);                // a workspace limit may have made the panels smaller
     const bool overlapped = g.overlap && overlap_applies(L.Kp, Po.count);
     if (overlapped) P = Po;
-    g.last = L; g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0;
+    g.last = L; g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0; g.last_gemm_launches = 0;
     g.have_last = true; g.have_last_prod = P.count == 1; g.ev_recorded = false;
 
     void *scratch = g.ws + L.off_bt;
@@ -418,7 +443,7 @@ oz2_status prepared_impl(Ctx &g, const oz2_operand *l, const oz2_operand *r, dou
     Panels P{};
     if (oz2_status st = ensure_workspace(g, L.prod_whole, L.prod_min, &have)) return st;
     if (!plan_panels(L, have, &P)) return OZ2_WORKSPACE;
-    g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0;
+    g.last_panels = P; g.have_panels = true; g.last_overlapped_panels = 0; g.last_gemm_launches = 0;
     g.have_last = g.have_last_prod = false; g.ev_recorded = false;
     for (int i = 0; i < 3; ++i)
         if (oz2_status st = mark(g, i, stream)) return st;
@@ -569,6 +594,14 @@ oz2_status oz2_ctx_last_panels(oz2_context *ctx, int64_t *panel_rows, int64_t *p
     return OZ2_OK;
 }
 
+oz2_status oz2_ctx_last_gemm_launches(oz2_context *ctx, int64_t *launches) {
+    Ctx &g = resolve(ctx);
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (!g.have_panels || !launches) return OZ2_INVALID_ARG;
+    *launches = g.last_gemm_launches;
+    return OZ2_OK;
+}
+
 oz2_status oz2_ctx_stage_ptr(oz2_context *ctx, int stage, void **dev_ptr, int64_t *dims) {
     Ctx &g = resolve(ctx);
     std::lock_guard<std::mutex> lock(g.mu);
@@ -714,6 +747,7 @@ oz2_status oz2_plan_panels(int64_t m, int64_t n, int64_t k, int num_moduli, size
 oz2_status oz2_last_panels(int64_t *panel_rows, int64_t *panel_cols, int64_t *count) {
     return oz2_ctx_last_panels(nullptr, panel_rows, panel_cols, count);
 }
+oz2_status oz2_last_gemm_launches(int64_t *launches) { return oz2_ctx_last_gemm_launches(nullptr, launches); }
 
 oz2_status oz2_set_workspace(void *dev_ptr, size_t bytes) { return oz2_ctx_set_workspace(nullptr, dev_ptr, bytes); }
 

@@ -352,6 +352,17 @@ int main(int argc, char **argv) {
             Panels P{0, 0, 0};
             const bool ok = ws >= L.off_prod && plan_panels(L, ws - L.off_prod, &P);
             const Panels Po = ok ? overlap_panels(L, P) : P;
+            // the cut of the GEMM launches of an unbounded product: whole panels that tile C exactly
+            const Panels Q = launch_panels(L);
+            int64_t covered = 0, launches = 0;
+            for (int64_t r0 = 0; r0 < L.Mp; r0 += Q.pr)
+                for (int64_t c0 = 0; c0 < L.Np; c0 += Q.pc) {
+                    const int64_t rows = std::min(Q.pr, L.Mp - r0), cols = std::min(Q.pc, L.Np - c0);
+                    if (rows <= 0 || cols <= 0 || rows % kPadMN || cols % kPadMN || r0 % kPadMN || c0 % kPadMN) return 3;
+                    covered += rows * cols; ++launches;
+                }
+            if (covered != L.Mp * L.Np || launches != Q.count || Q.pr > L.Mp || Q.pc > L.Np) return 4;
+            if (L.Kp < kLaunchPanelMinK && Q.count != 1) return 5;
             std::printf("%lld %lld %lld %d %zu %d : %zu %zu %d %lld %lld %lld | %lld %lld %lld %d %d\n", (long long)m,
                         (long long)n, (long long)k, N, ws, u8, L.off_prod + L.prod_whole, L.off_prod + L.prod_min, (int)ok,
                         (long long)P.pr, (long long)P.pc, (long long)P.count, (long long)Po.pr, (long long)Po.pc,

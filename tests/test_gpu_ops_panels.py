@@ -582,6 +582,7 @@ def test_overlapped_form_with_k_ranges_fp32_and_a_workspace_limit(oz, oracle):
     try:
         want = oz.matmul(dA, dB, N)
         assert oz.oz2_last_panels() == (4352, 4608, 1)
+        assert oz.oz2_last_gemm_launches() == 4            # 4096 + 256 rows, two K ranges each
     finally:
         oz.oz2_set_overlap(True)
     got = oz.matmul(dA, dB, N)                             # four panels, and k is long enough to overlap

@@ -483,6 +483,19 @@ def test_config_16384_dgemm_sampled(oz, oracle):
     modulus) and on 10^5 scattered entries."""
     sampled_parity(oz, oracle, 16384, 16384, 16384, 16, 0.5, np.float64, seed=0,
                    bands=256, n_entries=100000)
+    assert oz.oz2_last_panels() == (16384, 16384, 1) and oz.oz2_last_gemm_launches() == 8
+
+
+def test_gemm_launches_cut_in_place(oz, oracle):
+    """A product whose planes all fit the workspace runs its INT8 GEMMs as several launches for a
+    long contraction (here 4096 + 512 rows by 8192 + 512 columns: four launches, ragged ones
+    included), each writing its part of the whole product in place: products and C equal the
+    oracle's on rows of every launch panel; a short contraction stays one launch."""
+    sampled_parity(oz, oracle, 4500, 8600, 8200, 6, 1.0, np.float64, seed=31, bands=512, n_entries=4000)
+    assert oz.oz2_last_panels() == (4608, 8704, 1) and oz.oz2_last_gemm_launches() == 4
+    sampled_parity(oz, oracle, 4500, 8600, 520, 14, 0.5, np.float64, seed=32, n_rows=4, n_entries=1000)
+    assert oz.oz2_last_panels() == (4608, 8704, 1) and oz.oz2_last_gemm_launches() == 1
+    oz.oz2_release()
 
 
 @pytest.mark.parametrize("phi,N", [(1.0, 18), (2.0, 20)])
