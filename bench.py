@@ -40,8 +40,9 @@ def measured_gemm_traffic(dtype: str, size: int, num_moduli: int):
     (FETCH_SIZE / WRITE_SIZE runs of this script, scaled by what the counters read for
     `--stage copy`).  The figure is not measured by this run: it is read from the committed
     summary under profiles/ that holds it, from a line of the form
-        bench.roofline.traffic: dtype=f64 size=16384 N=16 bytes=1.09e11 commit=abc1234
-    (the commit the profile was taken at).  None when no summary covers the workload."""
+        bench.roofline.traffic: dtype=f64 size=16384 N=16 launches=8 bytes=1.7e10 commit=abc1234
+    (bytes per launch, the launches a call made in the profiled run, the commit the profile was
+    taken at).  None when no summary covers the workload."""
     import glob
     import re
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
@@ -50,7 +51,8 @@ def measured_gemm_traffic(dtype: str, size: int, num_moduli: int):
                 continue
             kv = dict(re.findall(r"(\w+)=(\S+)", line))
             if kv.get("dtype") == dtype and int(kv.get("size", -1)) == size and int(kv.get("N", -1)) == num_moduli:
-                return {"bytes": float(kv["bytes"]), "commit": kv.get("commit"), "file": os.path.basename(path)}
+                return {"bytes": float(kv["bytes"]), "launches": int(kv.get("launches", 1)), "commit": kv.get("commit"),
+                        "file": os.path.basename(path)}
     return None
 
 
@@ -776,7 +778,8 @@ def main() -> int:
         "roofline": {"bound": "mfma", "kernel": "k_int8_gemm (batched over moduli)",
                      "achieved": gemm_tops, "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",
                      "frac": gemm_tops / INT8_PEAK_TOPS,
-                     "traffic": (traffic or {}).get("bytes"),
+                     # per launch of THIS run (the profiled run's bytes per call over this run's launches)
+                     "traffic": traffic["bytes"] * traffic["launches"] / gemm_launches if traffic else None,
                      "traffic_source": traffic,
                      "ops_per_launch": gemm_ops / gemm_launches,
                      "avg_launch_ms": float(stage_ms[2] / gemm_launches),
