@@ -162,9 +162,10 @@ oz2_status run_products(Ctx &g, const Layout &L, const Panels &P, const int8_t *
                         const int32_t *tA, const int32_t *tB, void *prod, const ModArgs &ma,
                         double alpha, double beta, T *C, int64_t ldc, hipStream_t stream) {
     if (P.count == 1) {
-        // all planes fit: the GEMM launches are cut (launch_panels) and write their parts of the
-        // whole product in place; one accumulation over all of C follows
+        // all planes fit: the GEMM launches are cut (launch_panels, launch_k_len) and write their
+        // parts of the whole product in place; one accumulation over all of C follows
         const Panels Q = launch_panels(L);
+        const int64_t k_len = launch_k_len(L, Q);
         const int64_t plane = L.Mp * L.Np;
         const size_t entry = L.prod_u8 ? 1 : 4;
         for (int64_t row0 = 0; row0 < L.Mp; row0 += Q.pr)
@@ -172,8 +173,8 @@ oz2_status run_products(Ctx &g, const Layout &L, const Panels &P, const int8_t *
                 const int64_t rows = std::min(Q.pr, L.Mp - row0), cols = std::min(Q.pc, L.Np - col0);
                 const GemmPanel pn{row0, rows, col0, cols, L.Np, plane};
                 void *dst = static_cast<char *>(prod) + (size_t)(row0 * L.Np + col0) * entry;
-                for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
-                    const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
+                for (int64_t k0 = 0; k0 < L.Kp; k0 += k_len) {
+                    const int64_t len = std::min<int64_t>(k_len, L.Kp - k0);
                     ++g.last_gemm_launches;
                     OZ2_TRY(launch_int8_gemm(rA, rB, dst, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0, &ma,
                                              stream, &pn));

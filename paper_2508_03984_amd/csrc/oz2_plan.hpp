@@ -158,6 +158,28 @@ inline Panels launch_panels(const Layout &L) {
     return Q;
 }
 
+// ... and along k: a launch of such a panel is kept to about kLaunchMs of matrix-core work (a
+// round of 256 tiles takes about 13.4 ns per element of k), in equal K ranges that are multiples
+// of 8192; the results of the ranges are folded modulo p_s in the GEMM's store phase like the
+// ranges of 2^17 that exactness requires (Section 4.3).  Returns the length of a K range: Kp
+// itself when one launch is short enough, never more than OZ2_MAX_K.  Measured: 8192 x 8192 x
+// 65536, N = 18: 74.3 -> 72.3 ms; 4096 x 4096 x 131072, N = 16: 38.4 -> 36.6 ms.
+constexpr double kLaunchMs = 7.0, kRoundNsPerK = 13.4;
+constexpr int64_t kLaunchKStep = 8192;
+
+inline int64_t launch_k_len(const Layout &L, const Panels &Q) {
+    const int64_t whole = std::min<int64_t>(L.Kp, OZ2_MAX_K);
+    if (kLaunchPanelRows <= 0 || L.Kp < 2 * kLaunchPanelMinK) return whole;
+    const int64_t tiles = (Q.pr / kPadMN) * (Q.pc / kPadMN) * L.N;
+    const int64_t rounds = (tiles + 255) / 256;
+    const double want = kLaunchMs * 1e6 / (kRoundNsPerK * (double)rounds);      // elements of k per launch
+    int64_t len = std::max<int64_t>(kLaunchKStep, (int64_t)(want / kLaunchKStep + 0.5) * kLaunchKStep);
+    if (2 * L.Kp < 3 * len) return whole;                  // less than one and a half launches: leave it whole
+    const int64_t n = (L.Kp + len - 1) / len;
+    len = round_up((L.Kp + n - 1) / n, kLaunchKStep);
+    return std::min<int64_t>(len, OZ2_MAX_K);
+}
+
 // Side of a panel of the overlapped form: the INT8 GEMM loses nothing down to 4096 x 4096.
 constexpr int64_t kOverlapPanel = 4096;
 

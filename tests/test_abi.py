@@ -363,6 +363,9 @@ int main(int argc, char **argv) {
                 }
             if (covered != L.Mp * L.Np || launches != Q.count || Q.pr > L.Mp || Q.pc > L.Np) return 4;
             if (L.Kp < kLaunchPanelMinK && Q.count != 1) return 5;
+            const int64_t kl = launch_k_len(L, Q);
+            if (kl <= 0 || kl > OZ2_MAX_K || kl % kPadK || (kl < L.Kp && kl % kLaunchKStep)) return 6;
+            if (L.Kp <= OZ2_MAX_K && L.Kp < 2 * kLaunchPanelMinK && kl != L.Kp) return 7;
             std::printf("%lld %lld %lld %d %zu %d : %zu %zu %d %lld %lld %lld | %lld %lld %lld %d %d\n", (long long)m,
                         (long long)n, (long long)k, N, ws, u8, L.off_prod + L.prod_whole, L.off_prod + L.prod_min, (int)ok,
                         (long long)P.pr, (long long)P.pc, (long long)P.count, (long long)Po.pr, (long long)Po.pc,

@@ -498,6 +498,15 @@ def test_gemm_launches_cut_in_place(oz, oracle):
     oz.oz2_release()
 
 
+def test_gemm_launches_cut_along_k(oz, oracle):
+    """Launches with many rounds of workgroups and a long contraction are also cut along k (here two
+    K ranges of 24576 although k < 2^17): the second range is folded onto the first modulo p_s in
+    the store phase, and U_s and C still equal the oracle's."""
+    sampled_parity(oz, oracle, 4096, 4096, 49152, 16, 0.5, np.float64, seed=33, n_rows=3, n_entries=3000)
+    assert oz.oz2_last_panels() == (4096, 4096, 1) and oz.oz2_last_gemm_launches() == 2
+    oz.oz2_release()
+
+
 @pytest.mark.parametrize("phi,N", [(1.0, 18), (2.0, 20)])
 def test_config_16384_dgemm_wider_exponent_range_sampled(oz, oracle, phi, N):
     """The other corners of the 16384^3 configuration (phi up to 2, up to 20 moduli, the widest
