@@ -161,40 +161,28 @@ template <typename T>
 oz2_status run_products(Ctx &g, const Layout &L, const Panels &P, const int8_t *rA, const int8_t *rB,
                         const int32_t *tA, const int32_t *tB, void *prod, const ModArgs &ma,
                         double alpha, double beta, T *C, int64_t ldc, hipStream_t stream) {
-    if (P.count == 1) {
-        // all planes fit: the GEMM launches are cut (launch_panels, launch_k_len) and write their
-        // parts of the whole product in place; one accumulation over all of C follows
-        const Panels Q = launch_panels(L);
-        const int64_t k_len = launch_k_len(L, Q);
-        const int64_t plane = L.Mp * L.Np;
-        const size_t entry = L.prod_u8 ? 1 : 4;
-        for (int64_t row0 = 0; row0 < L.Mp; row0 += Q.pr)
-            for (int64_t col0 = 0; col0 < L.Np; col0 += Q.pc) {
-                const int64_t rows = std::min(Q.pr, L.Mp - row0), cols = std::min(Q.pc, L.Np - col0);
-                const GemmPanel pn{row0, rows, col0, cols, L.Np, plane};
-                void *dst = static_cast<char *>(prod) + (size_t)(row0 * L.Np + col0) * entry;
-                for (int64_t k0 = 0; k0 < L.Kp; k0 += k_len) {
-                    const int64_t len = std::min<int64_t>(k_len, L.Kp - k0);
-                    ++g.last_gemm_launches;
-                    OZ2_TRY(launch_int8_gemm(rA, rB, dst, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0, &ma,
-                                             stream, &pn));
-                }
-            }
-        if (oz2_status st = mark(g, 3, stream)) return st;
-        OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, L.Mp, L.Np, L.m, L.n, tA, tB, ma, alpha, beta, C, ldc, stream));
-        return mark(g, 4, stream);
-    }
+    // The product buffer holds one panel of C at a time: [N][rows][cols] (all of C if P.count is 1).
+    // The GEMM launches of a panel are cut further (launch_panels, launch_k_len), each writing its
+    // part of the buffer in place.  (The diagnostic int32 form keeps the raw sums C'_s of a whole
+    // contraction up to 2^17.)
+    const size_t entry = L.prod_u8 ? 1 : 4;
     int64_t done = 0;
     for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
         for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
             const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);
-            const GemmPanel pn{row0, rows, col0, cols, cols, rows * cols};
-            for (int64_t k0 = 0; k0 < L.Kp; k0 += OZ2_MAX_K) {
-                const int64_t len = std::min<int64_t>(OZ2_MAX_K, L.Kp - k0);
-                ++g.last_gemm_launches;
-                OZ2_TRY(launch_int8_gemm(rA, rB, prod, L.N, L.Mp, L.Np, L.Kp, k0, len, L.prod_u8, k0 > 0,
-                                         &ma, stream, &pn));
-            }
+            const Panels Q = launch_panels(rows, cols, L.Kp);
+            const int64_t k_len = L.prod_u8 ? launch_k_len(L.Kp, L.N, Q) : std::min<int64_t>(L.Kp, OZ2_MAX_K);
+            for (int64_t r1 = 0; r1 < rows; r1 += Q.pr)
+                for (int64_t c1 = 0; c1 < cols; c1 += Q.pc) {
+                    const GemmPanel pn{row0 + r1, std::min(Q.pr, rows - r1), col0 + c1, std::min(Q.pc, cols - c1), cols,
+                                       rows * cols};
+                    void *dst = static_cast<char *>(prod) + (size_t)(r1 * cols + c1) * entry;
+                    for (int64_t k0 = 0; k0 < L.Kp; k0 += k_len) {
+                        ++g.last_gemm_launches;
+                        OZ2_TRY(launch_int8_gemm(rA, rB, dst, L.N, L.Mp, L.Np, L.Kp, k0, std::min<int64_t>(k_len, L.Kp - k0),
+                                                 L.prod_u8, k0 > 0, &ma, stream, &pn));
+                    }
+                }
             if (++done == P.count)                            // stage times: the last accumulation only
                 if (oz2_status st = mark(g, 3, stream)) return st;
             OZ2_TRY(launch_epilogue<T>(prod, L.prod_u8, rows, cols, std::min(L.m - row0, rows),

@@ -127,9 +127,9 @@ inline bool plan_panels(const Layout &L, size_t avail, Panels *out) {
     return true;
 }
 
-// How the INT8 GEMM launches of a product are cut when all its planes fit the workspace (one
-// workspace panel): into launches of at most kLaunchPanelRows x kLaunchPanelCols entries of C per
-// modulus, each writing its part of the whole product in place.  A launch over all of a large C
+// How the INT8 GEMM launches of a product (of each workspace panel, if C is worked through in
+// panels) are cut: into launches of at most kLaunchPanelRows x kLaunchPanelCols entries of C per
+// modulus, each writing its part of the product buffer in place.  A launch over all of a large C
 // runs hundreds of rounds of 256 workgroups; over such a launch the workgroups of a round drift
 // apart, the operand tiles that an XCD's L2 holds are shared by fewer of its workgroups and the
 // launch fetches a quarter more through the fabric.  A launch boundary every 32 rounds or so
@@ -150,11 +150,12 @@ inline bool plan_panels(const Layout &L, size_t avail, Panels *out) {
 constexpr int64_t kLaunchPanelRows = OZ2_LAUNCH_PANEL_ROWS, kLaunchPanelCols = OZ2_LAUNCH_PANEL_COLS;
 constexpr int64_t kLaunchPanelMinK = OZ2_LAUNCH_PANEL_MIN_K;
 
-inline Panels launch_panels(const Layout &L) {
-    Panels Q{L.Mp, L.Np, 1};
-    if (kLaunchPanelRows <= 0 || L.Kp < kLaunchPanelMinK) return Q;
-    Q.pr = std::min(L.Mp, kLaunchPanelRows); Q.pc = std::min(L.Np, kLaunchPanelCols);
-    Q.count = ((L.Mp + Q.pr - 1) / Q.pr) * ((L.Np + Q.pc - 1) / Q.pc);
+// rows x cols: the padded extent of what the launches cover (all of C, or one workspace panel).
+inline Panels launch_panels(int64_t rows, int64_t cols, int64_t Kp) {
+    Panels Q{rows, cols, 1};
+    if (kLaunchPanelRows <= 0 || Kp < kLaunchPanelMinK) return Q;
+    Q.pr = std::min(rows, kLaunchPanelRows); Q.pc = std::min(cols, kLaunchPanelCols);
+    Q.count = ((rows + Q.pr - 1) / Q.pr) * ((cols + Q.pc - 1) / Q.pc);
     return Q;
 }
 
@@ -167,16 +168,16 @@ inline Panels launch_panels(const Layout &L) {
 constexpr double kLaunchMs = 7.0, kRoundNsPerK = 13.4;
 constexpr int64_t kLaunchKStep = 8192;
 
-inline int64_t launch_k_len(const Layout &L, const Panels &Q) {
-    const int64_t whole = std::min<int64_t>(L.Kp, OZ2_MAX_K);
-    if (kLaunchPanelRows <= 0 || L.Kp < 2 * kLaunchPanelMinK) return whole;
-    const int64_t tiles = (Q.pr / kPadMN) * (Q.pc / kPadMN) * L.N;
+inline int64_t launch_k_len(int64_t Kp, int N, const Panels &Q) {
+    const int64_t whole = std::min<int64_t>(Kp, OZ2_MAX_K);
+    if (kLaunchPanelRows <= 0 || Kp < 2 * kLaunchPanelMinK) return whole;
+    const int64_t tiles = (Q.pr / kPadMN) * (Q.pc / kPadMN) * N;
     const int64_t rounds = (tiles + 255) / 256;
     const double want = kLaunchMs * 1e6 / (kRoundNsPerK * (double)rounds);      // elements of k per launch
     int64_t len = std::max<int64_t>(kLaunchKStep, (int64_t)(want / kLaunchKStep + 0.5) * kLaunchKStep);
-    if (2 * L.Kp < 3 * len) return whole;                  // less than one and a half launches: leave it whole
-    const int64_t n = (L.Kp + len - 1) / len;
-    len = round_up((L.Kp + n - 1) / n, kLaunchKStep);
+    if (2 * Kp < 3 * len) return whole;                    // less than one and a half launches: leave it whole
+    const int64_t n = (Kp + len - 1) / len;
+    len = round_up((Kp + n - 1) / n, kLaunchKStep);
     return std::min<int64_t>(len, OZ2_MAX_K);
 }
 

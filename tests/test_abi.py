@@ -353,7 +353,7 @@ int main(int argc, char **argv) {
             const bool ok = ws >= L.off_prod && plan_panels(L, ws - L.off_prod, &P);
             const Panels Po = ok ? overlap_panels(L, P) : P;
             // the cut of the GEMM launches of an unbounded product: whole panels that tile C exactly
-            const Panels Q = launch_panels(L);
+            const Panels Q = launch_panels(L.Mp, L.Np, L.Kp);
             int64_t covered = 0, launches = 0;
             for (int64_t r0 = 0; r0 < L.Mp; r0 += Q.pr)
                 for (int64_t c0 = 0; c0 < L.Np; c0 += Q.pc) {
@@ -363,7 +363,7 @@ int main(int argc, char **argv) {
                 }
             if (covered != L.Mp * L.Np || launches != Q.count || Q.pr > L.Mp || Q.pc > L.Np) return 4;
             if (L.Kp < kLaunchPanelMinK && Q.count != 1) return 5;
-            const int64_t kl = launch_k_len(L, Q);
+            const int64_t kl = launch_k_len(L.Kp, L.N, Q);
             if (kl <= 0 || kl > OZ2_MAX_K || kl % kPadK || (kl < L.Kp && kl % kLaunchKStep)) return 6;
             if (L.Kp <= OZ2_MAX_K && L.Kp < 2 * kLaunchPanelMinK && kl != L.Kp) return 7;
             std::printf("%lld %lld %lld %d %zu %d : %zu %zu %d %lld %lld %lld | %lld %lld %lld %d %d\n", (long long)m,
