@@ -541,6 +541,59 @@ def sweep_overlap(oz, torch, args) -> int:
     return 0
 
 
+def sweep_launches(oz, torch, args) -> int:
+    """One INT8 GEMM launch per product (option OZ2_OPT_CUT_LAUNCHES off) against the default, in
+    which the launches of a large product are cut into parts of C and K ranges, on the same device
+    and buffers, in turns; the results must be the same bits.  One JSON line per workload goes to
+    --out."""
+    import numpy as np
+    import synth_inputs as S
+    from paper_2508_03984_amd import binding as b
+    path = args.out or "sweep_launches.jsonl"
+    if os.path.dirname(path):
+        os.makedirs(os.path.dirname(path), exist_ok=True)
+    cases = [(16384, 16384, 16384, 16, True, False), (16384, 16384, 16384, 14, True, False),
+             (16384, 16384, 16384, 16, True, True), (16384, 16384, 16384, 8, False, False),
+             (8192, 8192, 65536, 18, True, False), (10000, 9000, 20000, 15, True, False),
+             (8192, 8192, 8192, 16, True, False), (16384, 16384, 4096, 15, True, False)]
+    with open(path, "w") as f:
+        for (m, n, k, N, is_double, accurate) in cases:
+            A, B = S.gemm_inputs(m, n, k, args.phi, seed=0, dtype=np.float64 if is_double else np.float32)
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+            del A, B
+            dC = torch.empty((m, n), dtype=dA.dtype, device="cuda")
+            call = lambda: oz.matmul(dA, dB, N, out=dC, accurate=accurate)
+            ms, launches, sums = {False: [], True: []}, {}, {}
+            try:
+                for _ in range(2):                         # in turns, so that drift hits both alike
+                    for on in (False, True):
+                        oz.oz2_ctx_set_option(None, b.OZ2_OPT_CUT_LAUNCHES, on)
+                        for _ in range(args.warmup):
+                            call()
+                        torch.cuda.synchronize()
+                        t0 = time.perf_counter()
+                        for _ in range(args.steps):
+                            call()
+                        torch.cuda.synchronize()
+                        ms[on].append(1e3 * (time.perf_counter() - t0) / args.steps)
+                        launches[on] = oz.oz2_last_gemm_launches()
+                        if on not in sums:
+                            sums[on] = dC.clone()
+                same = bool(torch.equal(sums[False], sums[True]))
+            finally:
+                oz.oz2_ctx_set_option(None, b.OZ2_OPT_CUT_LAUNCHES, True)
+            rec = {"m": m, "n": n, "k": k, "num_moduli": N, "dtype": "f64" if is_double else "f32",
+                   "mode": "accurate" if accurate else "fast", "one_launch_ms": min(ms[False]),
+                   "cut_launches_ms": min(ms[True]), "launches": [launches[False], launches[True]],
+                   "same_bits": same}
+            log(json.dumps(rec))
+            f.write(json.dumps(rec) + "\n")
+            del dA, dB, dC, sums
+    print(json.dumps({"sweep": "launches", "file": path}), flush=True)
+    oz.oz2_release()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -564,7 +617,7 @@ def main() -> int:
                     help="int8_gemm: time only the batched INT8 GEMM on random residues; "
                          "copy: a plain 4 GiB device copy (calibrates the profiler's HBM byte "
                          "counters); both print a reduced JSON line")
-    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general", "small", "accuracy", "rank_k", "overlap"], default=None,
+    ap.add_argument("--sweep", choices=sorted(SWEEPS) + ["general", "small", "accuracy", "rank_k", "overlap", "launches"], default=None,
                     help="time a whole configuration of the benchmark set over its moduli counts; "
                          "one JSON line per case goes to --out")
     ap.add_argument("--out", default=None, help="file for --sweep (default: sweep_<name>.jsonl)")
@@ -601,6 +654,8 @@ def main() -> int:
         return sweep_rank_k(oz, torch, args)
     if args.sweep == "overlap":
         return sweep_overlap(oz, torch, args)
+    if args.sweep == "launches":
+        return sweep_launches(oz, torch, args)
     if args.sweep:
         return sweep(oz, torch, args.sweep, args)
     if args.stage == "int8_gemm":

@@ -189,10 +189,13 @@ oz2_status oz2_sgemm_colmajor(oz2_op opA, oz2_op opB, int accurate, int64_t m, i
  *   OZ2_OPT_OVERLAP           see oz2_set_overlap            (default off)
  *   OZ2_OPT_SMALL_CONVERSION  see oz2_set_small_conversion   (default on)
  *   OZ2_OPT_PROFILING         see oz2_set_profiling          (default off)
+ *   OZ2_OPT_CUT_LAUNCHES      the INT8 GEMMs of a large product run as several launches (see
+ *                             oz2_last_gemm_launches); off = one launch per panel and K range of
+ *                             2^17, for comparison.  Bit-identical.  (default on)
  */
 typedef struct oz2_context oz2_context;
 typedef enum { OZ2_OPT_INT32_PRODUCTS = 0, OZ2_OPT_OVERLAP = 1, OZ2_OPT_SMALL_CONVERSION = 2,
-               OZ2_OPT_PROFILING = 3 } oz2_option;
+               OZ2_OPT_PROFILING = 3, OZ2_OPT_CUT_LAUNCHES = 4 } oz2_option;
 
 oz2_status oz2_create(oz2_context **out);
 oz2_status oz2_destroy(oz2_context *ctx);

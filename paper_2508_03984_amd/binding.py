@@ -31,7 +31,7 @@ EXPORTS = [
     "oz2_ctx_last_stage_times_ms", "oz2_dgemm_noalloc",
 ]
 
-OZ2_OPT_INT32_PRODUCTS, OZ2_OPT_OVERLAP, OZ2_OPT_SMALL_CONVERSION, OZ2_OPT_PROFILING = range(4)
+OZ2_OPT_INT32_PRODUCTS, OZ2_OPT_OVERLAP, OZ2_OPT_SMALL_CONVERSION, OZ2_OPT_PROFILING, OZ2_OPT_CUT_LAUNCHES = range(5)
 
 OZ2_OP_N, OZ2_OP_T = 0, 1
 

@@ -36,6 +36,7 @@ struct oz2_context {
     bool int32_products = false;           // diagnostic form: keep C'_s as int32
     bool overlap = false;                  // conversion of later panels beside the GEMMs (run_overlapped)
     bool small_conversion = true;          // fused conversion launches for small problems (oz2_small.hip)
+    bool cut_launches = true;              // GEMM launches of a large product cut into parts (launch_panels)
     hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     bool ev_recorded = false;
     // overlapped form: a second stream, ordering events, and with profiling one pair of timing
@@ -170,8 +171,8 @@ oz2_status run_products(Ctx &g, const Layout &L, const Panels &P, const int8_t *
     for (int64_t row0 = 0; row0 < L.Mp; row0 += P.pr)
         for (int64_t col0 = 0; col0 < L.Np; col0 += P.pc) {
             const int64_t rows = std::min(P.pr, L.Mp - row0), cols = std::min(P.pc, L.Np - col0);
-            const Panels Q = launch_panels(rows, cols, L.Kp);
-            const int64_t k_len = L.prod_u8 ? launch_k_len(L.Kp, L.N, Q) : std::min<int64_t>(L.Kp, OZ2_MAX_K);
+            const Panels Q = g.cut_launches ? launch_panels(rows, cols, L.Kp) : Panels{rows, cols, 1};
+            const int64_t k_len = g.cut_launches && L.prod_u8 ? launch_k_len(L.Kp, L.N, Q) : std::min<int64_t>(L.Kp, OZ2_MAX_K);
             for (int64_t r1 = 0; r1 < rows; r1 += Q.pr)
                 for (int64_t c1 = 0; c1 < cols; c1 += Q.pc) {
                     const GemmPanel pn{row0 + r1, std::min(Q.pr, rows - r1), col0 + c1, std::min(Q.pc, cols - c1), cols,
@@ -483,6 +484,7 @@ oz2_status oz2_ctx_set_option(oz2_context *ctx, oz2_option option, int value) {
     case OZ2_OPT_INT32_PRODUCTS: g.int32_products = on; break;
     case OZ2_OPT_OVERLAP: g.overlap = on; break;
     case OZ2_OPT_SMALL_CONVERSION: g.small_conversion = on; break;
+    case OZ2_OPT_CUT_LAUNCHES: g.cut_launches = on; break;
     case OZ2_OPT_PROFILING: g.profiling = on; if (!on) g.ev_recorded = false; break;
     default: return OZ2_INVALID_ARG;
     }

@@ -495,6 +495,19 @@ def test_gemm_launches_cut_in_place(oz, oracle):
     assert oz.oz2_last_panels() == (4608, 8704, 1) and oz.oz2_last_gemm_launches() == 4
     sampled_parity(oz, oracle, 4500, 8600, 520, 14, 0.5, np.float64, seed=32, n_rows=4, n_entries=1000)
     assert oz.oz2_last_panels() == (4608, 8704, 1) and oz.oz2_last_gemm_launches() == 1
+    # the option that switches the cut off: one launch, the same bits
+    import torch
+    from paper_2508_03984_amd import binding as b
+    A, B, dA, dB = device_inputs(4500, 8600, 8200, 1.0, 31, np.float64)
+    cut = oz.matmul(dA, dB, 6)
+    assert oz.oz2_last_gemm_launches() == 4
+    oz.oz2_ctx_set_option(None, b.OZ2_OPT_CUT_LAUNCHES, False)
+    try:
+        whole = oz.matmul(dA, dB, 6)
+        assert oz.oz2_last_gemm_launches() == 1
+    finally:
+        oz.oz2_ctx_set_option(None, b.OZ2_OPT_CUT_LAUNCHES, True)
+    assert torch.equal(cut, whole)
     oz.oz2_release()
 
 
