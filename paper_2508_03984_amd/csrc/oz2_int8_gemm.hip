@@ -98,6 +98,21 @@ __device__ inline void map_tile(const TileMap &tm, int id, int &s, int &tr, int 
 //                (k_int8_gemm only.)
 enum { kOutI32 = 0, kOutI32Fold = 1, kOutU8 = 2, kOutU8Fold = 3, kOutMax = 4 };
 
+// (a + b) mod p on each of the four bytes of a and b, all of them below p <= 256: the even and
+// the odd bytes as two pairs of 16-bit sums (at most 510), each reduced by one packed unsigned
+// minimum (s - p wraps to a large number when s < p).
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t add_mod_bytes(uint32_t a, uint32_t b, int p) {
+    const us2 pp = {(unsigned short)p, (unsigned short)p};
+    auto reduce = [&](uint32_t x) {
+        const us2 v = __builtin_bit_cast(us2, x);
+        return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(v, (us2)(v - pp)));
+    };
+    const uint32_t even = reduce((a & 0x00ff00ffu) + (b & 0x00ff00ffu));
+    const uint32_t odd = reduce(((a >> 8) & 0x00ff00ffu) + ((b >> 8) & 0x00ff00ffu));
+    return even | (odd << 8);
+}
+
 struct GemmMods {                       // moduli of the slices and their mulhi multipliers
     int32_t p[kMaxModuli];
     int32_t pinv_prime[kMaxModuli];
@@ -316,7 +331,7 @@ struct GemmCore {
                                           int64_t c_ld, int64_t c_plane, const GemmMods &mods) const {
         const int p = mods.p[s], pv = mods.pinv_prime[s];
         const int64_t c_off = (int64_t)s * c_plane + bm * c_ld + bn;   // C: [slice][row][column]
-        if (OUT == kOutU8) {
+        if (OUT == kOutU8 || OUT == kOutU8Fold) {
             // Four residues per register quad pack into one dword; the two half-wavefronts hold
             // alternating dwords of a row (columns 8g + 4*(l/32) ...), so they swap two dwords
             // each (lanes 0-31 end up with columns 0-15 of the block row, lanes 32-63 with 16-31)
@@ -341,10 +356,16 @@ struct GemmCore {
                     // - 32 | d2) in (a, b): the row's dwords in column order, no selects needed.
                     const auto s0 = __builtin_amdgcn_permlane32_swap(d[0], d[2], false, false);
                     const auto s1 = __builtin_amdgcn_permlane32_swap(d[1], d[3], false, false);
-                    const v4i q = v4i{(int)s0[0], (int)s0[1], (int)s1[0], (int)s1[1]};
+                    v4i q = v4i{(int)s0[0], (int)s0[1], (int)s1[0], (int)s1[1]};
                     const int row = wm * 32 * TM + i * 32 + lrow;
                     const int col = wn * 32 * TN + j * 32 + 16 * lhalf;
-                    *reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * c_ld + col) = q;
+                    v4i *dst = reinterpret_cast<v4i *>(static_cast<uint8_t *>(C) + c_off + (int64_t)row * c_ld + col);
+                    if (OUT == kOutU8Fold) {               // a further K range: (old + new) mod p_s, byte by byte
+                        const v4i old = *dst;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) q[w] = (int)add_mod_bytes((uint32_t)q[w], (uint32_t)old[w], p);
+                    }
+                    *dst = q;
                 }
             return;
         }
@@ -360,26 +381,13 @@ struct GemmCore {
                     int v[4];
 #pragma unroll
                     for (int c = 0; c < 4; ++c) v[c] = acc[i][j][4 * g + c];
-                    if (OUT == kOutI32 || OUT == kOutI32Fold) {
-                        v4i *dst = reinterpret_cast<v4i *>(static_cast<int32_t *>(C) + at);
-                        if (OUT == kOutI32Fold) {
-                            const v4i old = *dst;
+                    v4i *dst = reinterpret_cast<v4i *>(static_cast<int32_t *>(C) + at);
+                    if (OUT == kOutI32Fold) {
+                        const v4i old = *dst;
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) v[c] = mod_small(old[c], p, pv) + mod_small(v[c], p, pv);
-                        }
-                        *dst = v4i{v[0], v[1], v[2], v[3]};
-                    } else {                                   // kOutU8Fold
-                        uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<uint8_t *>(C) + at);
-                        uint32_t packed = 0;
-                        const uint32_t old = *dst;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            int u = mod_small(v[c], p, pv) + (int)((old >> (8 * c)) & 0xffu);
-                            u -= (u >= p) ? p : 0;
-                            packed |= (uint32_t)u << (8 * c);
-                        }
-                        *dst = packed;
+                        for (int c = 0; c < 4; ++c) v[c] = mod_small(old[c], p, pv) + mod_small(v[c], p, pv);
                     }
+                    *dst = v4i{v[0], v[1], v[2], v[3]};
                 }
     }
 
