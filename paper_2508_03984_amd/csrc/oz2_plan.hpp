@@ -165,7 +165,10 @@ inline Panels launch_panels(int64_t rows, int64_t cols, int64_t Kp) {
 // ranges of 2^17 that exactness requires (Section 4.3).  Returns the length of a K range: Kp
 // itself when one launch is short enough, never more than OZ2_MAX_K.  Measured: 8192 x 8192 x
 // 65536, N = 18: 74.3 -> 72.3 ms; 4096 x 4096 x 131072, N = 16: 38.4 -> 36.6 ms.
-constexpr double kLaunchMs = 7.0, kRoundNsPerK = 13.4;
+#ifndef OZ2_LAUNCH_MS
+#define OZ2_LAUNCH_MS 7.0
+#endif
+constexpr double kLaunchMs = OZ2_LAUNCH_MS, kRoundNsPerK = 13.4;
 constexpr int64_t kLaunchKStep = 8192;
 
 inline int64_t launch_k_len(int64_t Kp, int N, const Panels &Q) {
